@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the GPT stage forward+backward on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME|INDEX]
+
+One "step" = the whole hot path over one batch of the workload: every
+micro-batch's forward and backward (for the decoupled workload: all forwards on
+a forward stream, then all backwards on a backward stream).  Inputs are seeded
+synthetic tensors already resident in HBM.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3    # MI355X fp32 vector
+DEFAULT_WORKLOAD = "decoupled_bf16"
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--schedule", choices=["auto", "coupled", "decoupled"], default="auto")
+    return ap.parse_args()
+
+
+def pick_workload(arg):
+    from paper_2507_19845_amd import synth
+    if arg.isdigit():
+        return synth.WORKLOADS[int(arg)]
+    for w in synth.WORKLOADS:
+        if w.name == arg:
+            return w
+    raise SystemExit(f"unknown workload {arg!r}; known: {[w.name for w in synth.WORKLOADS]}")
+
+
+def cpu_baseline(shape):
+    """Time the oracle, as it stands, on a bounded sample of the workload:
+    one layer, one micro-batch, the first min(S, 2048) tokens of each sequence."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import gpt_stage_oracle as orc
+    from paper_2507_19845_amd import binding as B
+    from paper_2507_19845_amd import synth
+    s = shape.with_(n_layers=1, seq=min(shape.seq, 2048), n_microbatches=1)
+    params = [{k: v.astype(np.float64) for k, v in synth.make_layer_params(s, 0, 0).items()}]
+    x, dy = synth.make_x(s, 0).astype(np.float64), synth.make_dy(s, 0).astype(np.float64)
+    t0 = time.perf_counter()
+    orc.stage_fwd_bwd(x, dy, params, s.n_heads, s.head_dim, s.ln_eps, s.gelu)
+    dt = time.perf_counter() - t0
+    flops = B.gpt_stage_model_flops(B.make_cfg(s), True)
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "seconds": dt,
+            "sample": f"1 layer, 1 micro-batch, first {s.seq} tokens x batch {s.batch} of {shape.name} "
+                      f"(fp64 numpy oracle, {flops / 1e12:.3f} model TFLOP causal-aware)"}
+
+
+def gemm_roofline(shape, stream):
+    """Average duration of the dominant kernel (the matrix-product kernel) over the
+    matrix products of one layer's forward+backward, timed with HIP events on the
+    stream they are launched on."""
+    import torch
+    from paper_2507_19845_amd import binding as B
+    dt = B.GPTS_BF16 if shape.dtype == "bf16" else B.GPTS_FP32
+    td = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    T, H, P, F = shape.tokens, shape.hidden, shape.attn_width, shape.ffn
+    layers = [(3 * P, H), (H, P), (F, H), (H, F)]   # (out, in) of the four linears
+    calls = []
+    for out_f, in_f in layers:
+        calls.append((0, T, out_f, in_f))    # forward  C[T,out] = A[T,in] W[out,in]^T
+        calls.append((1, T, in_f, out_f))    # dgrad    dA[T,in] = dC[T,out] W[out,in]
+        calls.append((2, out_f, in_f, T))    # wgrad    dW[out,in] += dC[T,out]^T A[T,in]
+    total_ms, total_flops, n = 0.0, 0.0, 0
+    with torch.cuda.stream(stream):
+        for form, M, N, K in calls:
+            if form == 0:
+                A, Bm = torch.randn(M, K, device="cuda").to(td), (torch.randn(N, K, device="cuda") * 0.02).to(td)
+                Cd = torch.empty(M, N, device="cuda", dtype=td)
+            elif form == 1:
+                A, Bm = torch.randn(M, K, device="cuda").to(td), (torch.randn(K, N, device="cuda") * 0.02).to(td)
+                Cd = torch.empty(M, N, device="cuda", dtype=td)
+            else:
+                A, Bm = torch.randn(K, M, device="cuda").to(td), torch.randn(K, N, device="cuda").to(td)
+                Cd = torch.zeros(M, N, device="cuda", dtype=torch.float32)
+            B.gpt_stage_op_gemm(dt, form, M, N, K, A, Bm, Cd, stream=stream)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 3
+            e0.record(stream)
+            for _ in range(reps):
+                B.gpt_stage_op_gemm(dt, form, M, N, K, A, Bm, Cd, stream=stream)
+            e1.record(stream)
+            e1.synchronize()
+            total_ms += e0.elapsed_time(e1) / reps
+            total_flops += 2.0 * M * N * K
+            n += 1
+            del A, Bm, Cd
+    achieved = total_flops / (total_ms * 1e-3) / 1e12
+    peak = PEAK_BF16_TFLOPS if shape.dtype == "bf16" else PEAK_FP32_TFLOPS
+    return {"bound": "mfma" if shape.dtype == "bf16" else "alu", "achieved": achieved, "peak": peak,
+            "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+            "kernel": "stage matrix products (fwd NT, dgrad NN, wgrad TN of the 4 linears)",
+            "launches": n, "avg_launch_ms": total_ms / n, "flops_per_launch": total_flops / n}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: the stage has no collectives or sharding; run with --gpus 1")
+    import torch
+    from paper_2507_19845_amd import binding as B
+    from paper_2507_19845_amd import harness, synth
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    B.lib()
+    shape = pick_workload(args.workload)
+    n_mb = shape.n_microbatches
+    decoupled = (n_mb > 1) if args.schedule == "auto" else (args.schedule == "decoupled")
+    bufs = B.StageBuffers(shape, n_stash=n_mb if decoupled else 1)
+    t0 = time.perf_counter()
+    for l in range(shape.n_layers):   # one layer at a time keeps host memory small
+        p = synth.make_layer_params(shape, l, 0)
+        for tid, name in enumerate(synth.TENSOR_NAMES):
+            off, n = B.gpt_stage_param_offset(bufs.cfg, l, tid)
+            bufs.weights[off:off + n].copy_(B.to_device(p[name].reshape(-1), shape.dtype))
+    xs = [B.to_device(synth.make_x(shape, 0, m), shape.dtype) for m in range(n_mb)]
+    dys = [B.to_device(synth.make_dy(shape, 0, m), shape.dtype) for m in range(n_mb)]
+    ys = [bufs.act() for _ in range(n_mb)]
+    dxs = [bufs.act() for _ in range(n_mb)]
+    gen_s = time.perf_counter() - t0
+    runner = harness.StageRunner(bufs)
+
+    def step():
+        if decoupled:
+            runner.decoupled(xs, dys, ys, dxs)
+        else:
+            runner.coupled(xs, dys, ys, dxs)
+
+    for _ in range(args.warmup):
+        bufs.dparams.zero_()
+        step()
+    torch.cuda.synchronize()
+    bufs.dparams.zero_()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = wall * 1e3 / args.steps
+
+    flops = B.gpt_stage_model_flops(bufs.cfg, True) * n_mb
+    flops_dense = B.gpt_stage_model_flops(bufs.cfg, False) * n_mb
+    tflops = flops / (ms * 1e-3) / 1e12
+    peak = PEAK_BF16_TFLOPS if shape.dtype == "bf16" else PEAK_FP32_TFLOPS
+    roof = gemm_roofline(shape, torch.cuda.current_stream())
+    out = {
+        "metric": "model TFLOP/s for one stage fwd+bwd on 1 MI355X",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
+        "pct_of_peak": 100.0 * tflops / peak, "peak_tflops": peak,
+        "value_dense_attention_convention": flops_dense / (ms * 1e-3) / 1e12,
+        "model_tflop_per_step": flops / 1e12,
+        "config": {"workload": shape.name, "n_layers": shape.n_layers, "hidden": shape.hidden,
+                   "n_heads": shape.n_heads, "head_dim": shape.head_dim, "ffn": shape.ffn,
+                   "seq": shape.seq, "micro_batch": shape.batch, "n_microbatches": n_mb,
+                   "schedule": "decoupled: all fwd on stream F, then all bwd on stream B" if decoupled
+                               else "coupled fwd+bwd per micro-batch", "flop_count": "causal-aware",
+                   "input_gen_seconds": gen_s},
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,197 @@
+/*
+ * gpt_stage.h -- C ABI of libgptstage: forward and backward pass of one GPT
+ * pipeline stage (L pre-LayerNorm decoder layers) on one MI355X (gfx950).
+ *
+ * What the calls compute.  The paper's schedulers treat a pipeline stage as two
+ * separable phases: a "forward phase" and a "backward phase (gradient
+ * computation)" (MegaFBD, section 4.1), and one unit of work is "one model
+ * chunk applied to one micro-batch" (MegaDPP, section 5.2, parallel scheduler).
+ * The layer mathematics is that of the GPT/Megatron-LM decoder layer the paper
+ * builds on (section 2.2-2.3).  Per layer, for x in R^{T x H}, T = batch*seq:
+ *     a   = LayerNorm(x; ln1_g, ln1_b)
+ *     qkv = a W_qkv^T + b_qkv          (columns: [Q heads | K heads | V heads])
+ *     c   = causal softmax attention per head, scale 1/sqrt(head_dim)
+ *     x1  = x + c W_o^T + b_o
+ *     a2  = LayerNorm(x1; ln2_g, ln2_b)
+ *     u   = a2 W_fc1^T + b_fc1 ;  g = gelu(u)
+ *     y   = x1 + g W_fc2^T + b_fc2
+ * The backward phase returns dx = d<y,dy>/dx and ADDS d<y,dy>/dparam to the
+ * caller's gradient buffer (accumulation over micro-batches, as the
+ * breadth-first traversal of section 5.2 needs).
+ *
+ * General rules (all entry points)
+ *  - Every pointer named "device" is GPU memory owned by the caller; the library
+ *    allocates no device memory, keeps no mutable global state and frees nothing.
+ *  - Every call only enqueues kernels on `stream` (a hipStream_t passed as
+ *    void*; NULL = the default stream) and returns; it never synchronises.
+ *  - Device pointers must be 16-byte aligned.
+ *  - Return value: GPTS_OK (0) or a negative gpts_status; nothing is launched
+ *    when validation fails.  No exceptions cross this boundary.
+ *  - Results are run-to-run bitwise deterministic (no floating-point atomics).
+ */
+#ifndef GPT_STAGE_H_
+#define GPT_STAGE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GPTS_OK = 0,
+  GPTS_EINVAL = -1, /* null or misaligned pointer, bad enum value            */
+  GPTS_ESHAPE = -2, /* shape outside what the kernels support (see validate) */
+  GPTS_EHIP = -3    /* a HIP launch failed; text via gpt_stage_strerror      */
+} gpts_status;
+
+enum { GPTS_FP32 = 0, GPTS_BF16 = 1 };     /* cfg.dtype */
+enum { GPTS_GELU_TANH = 0, GPTS_GELU_ERF = 1 }; /* cfg.gelu  */
+
+/* Per-layer tensor ids, in the order they sit in the flat parameter buffer and
+ * in the flat fp32 gradient buffer.  Weights are row-major [out, in].
+ * W_QKV rows [0,P) are Q, [P,2P) K, [2P,3P) V, P = n_heads*head_dim; head n owns
+ * rows n*head_dim .. (n+1)*head_dim-1 of each block. */
+enum {
+  GPTS_LN1_G = 0, GPTS_LN1_B, GPTS_W_QKV, GPTS_B_QKV, GPTS_W_O, GPTS_B_O,
+  GPTS_LN2_G, GPTS_LN2_B, GPTS_W_FC1, GPTS_B_FC1, GPTS_W_FC2, GPTS_B_FC2,
+  GPTS_N_TENSORS
+};
+
+typedef struct {
+  int32_t n_layers;  /* L >= 1                                               */
+  int32_t hidden;    /* H                                                    */
+  int32_t n_heads;   /* a : heads held by this GPU (P = a*head_dim may != H) */
+  int32_t head_dim;  /* d in {32, 64, 128}                                   */
+  int32_t ffn;       /* F                                                    */
+  int32_t seq;       /* S                                                    */
+  int32_t batch;     /* B : micro-batch size; tokens T = B*S                 */
+  int32_t dtype;     /* GPTS_FP32: every tensor fp32.  GPTS_BF16: activations,
+                        weights, x, y, dy, dx bf16; statistics, accumulators
+                        and parameter gradients fp32.                        */
+  int32_t gelu;      /* GPTS_GELU_TANH or GPTS_GELU_ERF                      */
+  float   ln_eps;    /* LayerNorm epsilon (inside the square root)           */
+} gpt_stage_cfg;
+
+typedef struct {
+  gpt_stage_cfg cfg;
+  const void* weights;   /* device; gpt_stage_param_bytes(); layout from
+                            gpt_stage_param_offset(); read-only              */
+  void*       workspace; /* device scratch of gpt_stage_workspace_bytes();
+                            contents undefined between calls; two calls that
+                            may overlap in time must not share it            */
+} gpt_stage_params;
+
+/* ---- host-side queries (no GPU needed) ---------------------------------- */
+
+/* GPTS_OK if the kernels support cfg: L,B,S >= 1; head_dim in {32,64,128};
+ * H, P, F multiples of 8; H <= 16384; dtype/gelu valid.  bf16 additionally
+ * needs T = B*S, H, P, F multiples of 64 (MFMA tile granularity). */
+int gpt_stage_validate(const gpt_stage_cfg* cfg);
+
+size_t gpt_stage_param_count(const gpt_stage_cfg* cfg);  /* elements, all layers */
+size_t gpt_stage_param_bytes(const gpt_stage_cfg* cfg);  /* weights buffer (cfg.dtype elements) */
+size_t gpt_stage_grad_bytes(const gpt_stage_cfg* cfg);   /* dparams buffer (fp32 elements, same order) */
+size_t gpt_stage_stash_bytes(const gpt_stage_cfg* cfg);  /* ONE micro-batch's activation stash */
+size_t gpt_stage_workspace_bytes(const gpt_stage_cfg* cfg, int phase); /* 0 = forward, 1 = backward */
+
+/* Element offset and element count of tensor `tensor_id` of `layer` inside the
+ * parameter buffer (identical for the gradient buffer).  Offsets are multiples
+ * of 8 elements. */
+int gpt_stage_param_offset(const gpt_stage_cfg* cfg, int layer, int tensor_id,
+                           size_t* elem_off, size_t* n_elem);
+
+/* Model FLOPs of one forward+backward of one micro-batch: 3 x forward, forward =
+ * 2*T*(3PH + PH + 2HF) for the four linears + attention 4*B*a*d*S*(S+1)/2
+ * (causal_aware != 0) or 4*B*a*d*S*S (dense convention).  Recomputation is
+ * never counted. */
+double gpt_stage_model_flops(const gpt_stage_cfg* cfg, int causal_aware);
+
+const char* gpt_stage_strerror(int code);
+
+/* ---- the stage calls ----------------------------------------------------- */
+
+/* Forward phase (section 4.1 "forward phase"; section 5.2 one task).
+ *   x         device, [B,S,H] cfg.dtype, read-only, must not alias y
+ *   act_stash device, gpt_stage_stash_bytes(); written; opaque; one per
+ *             in-flight micro-batch; stays valid until its backward has run
+ *   y         device, [B,S,H] cfg.dtype, written
+ * Needs p->workspace of workspace_bytes(cfg, 0) (may be NULL when that is 0). */
+int gpt_stage_fwd(const gpt_stage_params* p, const void* x, void* act_stash,
+                  void* y, void* stream);
+
+/* Backward phase (section 4.1 "gradient computation").
+ *   act_stash device, as written by the forward of the same micro-batch; not modified
+ *   dy        device, [B,S,H] cfg.dtype, read-only
+ *   dx        device, [B,S,H] cfg.dtype, written; may alias dy
+ *   dparams   device, fp32, gpt_stage_grad_bytes(); ACCUMULATED into (+=): the
+ *             caller zeroes it before the first micro-batch
+ * Needs p->workspace of workspace_bytes(cfg, 1).  Concurrent backward calls
+ * must not share dparams or workspace. */
+int gpt_stage_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy,
+                  void* dx, void* dparams, void* stream);
+
+/* Decoupled entry points (MegaFBD section 4.1 "instance-level decoupled
+ * scheduling": the two phases run as separate instances and meet only at the
+ * stash).  Same mathematics as the two calls above plus event plumbing so a
+ * forward stream and a backward stream never need a host synchronisation:
+ *   done_event  hipEvent_t or NULL; recorded on `stream` after the last kernel
+ *   wait_event  hipEvent_t or NULL; `stream` waits on it before the first kernel */
+int gpt_stage_fwd_only(const gpt_stage_params* p, const void* x, void* act_stash,
+                       void* y, void* stream, void* done_event);
+int gpt_stage_bwd_only(const gpt_stage_params* p, const void* act_stash, const void* dy,
+                       void* dx, void* dparams, void* stream, void* wait_event);
+
+/* Coupled convenience: forward then backward of one micro-batch on one stream.
+ * p->workspace must hold max(workspace_bytes(cfg,0), workspace_bytes(cfg,1)). */
+int gpt_stage_fwd_bwd(const gpt_stage_params* p, const void* x, const void* dy,
+                      void* act_stash, void* y, void* dx, void* dparams, void* stream);
+
+/* ---- single operations (the kernels the stage is built from) -------------
+ * Exposed so each kernel can be checked and timed on its own.  `dtype` is
+ * GPTS_FP32 or GPTS_BF16 as in cfg; all pointers device. */
+
+/* out[t,:] = (x[t,:]-mu_t) * rstd_t * gamma + beta ; mean/rstd fp32 [T] written. */
+int gpt_stage_op_layernorm_fwd(int dtype, int T, int H, float eps, const void* x,
+                               const void* gamma, const void* beta, void* out,
+                               float* mean, float* rstd, void* stream);
+
+/* dx = dres + LN-backward(dout) ; dgamma += sum_t dout*xhat ; dbeta += sum_t dout.
+ * dres may be NULL (treated as 0).  partial: fp32 scratch of
+ * gpt_stage_op_layernorm_bwd_scratch_bytes(T,H). */
+size_t gpt_stage_op_layernorm_bwd_scratch_bytes(int T, int H);
+int gpt_stage_op_layernorm_bwd(int dtype, int T, int H, const void* dout, const void* x,
+                               const float* mean, const float* rstd, const void* gamma,
+                               const void* dres, void* dx, float* dgamma, float* dbeta,
+                               float* partial, void* stream);
+
+/* Matrix products of the three forms the stage uses; fp32 accumulation.
+ *   form 0 (NT, forward):  C[M,N]  = A[M,K] B[N,K]^T (+ bias[N]) (+ residual[M,N])
+ *                          gelu != 0: also writes C2 = gelu(C) (C keeps the pre-activation)
+ *   form 1 (NN, dgrad):    C[M,N]  = A[M,K] B[K,N] ; dgelu_u != NULL: C *= gelu'(dgelu_u[M,N])
+ *   form 2 (TN, wgrad):    Cf[M,N] += A[K,M]^T B[K,N]   (Cf fp32, accumulated into)
+ * A, B, C, C2, residual, dgelu_u are `dtype`; bias is `dtype`; gelu_kind as cfg.gelu. */
+int gpt_stage_op_gemm(int dtype, int form, int M, int N, int K, const void* A, const void* B,
+                      void* C, const void* bias, const void* residual, void* C2,
+                      const void* dgelu_u, int gelu_kind, void* stream);
+
+/* colsum[n] += sum_m A[m,n]   (bias gradients); A `dtype`, colsum fp32;
+ * partial: fp32 scratch of gpt_stage_op_colsum_scratch_bytes(M,N). */
+size_t gpt_stage_op_colsum_scratch_bytes(int M, int N);
+int gpt_stage_op_colsum(int dtype, int M, int N, const void* A, float* colsum,
+                        float* partial, void* stream);
+
+/* Causal attention.  qkv [B,S,3P] ([Q|K|V], P = n_heads*head_dim); out [B,S,P];
+ * lse fp32 [B,n_heads,S] = log sum_j exp(s_ij) of each causal row. */
+int gpt_stage_op_attention_fwd(int dtype, int B, int S, int n_heads, int head_dim,
+                               const void* qkv, void* out, float* lse, void* stream);
+/* dqkv [B,S,3P] written; delta: fp32 scratch [B,n_heads,S]. */
+int gpt_stage_op_attention_bwd(int dtype, int B, int S, int n_heads, int head_dim,
+                               const void* qkv, const void* out, const float* lse,
+                               const void* dout, void* dqkv, float* delta, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GPT_STAGE_H_ */

@@ -1,0 +1,305 @@
+"""ctypes binding of libgptstage.so (declared in include/gpt_stage.h).
+
+Argument marshalling only: every function here has the name of the C entry
+point it calls, takes torch tensors (used purely as device memory) or raw
+integers, and forwards pointers.  No arithmetic of the stage runs in Python.
+If the shared library has not been built this module raises at load time;
+there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional
+
+import numpy as np
+import torch
+
+from . import synth
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgptstage.so")
+
+GPTS_FP32, GPTS_BF16 = 0, 1
+GPTS_GELU_TANH, GPTS_GELU_ERF = 0, 1
+GPTS_OK, GPTS_EINVAL, GPTS_ESHAPE, GPTS_EHIP = 0, -1, -2, -3
+N_TENSORS = 12
+
+EXPORTS = (
+    "gpt_stage_validate", "gpt_stage_param_count", "gpt_stage_param_bytes", "gpt_stage_grad_bytes",
+    "gpt_stage_stash_bytes", "gpt_stage_workspace_bytes", "gpt_stage_param_offset",
+    "gpt_stage_model_flops", "gpt_stage_strerror",
+    "gpt_stage_fwd", "gpt_stage_bwd", "gpt_stage_fwd_only", "gpt_stage_bwd_only", "gpt_stage_fwd_bwd",
+    "gpt_stage_op_layernorm_fwd", "gpt_stage_op_layernorm_bwd_scratch_bytes",
+    "gpt_stage_op_layernorm_bwd", "gpt_stage_op_gemm", "gpt_stage_op_colsum_scratch_bytes",
+    "gpt_stage_op_colsum", "gpt_stage_op_attention_fwd", "gpt_stage_op_attention_bwd",
+)
+
+
+class gpt_stage_cfg(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("ffn", C.c_int32), ("seq", C.c_int32),
+                ("batch", C.c_int32), ("dtype", C.c_int32), ("gelu", C.c_int32),
+                ("ln_eps", C.c_float)]
+
+
+class gpt_stage_params(C.Structure):
+    _fields_ = [("cfg", gpt_stage_cfg), ("weights", C.c_void_p), ("workspace", C.c_void_p)]
+
+
+class GptStageError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libgptstage error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load the shared library (once).  Fails loudly when it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: build it with `python -m paper_2507_19845_amd.build`")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, sz, f32 = C.c_void_p, C.c_int, C.c_size_t, C.c_float
+    cfgp, parp = C.POINTER(gpt_stage_cfg), C.POINTER(gpt_stage_params)
+    sig = {
+        "gpt_stage_validate": (i32, [cfgp]),
+        "gpt_stage_param_count": (sz, [cfgp]),
+        "gpt_stage_param_bytes": (sz, [cfgp]),
+        "gpt_stage_grad_bytes": (sz, [cfgp]),
+        "gpt_stage_stash_bytes": (sz, [cfgp]),
+        "gpt_stage_workspace_bytes": (sz, [cfgp, i32]),
+        "gpt_stage_param_offset": (i32, [cfgp, i32, i32, C.POINTER(sz), C.POINTER(sz)]),
+        "gpt_stage_model_flops": (C.c_double, [cfgp, i32]),
+        "gpt_stage_strerror": (C.c_char_p, [i32]),
+        "gpt_stage_fwd": (i32, [parp, vp, vp, vp, vp]),
+        "gpt_stage_bwd": (i32, [parp, vp, vp, vp, vp, vp]),
+        "gpt_stage_fwd_only": (i32, [parp, vp, vp, vp, vp, vp]),
+        "gpt_stage_bwd_only": (i32, [parp, vp, vp, vp, vp, vp, vp]),
+        "gpt_stage_fwd_bwd": (i32, [parp, vp, vp, vp, vp, vp, vp, vp]),
+        "gpt_stage_op_layernorm_fwd": (i32, [i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp]),
+        "gpt_stage_op_layernorm_bwd_scratch_bytes": (sz, [i32, i32]),
+        "gpt_stage_op_layernorm_bwd": (i32, [i32, i32, i32] + [vp] * 11),
+        "gpt_stage_op_gemm": (i32, [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp]),
+        "gpt_stage_op_colsum_scratch_bytes": (sz, [i32, i32]),
+        "gpt_stage_op_colsum": (i32, [i32, i32, i32, vp, vp, vp, vp]),
+        "gpt_stage_op_attention_fwd": (i32, [i32, i32, i32, i32, i32, vp, vp, vp, vp]),
+        "gpt_stage_op_attention_bwd": (i32, [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = L
+    return L
+
+
+def _check(rc: int) -> None:
+    if rc != GPTS_OK:
+        raise GptStageError(rc, lib().gpt_stage_strerror(rc).decode())
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_contiguous()
+    return t.data_ptr()
+
+
+def _stream(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+def make_cfg(s: synth.StageShape) -> gpt_stage_cfg:
+    return gpt_stage_cfg(n_layers=s.n_layers, hidden=s.hidden, n_heads=s.n_heads, head_dim=s.head_dim,
+                         ffn=s.ffn, seq=s.seq, batch=s.batch,
+                         dtype=GPTS_BF16 if s.dtype == "bf16" else GPTS_FP32,
+                         gelu=GPTS_GELU_ERF if s.gelu == "erf" else GPTS_GELU_TANH,
+                         ln_eps=s.ln_eps)
+
+
+# ---- host-side queries --------------------------------------------------------
+def gpt_stage_validate(cfg: gpt_stage_cfg) -> int:
+    return lib().gpt_stage_validate(C.byref(cfg))
+
+
+def gpt_stage_param_count(cfg) -> int:
+    return lib().gpt_stage_param_count(C.byref(cfg))
+
+
+def gpt_stage_param_bytes(cfg) -> int:
+    return lib().gpt_stage_param_bytes(C.byref(cfg))
+
+
+def gpt_stage_grad_bytes(cfg) -> int:
+    return lib().gpt_stage_grad_bytes(C.byref(cfg))
+
+
+def gpt_stage_stash_bytes(cfg) -> int:
+    return lib().gpt_stage_stash_bytes(C.byref(cfg))
+
+
+def gpt_stage_workspace_bytes(cfg, phase: int) -> int:
+    return lib().gpt_stage_workspace_bytes(C.byref(cfg), phase)
+
+
+def gpt_stage_param_offset(cfg, layer: int, tensor_id: int):
+    off, n = C.c_size_t(), C.c_size_t()
+    _check(lib().gpt_stage_param_offset(C.byref(cfg), layer, tensor_id, C.byref(off), C.byref(n)))
+    return off.value, n.value
+
+
+def gpt_stage_model_flops(cfg, causal_aware: bool = True) -> float:
+    return lib().gpt_stage_model_flops(C.byref(cfg), 1 if causal_aware else 0)
+
+
+def gpt_stage_strerror(code: int) -> str:
+    return lib().gpt_stage_strerror(code).decode()
+
+
+# ---- the stage calls -----------------------------------------------------------
+def _params(cfg, weights, workspace) -> gpt_stage_params:
+    return gpt_stage_params(cfg=cfg, weights=_ptr(weights), workspace=_ptr(workspace))
+
+
+def gpt_stage_fwd(cfg, weights, workspace, x, act_stash, y, stream=None) -> None:
+    p = _params(cfg, weights, workspace)
+    _check(lib().gpt_stage_fwd(C.byref(p), _ptr(x), _ptr(act_stash), _ptr(y), _stream(stream)))
+
+
+def gpt_stage_bwd(cfg, weights, workspace, act_stash, dy, dx, dparams, stream=None) -> None:
+    p = _params(cfg, weights, workspace)
+    _check(lib().gpt_stage_bwd(C.byref(p), _ptr(act_stash), _ptr(dy), _ptr(dx), _ptr(dparams),
+                               _stream(stream)))
+
+
+def gpt_stage_fwd_only(cfg, weights, workspace, x, act_stash, y, stream=None,
+                       done_event: Optional[torch.cuda.Event] = None) -> None:
+    p = _params(cfg, weights, workspace)
+    ev = done_event.cuda_event if done_event is not None else None
+    _check(lib().gpt_stage_fwd_only(C.byref(p), _ptr(x), _ptr(act_stash), _ptr(y), _stream(stream), ev))
+
+
+def gpt_stage_bwd_only(cfg, weights, workspace, act_stash, dy, dx, dparams, stream=None,
+                       wait_event: Optional[torch.cuda.Event] = None) -> None:
+    p = _params(cfg, weights, workspace)
+    ev = wait_event.cuda_event if wait_event is not None else None
+    _check(lib().gpt_stage_bwd_only(C.byref(p), _ptr(act_stash), _ptr(dy), _ptr(dx), _ptr(dparams),
+                                    _stream(stream), ev))
+
+
+def gpt_stage_fwd_bwd(cfg, weights, workspace, x, dy, act_stash, y, dx, dparams, stream=None) -> None:
+    p = _params(cfg, weights, workspace)
+    _check(lib().gpt_stage_fwd_bwd(C.byref(p), _ptr(x), _ptr(dy), _ptr(act_stash), _ptr(y), _ptr(dx),
+                                   _ptr(dparams), _stream(stream)))
+
+
+# ---- single operations ----------------------------------------------------------
+def gpt_stage_op_layernorm_fwd(dtype, T, H, eps, x, gamma, beta, out, mean, rstd, stream=None):
+    _check(lib().gpt_stage_op_layernorm_fwd(dtype, T, H, eps, _ptr(x), _ptr(gamma), _ptr(beta),
+                                            _ptr(out), _ptr(mean), _ptr(rstd), _stream(stream)))
+
+
+def gpt_stage_op_layernorm_bwd_scratch_bytes(T, H) -> int:
+    return lib().gpt_stage_op_layernorm_bwd_scratch_bytes(T, H)
+
+
+def gpt_stage_op_layernorm_bwd(dtype, T, H, dout, x, mean, rstd, gamma, dres, dx, dgamma, dbeta,
+                               partial, stream=None):
+    _check(lib().gpt_stage_op_layernorm_bwd(dtype, T, H, _ptr(dout), _ptr(x), _ptr(mean), _ptr(rstd),
+                                            _ptr(gamma), _ptr(dres), _ptr(dx), _ptr(dgamma),
+                                            _ptr(dbeta), _ptr(partial), _stream(stream)))
+
+
+def gpt_stage_op_gemm(dtype, form, M, N, K, A, B, Cout, bias=None, residual=None, C2=None,
+                      dgelu_u=None, gelu_kind=GPTS_GELU_TANH, stream=None):
+    _check(lib().gpt_stage_op_gemm(dtype, form, M, N, K, _ptr(A), _ptr(B), _ptr(Cout), _ptr(bias),
+                                   _ptr(residual), _ptr(C2), _ptr(dgelu_u), gelu_kind, _stream(stream)))
+
+
+def gpt_stage_op_colsum_scratch_bytes(M, N) -> int:
+    return lib().gpt_stage_op_colsum_scratch_bytes(M, N)
+
+
+def gpt_stage_op_colsum(dtype, M, N, A, colsum, partial, stream=None):
+    _check(lib().gpt_stage_op_colsum(dtype, M, N, _ptr(A), _ptr(colsum), _ptr(partial), _stream(stream)))
+
+
+def gpt_stage_op_attention_fwd(dtype, B, S, n_heads, head_dim, qkv, out, lse, stream=None):
+    _check(lib().gpt_stage_op_attention_fwd(dtype, B, S, n_heads, head_dim, _ptr(qkv), _ptr(out),
+                                            _ptr(lse), _stream(stream)))
+
+
+def gpt_stage_op_attention_bwd(dtype, B, S, n_heads, head_dim, qkv, out, lse, dout, dqkv, delta,
+                               stream=None):
+    _check(lib().gpt_stage_op_attention_bwd(dtype, B, S, n_heads, head_dim, _ptr(qkv), _ptr(out),
+                                            _ptr(lse), _ptr(dout), _ptr(dqkv), _ptr(delta),
+                                            _stream(stream)))
+
+
+# ---- device-memory plumbing (torch tensors as buffers; no arithmetic) --------------
+def to_device(a: np.ndarray, dtype: str, device="cuda") -> torch.Tensor:
+    """Upload an fp32 numpy array whose values are already representable in
+    `dtype` ("fp32" or "bf16") as a tensor of that storage type."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if dtype == "bf16":
+        bits = synth.bf16_bits(a).view(np.int16)
+        return torch.from_numpy(bits).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    """Download a tensor as float64 numpy (exact widening)."""
+    if t.dtype == torch.bfloat16:
+        bits = t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        return synth.bf16_bits_to_f32(bits).astype(np.float64)
+    return t.cpu().numpy().astype(np.float64)
+
+
+class StageBuffers:
+    """Owns the device buffers one stage needs and moves parameters in and
+    gradients out.  Pure allocation and copying."""
+
+    def __init__(self, shape: synth.StageShape, n_stash: int = 1, device="cuda"):
+        self.shape = shape
+        self.cfg = make_cfg(shape)
+        rc = gpt_stage_validate(self.cfg)
+        if rc != GPTS_OK:
+            raise GptStageError(rc, gpt_stage_strerror(rc))
+        self.device = device
+        self.tdtype = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+        self.n_param = gpt_stage_param_count(self.cfg)
+        self.weights = torch.zeros(self.n_param, dtype=self.tdtype, device=device)
+        self.dparams = torch.zeros(self.n_param, dtype=torch.float32, device=device)
+        self.stash = [torch.empty(gpt_stage_stash_bytes(self.cfg), dtype=torch.uint8, device=device)
+                      for _ in range(n_stash)]
+        wb = max(gpt_stage_workspace_bytes(self.cfg, 0), gpt_stage_workspace_bytes(self.cfg, 1), 256)
+        self.workspace = torch.empty(wb, dtype=torch.uint8, device=device)
+
+    def act(self) -> torch.Tensor:
+        s = self.shape
+        return torch.empty((s.batch, s.seq, s.hidden), dtype=self.tdtype, device=self.device)
+
+    def load_params(self, params: List[Dict[str, np.ndarray]]) -> None:
+        for l, p in enumerate(params):
+            for tid, name in enumerate(synth.TENSOR_NAMES):
+                off, n = gpt_stage_param_offset(self.cfg, l, tid)
+                assert p[name].size == n, (name, p[name].shape, n)
+                self.weights[off:off + n].copy_(to_device(p[name].reshape(-1), self.shape.dtype, self.device))
+
+    def read_grads(self) -> List[Dict[str, np.ndarray]]:
+        shapes = synth.param_shapes(self.shape)
+        flat = self.dparams.cpu().numpy()
+        out = []
+        for l in range(self.shape.n_layers):
+            d = {}
+            for tid, name in enumerate(synth.TENSOR_NAMES):
+                off, n = gpt_stage_param_offset(self.cfg, l, tid)
+                d[name] = flat[off:off + n].reshape(shapes[name]).astype(np.float64)
+            out.append(d)
+        return out

@@ -1,0 +1,100 @@
+// Shared device/host helpers of libgptstage (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gpts {
+
+using bf16 = __bf16;  // hardware round-to-nearest-even conversions (v_cvt_pk_bf16_f32)
+
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+
+// ---- storage <-> fp32 -------------------------------------------------------
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16 v) { return static_cast<float>(v); }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return static_cast<bf16>(v); }
+
+// A 16-byte vector of storage elements: 4 x fp32 or 8 x bf16.
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+  static constexpr int N = 4;
+  f32x4 v;
+  __device__ __forceinline__ float get(int i) const { return v[i]; }
+  __device__ __forceinline__ void set(int i, float x) { v[i] = x; }
+};
+template <> struct Vec16<bf16> {
+  static constexpr int N = 8;
+  bf16x8 v;
+  __device__ __forceinline__ float get(int i) const { return static_cast<float>(v[i]); }
+  __device__ __forceinline__ void set(int i, float x) { v[i] = static_cast<bf16>(x); }
+};
+template <typename T> __device__ __forceinline__ Vec16<T> load16(const T* p) {
+  return *reinterpret_cast<const Vec16<T>*>(p);
+}
+template <typename T> __device__ __forceinline__ void store16(T* p, const Vec16<T>& v) {
+  *reinterpret_cast<Vec16<T>*>(p) = v;
+}
+
+// ---- wavefront / workgroup reductions (64-wide) ------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+// Sum over a workgroup of NW waves; every thread gets the result.  `red` is
+// NW floats of LDS.  Fixed combination order -> deterministic.
+template <int NW> __device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  if constexpr (NW == 1) return v;
+  const int w = threadIdx.x / kWave;
+  __syncthreads();
+  if ((threadIdx.x & (kWave - 1)) == 0) red[w] = v;
+  __syncthreads();
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) s += red[i];
+  return s;
+}
+
+// ---- GeLU (fp32 evaluation) -----------------------------------------------------
+// tanh form: 0.5 u (1 + tanh(k (u + 0.044715 u^3))), k = sqrt(2/pi); erf form: u Phi(u).
+__device__ __forceinline__ float tanh_fast(float z) {
+  // tanh z = 1 - 2/(exp(2z)+1); exact limits at +-inf, abs error ~1e-7
+  const float e = __expf(2.f * z);
+  return 1.f - 2.f / (e + 1.f);
+}
+template <int KIND> __device__ __forceinline__ float gelu_f(float u) {
+  if constexpr (KIND == 0) {
+    const float z = 0.7978845608028654f * (u + 0.044715f * u * u * u);
+    return 0.5f * u * (1.f + tanh_fast(z));
+  } else {
+    return 0.5f * u * (1.f + erff(u * 0.7071067811865476f));
+  }
+}
+template <int KIND> __device__ __forceinline__ float gelu_grad_f(float u) {
+  if constexpr (KIND == 0) {
+    const float z = 0.7978845608028654f * (u + 0.044715f * u * u * u);
+    const float t = tanh_fast(z);
+    return 0.5f * (1.f + t) +
+           0.5f * u * (1.f - t * t) * 0.7978845608028654f * (1.f + 3.f * 0.044715f * u * u);
+  } else {
+    const float cdf = 0.5f * (1.f + erff(u * 0.7071067811865476f));
+    const float pdf = 0.3989422804014327f * __expf(-0.5f * u * u);
+    return cdf + u * pdf;
+  }
+}
+
+}  // namespace gpts

@@ -1,0 +1,43 @@
+// Internal launcher interface between the stage orchestrator and the kernels.
+// Every launcher only enqueues on `st` and returns hipGetLastError().
+#pragma once
+#include "common.hpp"
+
+namespace gpts {
+
+// dtype: 0 = fp32 storage, 1 = bf16 storage (fp32 arithmetic in both).
+
+hipError_t ln_fwd(int dtype, int T_rows, int H, float eps, const void* x, const void* gamma,
+                  const void* beta, void* out, float* mean, float* rstd, hipStream_t st);
+size_t ln_bwd_scratch_bytes(int T_rows, int H);
+hipError_t ln_bwd(int dtype, int T_rows, int H, const void* dout, const void* x, const float* mean,
+                  const float* rstd, const void* gamma, const void* dres, void* dx, float* dgamma,
+                  float* dbeta, float* partial, hipStream_t st);
+size_t colsum_scratch_bytes(int M, int N);
+hipError_t colsum(int dtype, int M, int N, const void* A, float* out, float* partial,
+                  hipStream_t st);
+
+// Epilogue description shared by all GEMM implementations.
+struct GemmEpilogue {
+  const void* bias = nullptr;      // [N], storage dtype, added to every row
+  const void* residual = nullptr;  // [M,N], storage dtype, added
+  void* gelu_out = nullptr;        // [M,N]: if set, C keeps the pre-activation and this gets gelu(C)
+  const void* dgelu_u = nullptr;   // [M,N]: if set, C *= gelu'(u)
+  int gelu_kind = 0;               // 0 tanh, 1 erf
+};
+// form 0: C[M,N] = A[M,K] B[N,K]^T ; form 1: C[M,N] = A[M,K] B[K,N] ;
+// form 2: Cf32[M,N] += A[K,M]^T B[K,N].
+hipError_t gemm_simple(int dtype, int form, int M, int N, int K, const void* A, const void* B,
+                       void* C, const GemmEpilogue& ep, hipStream_t st);
+// bf16 MFMA path; returns hipErrorNotSupported if the shape does not fit its tiles.
+bool gemm_mfma_supported(int form, int M, int N, int K);
+hipError_t gemm_mfma(int form, int M, int N, int K, const void* A, const void* B, void* C,
+                     const GemmEpilogue& ep, hipStream_t st);
+
+hipError_t attention_fwd_simple(int dtype, int B, int S, int a, int d, const void* qkv, void* out,
+                                float* lse, hipStream_t st);
+hipError_t attention_bwd_simple(int dtype, int B, int S, int a, int d, const void* qkv,
+                                const void* out, const float* lse, const void* dout, void* dqkv,
+                                float* delta, hipStream_t st);
+
+}  // namespace gpts

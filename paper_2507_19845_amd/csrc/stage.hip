@@ -1,0 +1,416 @@
+// C-ABI of libgptstage and the stage orchestrator: buffer layouts, argument
+// validation and the per-layer launch sequence of the forward and backward
+// phases.  All arithmetic lives in the kernels; this file only sequences them.
+#include "../../include/gpt_stage.h"
+
+#include <string.h>
+
+#include "kernels.hpp"
+
+using namespace gpts;
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline size_t esize(const gpt_stage_cfg& c) { return c.dtype == GPTS_BF16 ? 2 : 4; }
+
+struct Dims {
+  int L, H, a, d, P, F, S, B, T;
+  explicit Dims(const gpt_stage_cfg& c)
+      : L(c.n_layers), H(c.hidden), a(c.n_heads), d(c.head_dim), P(c.n_heads * c.head_dim),
+        F(c.ffn), S(c.seq), B(c.batch), T(c.batch * c.seq) {}
+};
+
+size_t tensor_elems(const Dims& D, int id) {
+  switch (id) {
+    case GPTS_LN1_G: case GPTS_LN1_B: case GPTS_LN2_G: case GPTS_LN2_B:
+    case GPTS_B_O: case GPTS_B_FC2: return D.H;
+    case GPTS_W_QKV: return (size_t)3 * D.P * D.H;
+    case GPTS_B_QKV: return (size_t)3 * D.P;
+    case GPTS_W_O: return (size_t)D.H * D.P;
+    case GPTS_W_FC1: return (size_t)D.F * D.H;
+    case GPTS_B_FC1: return D.F;
+    case GPTS_W_FC2: return (size_t)D.H * D.F;
+  }
+  return 0;
+}
+
+size_t layer_elems(const Dims& D) {
+  size_t n = 0;
+  for (int i = 0; i < GPTS_N_TENSORS; ++i) n += tensor_elems(D, i);
+  return n;
+}
+
+size_t tensor_off(const Dims& D, int layer, int id) {
+  size_t o = (size_t)layer * layer_elems(D);
+  for (int i = 0; i < id; ++i) o += tensor_elems(D, i);
+  return o;
+}
+
+// ---- activation stash of one micro-batch: per layer, in this order ----------
+//   X [T,H]  mean1,rstd1 [T]f32  A [T,H]  QKV [T,3P]  C [T,P]  LSE [B,a,S]f32
+//   X1 [T,H] mean2,rstd2 [T]f32  A2 [T,H] U [T,F]  G [T,F]
+// every region 256-byte aligned.
+struct StashLayer {
+  size_t X, stat1, A, QKV, C, LSE, X1, stat2, A2, U, G, end;
+};
+StashLayer stash_layer(const gpt_stage_cfg& c) {
+  Dims D(c);
+  const size_t e = esize(c);
+  StashLayer s;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
+  s.X = take((size_t)D.T * D.H * e);
+  s.stat1 = take((size_t)2 * D.T * 4);
+  s.A = take((size_t)D.T * D.H * e);
+  s.QKV = take((size_t)D.T * 3 * D.P * e);
+  s.C = take((size_t)D.T * D.P * e);
+  s.LSE = take((size_t)D.B * D.a * D.S * 4);
+  s.X1 = take((size_t)D.T * D.H * e);
+  s.stat2 = take((size_t)2 * D.T * 4);
+  s.A2 = take((size_t)D.T * D.H * e);
+  s.U = take((size_t)D.T * D.F * e);
+  s.G = take((size_t)D.T * D.F * e);
+  s.end = o;
+  return s;
+}
+
+// ---- backward workspace ----------------------------------------------------------
+struct BwdWs {
+  size_t dU, dA, dX1, dC, dQKV, delta, ping, pong, ln_part, cs_part, end;
+};
+BwdWs bwd_ws(const gpt_stage_cfg& c) {
+  Dims D(c);
+  const size_t e = esize(c);
+  BwdWs w;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
+  w.dU = take((size_t)D.T * D.F * e);
+  w.dA = take((size_t)D.T * D.H * e);
+  w.dX1 = take((size_t)D.T * D.H * e);
+  w.dC = take((size_t)D.T * D.P * e);
+  w.dQKV = take((size_t)D.T * 3 * D.P * e);
+  w.delta = take((size_t)D.B * D.a * D.S * 4);
+  w.ping = take((size_t)D.T * D.H * e);
+  w.pong = take((size_t)D.T * D.H * e);
+  w.ln_part = take(ln_bwd_scratch_bytes(D.T, D.H));
+  int maxn = D.H;
+  if (3 * D.P > maxn) maxn = 3 * D.P;
+  if (D.F > maxn) maxn = D.F;
+  w.cs_part = take(colsum_scratch_bytes(D.T, maxn));
+  w.end = o;
+  return w;
+}
+
+int fail(int code, const char* msg) {
+  strncpy(g_err, msg, sizeof(g_err) - 1);
+  g_err[sizeof(g_err) - 1] = 0;
+  return code;
+}
+int hip_fail(hipError_t e, const char* where) {
+  snprintf(g_err, sizeof(g_err), "%s: %s", where, hipGetErrorString(e));
+  return GPTS_EHIP;
+}
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+#define GPTS_TRY(expr, where)                          \
+  do {                                                 \
+    hipError_t e__ = (expr);                           \
+    if (e__ != hipSuccess) return hip_fail(e__, where); \
+  } while (0)
+
+// One matrix product of the stage: MFMA path for bf16 shapes it covers, the
+// plain FMA path otherwise (always for fp32).
+hipError_t gemm(int dtype, int form, int M, int N, int K, const void* A, const void* B, void* C,
+                const GemmEpilogue& ep, hipStream_t st) {
+  if (dtype == GPTS_BF16 && gemm_mfma_supported(form, M, N, K))
+    return gemm_mfma(form, M, N, K, A, B, C, ep, st);
+  return gemm_simple(dtype, form, M, N, K, A, B, C, ep, st);
+}
+
+int check_call(const gpt_stage_params* p) {
+  if (!p) return fail(GPTS_EINVAL, "params is NULL");
+  int rc = gpt_stage_validate(&p->cfg);
+  if (rc != GPTS_OK) return rc;
+  if (!p->weights || misaligned(p->weights)) return fail(GPTS_EINVAL, "weights NULL or not 16-byte aligned");
+  if (p->workspace && misaligned(p->workspace)) return fail(GPTS_EINVAL, "workspace not 16-byte aligned");
+  return GPTS_OK;
+}
+
+int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, hipStream_t st) {
+  int rc = check_call(p);
+  if (rc != GPTS_OK) return rc;
+  if (!x || !act_stash || !y || misaligned(x) || misaligned(act_stash) || misaligned(y))
+    return fail(GPTS_EINVAL, "x / act_stash / y NULL or not 16-byte aligned");
+  if (x == y) return fail(GPTS_EINVAL, "y must not alias x");
+  const gpt_stage_cfg& c = p->cfg;
+  const Dims D(c);
+  const size_t e = esize(c);
+  const int dt = c.dtype;
+  const StashLayer sl = stash_layer(c);
+  const char* W = static_cast<const char*>(p->weights);
+  char* stash = static_cast<char*>(act_stash);
+  auto w = [&](int l, int id) { return (const void*)(W + tensor_off(D, l, id) * e); };
+
+  // layer 0 keeps its own copy of x so the backward phase never needs the caller's buffer
+  GPTS_TRY(hipMemcpyAsync(stash + sl.X, x, (size_t)D.T * D.H * e, hipMemcpyDeviceToDevice, st), "copy x");
+  for (int l = 0; l < D.L; ++l) {
+    char* s = stash + (size_t)l * sl.end;
+    void* X = s + sl.X;
+    float* stat1 = reinterpret_cast<float*>(s + sl.stat1);
+    float* stat2 = reinterpret_cast<float*>(s + sl.stat2);
+    void* Yout = (l == D.L - 1) ? y : (void*)(s + sl.end + sl.X);
+    GPTS_TRY(ln_fwd(dt, D.T, D.H, c.ln_eps, X, w(l, GPTS_LN1_G), w(l, GPTS_LN1_B), s + sl.A, stat1,
+                    stat1 + D.T, st), "ln1 fwd");
+    GemmEpilogue ep;
+    ep.bias = w(l, GPTS_B_QKV);
+    GPTS_TRY(gemm(dt, 0, D.T, 3 * D.P, D.H, s + sl.A, w(l, GPTS_W_QKV), s + sl.QKV, ep, st), "qkv gemm");
+    GPTS_TRY(attention_fwd_simple(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
+                                  reinterpret_cast<float*>(s + sl.LSE), st), "attention fwd");
+    ep = GemmEpilogue();
+    ep.bias = w(l, GPTS_B_O);
+    ep.residual = X;
+    GPTS_TRY(gemm(dt, 0, D.T, D.H, D.P, s + sl.C, w(l, GPTS_W_O), s + sl.X1, ep, st), "out-proj gemm");
+    GPTS_TRY(ln_fwd(dt, D.T, D.H, c.ln_eps, s + sl.X1, w(l, GPTS_LN2_G), w(l, GPTS_LN2_B), s + sl.A2,
+                    stat2, stat2 + D.T, st), "ln2 fwd");
+    ep = GemmEpilogue();
+    ep.bias = w(l, GPTS_B_FC1);
+    ep.gelu_out = s + sl.G;
+    ep.gelu_kind = c.gelu;
+    GPTS_TRY(gemm(dt, 0, D.T, D.F, D.H, s + sl.A2, w(l, GPTS_W_FC1), s + sl.U, ep, st), "fc1 gemm");
+    ep = GemmEpilogue();
+    ep.bias = w(l, GPTS_B_FC2);
+    ep.residual = s + sl.X1;
+    GPTS_TRY(gemm(dt, 0, D.T, D.H, D.F, s + sl.G, w(l, GPTS_W_FC2), Yout, ep, st), "fc2 gemm");
+  }
+  return GPTS_OK;
+}
+
+int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, void* dx,
+            void* dparams, hipStream_t st) {
+  int rc = check_call(p);
+  if (rc != GPTS_OK) return rc;
+  if (!act_stash || !dy || !dx || !dparams || misaligned(act_stash) || misaligned(dy) ||
+      misaligned(dx) || misaligned(dparams))
+    return fail(GPTS_EINVAL, "act_stash / dy / dx / dparams NULL or not 16-byte aligned");
+  if (!p->workspace) return fail(GPTS_EINVAL, "backward needs a workspace");
+  const gpt_stage_cfg& c = p->cfg;
+  const Dims D(c);
+  const size_t e = esize(c);
+  const int dt = c.dtype;
+  const StashLayer sl = stash_layer(c);
+  const BwdWs ws = bwd_ws(c);
+  const char* W = static_cast<const char*>(p->weights);
+  const char* stash = static_cast<const char*>(act_stash);
+  char* wk = static_cast<char*>(p->workspace);
+  float* dP = static_cast<float*>(dparams);
+  auto w = [&](int l, int id) { return (const void*)(W + tensor_off(D, l, id) * e); };
+  auto g = [&](int l, int id) { return dP + tensor_off(D, l, id); };
+  float* ln_part = reinterpret_cast<float*>(wk + ws.ln_part);
+  float* cs_part = reinterpret_cast<float*>(wk + ws.cs_part);
+  void* dU = wk + ws.dU;
+  void* dA = wk + ws.dA;
+  void* dX1 = wk + ws.dX1;
+  void* dC = wk + ws.dC;
+  void* dQKV = wk + ws.dQKV;
+  float* delta = reinterpret_cast<float*>(wk + ws.delta);
+
+  const void* dY = dy;
+  for (int l = D.L - 1; l >= 0; --l) {
+    const char* s = stash + (size_t)l * sl.end;
+    const float* stat1 = reinterpret_cast<const float*>(s + sl.stat1);
+    const float* stat2 = reinterpret_cast<const float*>(s + sl.stat2);
+    void* dXout = (l == 0) ? dx : (void*)(wk + (((D.L - 1 - l) & 1) ? ws.pong : ws.ping));
+    GemmEpilogue none;
+    // y = x1 + g W2^T + b2 ;  g = gelu(u)
+    GemmEpilogue ep;
+    ep.dgelu_u = s + sl.U;
+    ep.gelu_kind = c.gelu;
+    GPTS_TRY(gemm(dt, 1, D.T, D.F, D.H, dY, w(l, GPTS_W_FC2), dU, ep, st), "fc2 dgrad");
+    GPTS_TRY(gemm(dt, 2, D.H, D.F, D.T, dY, s + sl.G, g(l, GPTS_W_FC2), none, st), "fc2 wgrad");
+    GPTS_TRY(colsum(dt, D.T, D.H, dY, g(l, GPTS_B_FC2), cs_part, st), "fc2 bias grad");
+    // u = a2 W1^T + b1
+    GPTS_TRY(gemm(dt, 1, D.T, D.H, D.F, dU, w(l, GPTS_W_FC1), dA, none, st), "fc1 dgrad");
+    GPTS_TRY(gemm(dt, 2, D.F, D.H, D.T, dU, s + sl.A2, g(l, GPTS_W_FC1), none, st), "fc1 wgrad");
+    GPTS_TRY(colsum(dt, D.T, D.F, dU, g(l, GPTS_B_FC1), cs_part, st), "fc1 bias grad");
+    // a2 = LN2(x1), x1 also feeds the residual
+    GPTS_TRY(ln_bwd(dt, D.T, D.H, dA, s + sl.X1, stat2, stat2 + D.T, w(l, GPTS_LN2_G), dY, dX1,
+                    g(l, GPTS_LN2_G), g(l, GPTS_LN2_B), ln_part, st), "ln2 bwd");
+    // x1 = x + c Wo^T + bo
+    GPTS_TRY(gemm(dt, 1, D.T, D.P, D.H, dX1, w(l, GPTS_W_O), dC, none, st), "out-proj dgrad");
+    GPTS_TRY(gemm(dt, 2, D.H, D.P, D.T, dX1, s + sl.C, g(l, GPTS_W_O), none, st), "out-proj wgrad");
+    GPTS_TRY(colsum(dt, D.T, D.H, dX1, g(l, GPTS_B_O), cs_part, st), "out-proj bias grad");
+    // c = attention(qkv)
+    GPTS_TRY(attention_bwd_simple(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
+                                  reinterpret_cast<const float*>(s + sl.LSE), dC, dQKV, delta, st),
+             "attention bwd");
+    // qkv = a Wqkv^T + bqkv
+    GPTS_TRY(gemm(dt, 1, D.T, D.H, 3 * D.P, dQKV, w(l, GPTS_W_QKV), dA, none, st), "qkv dgrad");
+    GPTS_TRY(gemm(dt, 2, 3 * D.P, D.H, D.T, dQKV, s + sl.A, g(l, GPTS_W_QKV), none, st), "qkv wgrad");
+    GPTS_TRY(colsum(dt, D.T, 3 * D.P, dQKV, g(l, GPTS_B_QKV), cs_part, st), "qkv bias grad");
+    // a = LN1(x), x also feeds the residual
+    GPTS_TRY(ln_bwd(dt, D.T, D.H, dA, s + sl.X, stat1, stat1 + D.T, w(l, GPTS_LN1_G), dX1, dXout,
+                    g(l, GPTS_LN1_G), g(l, GPTS_LN1_B), ln_part, st), "ln1 bwd");
+    dY = dXout;
+  }
+  return GPTS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gpt_stage_validate(const gpt_stage_cfg* c) {
+  if (!c) return fail(GPTS_EINVAL, "cfg is NULL");
+  if (c->dtype != GPTS_FP32 && c->dtype != GPTS_BF16) return fail(GPTS_EINVAL, "dtype must be GPTS_FP32 or GPTS_BF16");
+  if (c->gelu != GPTS_GELU_TANH && c->gelu != GPTS_GELU_ERF) return fail(GPTS_EINVAL, "gelu must be GPTS_GELU_TANH or GPTS_GELU_ERF");
+  if (!(c->ln_eps >= 0.f)) return fail(GPTS_EINVAL, "ln_eps must be >= 0");
+  if (c->n_layers < 1 || c->batch < 1 || c->seq < 1 || c->n_heads < 1 || c->hidden < 1 || c->ffn < 1)
+    return fail(GPTS_ESHAPE, "n_layers, batch, seq, n_heads, hidden, ffn must be >= 1");
+  if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128)
+    return fail(GPTS_ESHAPE, "head_dim must be 32, 64 or 128");
+  const long long P = (long long)c->n_heads * c->head_dim, T = (long long)c->batch * c->seq;
+  if (c->hidden % 8 || c->ffn % 8) return fail(GPTS_ESHAPE, "hidden and ffn must be multiples of 8");
+  if (c->hidden > 16384) return fail(GPTS_ESHAPE, "hidden must be <= 16384");
+  if (T > (1 << 24) || P > (1 << 20) || c->ffn > (1 << 20)) return fail(GPTS_ESHAPE, "tokens, attention width or ffn too large");
+  if (c->dtype == GPTS_BF16 && (T % 64 || c->hidden % 64 || P % 64 || c->ffn % 64))
+    return fail(GPTS_ESHAPE, "bf16 stages need tokens, hidden, attention width and ffn to be multiples of 64");
+  return GPTS_OK;
+}
+
+size_t gpt_stage_param_count(const gpt_stage_cfg* c) {
+  if (gpt_stage_validate(c) != GPTS_OK) return 0;
+  Dims D(*c);
+  return layer_elems(D) * D.L;
+}
+size_t gpt_stage_param_bytes(const gpt_stage_cfg* c) { return gpt_stage_param_count(c) * (c ? esize(*c) : 0); }
+size_t gpt_stage_grad_bytes(const gpt_stage_cfg* c) { return gpt_stage_param_count(c) * sizeof(float); }
+size_t gpt_stage_stash_bytes(const gpt_stage_cfg* c) {
+  if (gpt_stage_validate(c) != GPTS_OK) return 0;
+  return stash_layer(*c).end * c->n_layers;
+}
+size_t gpt_stage_workspace_bytes(const gpt_stage_cfg* c, int phase) {
+  if (gpt_stage_validate(c) != GPTS_OK) return 0;
+  return phase == 0 ? 0 : bwd_ws(*c).end;
+}
+int gpt_stage_param_offset(const gpt_stage_cfg* c, int layer, int tensor_id, size_t* elem_off, size_t* n_elem) {
+  int rc = gpt_stage_validate(c);
+  if (rc != GPTS_OK) return rc;
+  if (layer < 0 || layer >= c->n_layers || tensor_id < 0 || tensor_id >= GPTS_N_TENSORS || !elem_off || !n_elem)
+    return fail(GPTS_EINVAL, "layer / tensor_id out of range or NULL output pointer");
+  Dims D(*c);
+  *elem_off = tensor_off(D, layer, tensor_id);
+  *n_elem = tensor_elems(D, tensor_id);
+  return GPTS_OK;
+}
+double gpt_stage_model_flops(const gpt_stage_cfg* c, int causal_aware) {
+  if (gpt_stage_validate(c) != GPTS_OK) return 0.0;
+  Dims D(*c);
+  const double lin = 2.0 * D.T * (4.0 * D.P * D.H + 2.0 * (double)D.H * D.F);
+  const double pairs = causal_aware ? (double)D.S * (D.S + 1) / 2.0 : (double)D.S * D.S;
+  const double att = 4.0 * D.B * D.a * D.d * pairs;
+  return 3.0 * D.L * (lin + att);
+}
+const char* gpt_stage_strerror(int code) {
+  switch (code) {
+    case GPTS_OK: return "ok";
+    case GPTS_EINVAL: case GPTS_ESHAPE: case GPTS_EHIP: return g_err[0] ? g_err : "error";
+  }
+  return "unknown status";
+}
+
+int gpt_stage_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, void* stream) {
+  return run_fwd(p, x, act_stash, y, static_cast<hipStream_t>(stream));
+}
+int gpt_stage_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, void* dx,
+                  void* dparams, void* stream) {
+  return run_bwd(p, act_stash, dy, dx, dparams, static_cast<hipStream_t>(stream));
+}
+int gpt_stage_fwd_only(const gpt_stage_params* p, const void* x, void* act_stash, void* y,
+                       void* stream, void* done_event) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rc = run_fwd(p, x, act_stash, y, st);
+  if (rc != GPTS_OK) return rc;
+  if (done_event) GPTS_TRY(hipEventRecord(static_cast<hipEvent_t>(done_event), st), "record done_event");
+  return GPTS_OK;
+}
+int gpt_stage_bwd_only(const gpt_stage_params* p, const void* act_stash, const void* dy, void* dx,
+                       void* dparams, void* stream, void* wait_event) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rc = check_call(p);  // validate before touching the stream
+  if (rc != GPTS_OK) return rc;
+  if (wait_event) GPTS_TRY(hipStreamWaitEvent(st, static_cast<hipEvent_t>(wait_event), 0), "wait on wait_event");
+  return run_bwd(p, act_stash, dy, dx, dparams, st);
+}
+int gpt_stage_fwd_bwd(const gpt_stage_params* p, const void* x, const void* dy, void* act_stash,
+                      void* y, void* dx, void* dparams, void* stream) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rc = run_fwd(p, x, act_stash, y, st);
+  if (rc != GPTS_OK) return rc;
+  return run_bwd(p, act_stash, dy, dx, dparams, st);
+}
+
+// ---- single operations ------------------------------------------------------------
+static int op_dtype_ok(int dtype) { return dtype == GPTS_FP32 || dtype == GPTS_BF16; }
+
+int gpt_stage_op_layernorm_fwd(int dtype, int T, int H, float eps, const void* x, const void* gamma,
+                               const void* beta, void* out, float* mean, float* rstd, void* stream) {
+  if (!op_dtype_ok(dtype) || !x || !gamma || !beta || !out || !mean || !rstd) return fail(GPTS_EINVAL, "layernorm_fwd: bad argument");
+  if (T < 1 || H < 8 || H % 8 || H > 16384) return fail(GPTS_ESHAPE, "layernorm_fwd: H must be a multiple of 8, <= 16384");
+  GPTS_TRY(ln_fwd(dtype, T, H, eps, x, gamma, beta, out, mean, rstd, static_cast<hipStream_t>(stream)), "layernorm_fwd");
+  return GPTS_OK;
+}
+size_t gpt_stage_op_layernorm_bwd_scratch_bytes(int T, int H) { return ln_bwd_scratch_bytes(T, H); }
+int gpt_stage_op_layernorm_bwd(int dtype, int T, int H, const void* dout, const void* x,
+                               const float* mean, const float* rstd, const void* gamma,
+                               const void* dres, void* dx, float* dgamma, float* dbeta,
+                               float* partial, void* stream) {
+  if (!op_dtype_ok(dtype) || !dout || !x || !mean || !rstd || !gamma || !dx || !dgamma || !dbeta || !partial)
+    return fail(GPTS_EINVAL, "layernorm_bwd: bad argument");
+  if (T < 1 || H < 8 || H % 8 || H > 16384) return fail(GPTS_ESHAPE, "layernorm_bwd: H must be a multiple of 8, <= 16384");
+  GPTS_TRY(ln_bwd(dtype, T, H, dout, x, mean, rstd, gamma, dres, dx, dgamma, dbeta, partial,
+                  static_cast<hipStream_t>(stream)), "layernorm_bwd");
+  return GPTS_OK;
+}
+int gpt_stage_op_gemm(int dtype, int form, int M, int N, int K, const void* A, const void* B, void* C,
+                      const void* bias, const void* residual, void* C2, const void* dgelu_u,
+                      int gelu_kind, void* stream) {
+  if (!op_dtype_ok(dtype) || form < 0 || form > 2 || !A || !B || !C) return fail(GPTS_EINVAL, "gemm: bad argument");
+  if (M < 1 || N < 1 || K < 1) return fail(GPTS_ESHAPE, "gemm: M, N, K must be >= 1");
+  if (form == 2 && (bias || residual || C2 || dgelu_u)) return fail(GPTS_EINVAL, "gemm: the wgrad form takes no epilogue");
+  if (form == 1 && C2) return fail(GPTS_EINVAL, "gemm: gelu output only with form 0");
+  if (form == 0 && dgelu_u) return fail(GPTS_EINVAL, "gemm: dgelu only with form 1");
+  GemmEpilogue ep;
+  ep.bias = bias; ep.residual = residual; ep.gelu_out = C2; ep.dgelu_u = dgelu_u; ep.gelu_kind = gelu_kind;
+  GPTS_TRY(gemm(dtype, form, M, N, K, A, B, C, ep, static_cast<hipStream_t>(stream)), "gemm");
+  return GPTS_OK;
+}
+size_t gpt_stage_op_colsum_scratch_bytes(int M, int N) { return colsum_scratch_bytes(M, N); }
+int gpt_stage_op_colsum(int dtype, int M, int N, const void* A, float* out, float* partial, void* stream) {
+  if (!op_dtype_ok(dtype) || !A || !out || !partial) return fail(GPTS_EINVAL, "colsum: bad argument");
+  if (M < 1 || N < 8 || N % 8) return fail(GPTS_ESHAPE, "colsum: N must be a multiple of 8");
+  GPTS_TRY(colsum(dtype, M, N, A, out, partial, static_cast<hipStream_t>(stream)), "colsum");
+  return GPTS_OK;
+}
+int gpt_stage_op_attention_fwd(int dtype, int B, int S, int n_heads, int head_dim, const void* qkv,
+                               void* out, float* lse, void* stream) {
+  if (!op_dtype_ok(dtype) || !qkv || !out || !lse) return fail(GPTS_EINVAL, "attention_fwd: bad argument");
+  if (B < 1 || S < 1 || n_heads < 1 || (head_dim != 32 && head_dim != 64 && head_dim != 128))
+    return fail(GPTS_ESHAPE, "attention_fwd: head_dim must be 32, 64 or 128");
+  GPTS_TRY(attention_fwd_simple(dtype, B, S, n_heads, head_dim, qkv, out, lse, static_cast<hipStream_t>(stream)), "attention_fwd");
+  return GPTS_OK;
+}
+int gpt_stage_op_attention_bwd(int dtype, int B, int S, int n_heads, int head_dim, const void* qkv,
+                               const void* out, const float* lse, const void* dout, void* dqkv,
+                               float* delta, void* stream) {
+  if (!op_dtype_ok(dtype) || !qkv || !out || !lse || !dout || !dqkv || !delta) return fail(GPTS_EINVAL, "attention_bwd: bad argument");
+  if (B < 1 || S < 1 || n_heads < 1 || (head_dim != 32 && head_dim != 64 && head_dim != 128))
+    return fail(GPTS_ESHAPE, "attention_bwd: head_dim must be 32, 64 or 128");
+  GPTS_TRY(attention_bwd_simple(dtype, B, S, n_heads, head_dim, qkv, out, lse, dout, dqkv, delta,
+                                static_cast<hipStream_t>(stream)), "attention_bwd");
+  return GPTS_OK;
+}
+
+}  // extern "C"

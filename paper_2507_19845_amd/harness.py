@@ -1,0 +1,48 @@
+"""Schedules of stage calls over micro-batches (host-side sequencing only).
+
+Two schedules, both built from the C entry points:
+  * coupled   -- for each micro-batch: gpt_stage_fwd then gpt_stage_bwd on one stream;
+  * decoupled -- every micro-batch's forward first on a forward stream, each into
+    its own stash slot, then every backward on a separate backward stream that
+    waits on an event recorded after the last forward: the breadth-first order
+    of the paper's section 5.2 run as the two decoupled phases of section 4.1.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import torch
+
+from . import binding as B
+
+
+class StageRunner:
+    def __init__(self, bufs: B.StageBuffers):
+        self.b = bufs
+        self.fwd_stream = torch.cuda.Stream()
+        self.bwd_stream = torch.cuda.Stream()
+        self.event = torch.cuda.Event()
+
+    def coupled(self, xs: Sequence[torch.Tensor], dys: Sequence[torch.Tensor],
+                ys: Sequence[torch.Tensor], dxs: Sequence[torch.Tensor],
+                stream: Optional[torch.cuda.Stream] = None) -> None:
+        b = self.b
+        for x, dy, y, dx in zip(xs, dys, ys, dxs):
+            B.gpt_stage_fwd(b.cfg, b.weights, b.workspace, x, b.stash[0], y, stream)
+            B.gpt_stage_bwd(b.cfg, b.weights, b.workspace, b.stash[0], dy, dx, b.dparams, stream)
+
+    def decoupled(self, xs, dys, ys, dxs) -> None:
+        """All forwards on fwd_stream, then all backwards on bwd_stream.  The
+        caller's current stream is joined on both sides."""
+        b = self.b
+        assert len(b.stash) >= len(xs), "one stash slot per in-flight micro-batch"
+        cur = torch.cuda.current_stream()
+        self.fwd_stream.wait_stream(cur)
+        n = len(xs)
+        for i in range(n):
+            B.gpt_stage_fwd_only(b.cfg, b.weights, b.workspace, xs[i], b.stash[i], ys[i],
+                                 self.fwd_stream, self.event if i == n - 1 else None)
+        for i in range(n):
+            B.gpt_stage_bwd_only(b.cfg, b.weights, b.workspace, b.stash[i], dys[i], dxs[i],
+                                 b.dparams, self.bwd_stream, self.event if i == 0 else None)
+        cur.wait_stream(self.bwd_stream)

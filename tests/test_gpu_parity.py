@@ -1,0 +1,251 @@
+"""GPU parity: the HIP library, called through its C-ABI, against the CPU fp64
+oracle on the same seeded inputs, tensor by tensor.  Tolerance (tensor-max-
+normalised max error): 1e-4 for fp32 stages, 2e-2 for bf16 stages."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gpt_stage_oracle as orc
+from paper_2507_19845_amd import binding as B
+from paper_2507_19845_amd import synth
+
+from parity_util import TOL, compare, gpu_run, max_norm_err, oracle_run, p64
+
+pytestmark = pytest.mark.gpu
+
+W = synth.WORKLOADS
+
+
+def _inputs(shape, n_mb=1, seed=0):
+    params = synth.make_params(shape, seed)
+    xs = [synth.make_x(shape, seed, m) for m in range(n_mb)]
+    dys = [synth.make_dy(shape, seed, m) for m in range(n_mb)]
+    return params, xs, dys
+
+
+def _report(name, errs):
+    worst = max(errs, key=errs.get)
+    print(f"[parity] {name}: worst {worst} = {errs[worst]:.3e}", flush=True)
+
+
+# ------------------------------------------------------------- whole stage ----
+SMALL = [
+    W[0],                                                        # workload 1 as specified (fp32)
+    W[0].with_(name="tiny_fp32_erf", gelu="erf", bias_std=0.02, ln_jitter=0.1),
+    W[0].with_(name="tiny_fp32_ragged", seq=50, batch=3, n_layers=2, bias_std=0.02, ln_jitter=0.1),
+    W[0].with_(name="tiny_fp32_seq1", seq=1, batch=5),
+    W[0].with_(name="tiny_fp32_tp", hidden=192, n_heads=2, head_dim=32, ffn=136, bias_std=0.02),
+    W[0].with_(name="tiny_fp32_d64", n_heads=2, head_dim=64, seq=70),
+    W[0].with_(name="tiny_fp32_d128", n_heads=1, head_dim=128, seq=33),
+    # bf16 cases spanning several tiles with a ragged (non-256) tail in every dimension
+    W[1].with_(name="bf16_small", n_layers=2, hidden=320, n_heads=5, head_dim=64, ffn=832, seq=192,
+               batch=2, bias_std=0.02, ln_jitter=0.1),
+    W[1].with_(name="bf16_d128_tp", n_layers=2, hidden=512, n_heads=3, head_dim=128, ffn=448,
+               seq=320, batch=1, bias_std=0.02, ln_jitter=0.1),
+    W[1].with_(name="bf16_erf", n_layers=1, hidden=256, n_heads=4, head_dim=64, ffn=512, seq=64,
+               batch=1, gelu="erf", bias_std=0.02),
+]
+
+
+@pytest.mark.parametrize("shape", SMALL, ids=lambda s: s.name)
+def test_stage_matches_oracle(shape):
+    print(f"[case] stage {shape}", flush=True)
+    params, xs, dys = _inputs(shape)
+    got = gpu_run(shape, params, xs, dys)
+    ref = oracle_run(shape, params, xs, dys)
+    _report(shape.name, compare(shape, got, ref))
+
+
+def test_microbatch_accumulation_and_decoupled_schedule():
+    """3 micro-batches: gradients accumulate across calls; the decoupled
+    (all-forward-then-all-backward, two streams) schedule gives bit-identical
+    results to the coupled one; both match the oracle."""
+    shape = W[1].with_(name="bf16_mb", n_layers=2, hidden=256, n_heads=4, head_dim=64, ffn=512,
+                       seq=128, batch=1, bias_std=0.02, ln_jitter=0.1)
+    print(f"[case] microbatches {shape}", flush=True)
+    params, xs, dys = _inputs(shape, n_mb=3)
+    a = gpu_run(shape, params, xs, dys, decoupled=False)
+    b = gpu_run(shape, params, xs, dys, decoupled=True)
+    for i in range(3):
+        assert np.array_equal(a[0][i], b[0][i]) and np.array_equal(a[1][i], b[1][i])
+    for ga, gb in zip(a[2], b[2]):
+        for k in ga:
+            assert np.array_equal(ga[k], gb[k]), k
+    _report(shape.name, compare(shape, b, oracle_run(shape, params, xs, dys)))
+
+
+def test_run_to_run_bitwise_determinism():
+    shape = W[1].with_(name="bf16_det", n_layers=1, hidden=256, n_heads=4, head_dim=64, ffn=512,
+                       seq=256, batch=2)
+    print(f"[case] determinism {shape}", flush=True)
+    params, xs, dys = _inputs(shape)
+    a = gpu_run(shape, params, xs, dys)
+    b = gpu_run(shape, params, xs, dys)
+    assert np.array_equal(a[0][0], b[0][0]) and np.array_equal(a[1][0], b[1][0])
+    for ga, gb in zip(a[2], b[2]):
+        for k in ga:
+            assert np.array_equal(ga[k], gb[k]), k
+
+
+def test_zero_weight_identity_residual_on_gpu():
+    """All W = 0, b = 0: y = x and dx = dy bit for bit; db_o = db_fc2 = sum_t dy."""
+    shape = W[1].with_(name="bf16_zero", n_layers=2, hidden=256, n_heads=4, head_dim=64, ffn=512,
+                       seq=128, batch=1)
+    print(f"[case] zero weights {shape}", flush=True)
+    params, xs, dys = _inputs(shape)
+    for p in params:
+        for k in p:
+            if k[:2] in ("w_", "b_"):
+                p[k][...] = 0.0
+    ys, dxs, grads = gpu_run(shape, params, xs, dys)
+    assert np.array_equal(ys[0], xs[0].astype(np.float64))
+    assert np.array_equal(dxs[0], dys[0].astype(np.float64))
+    colsum = dys[0].astype(np.float64).reshape(-1, shape.hidden).sum(0)
+    for g in grads:
+        for k, v in g.items():
+            if k in ("b_o", "b_fc2"):
+                assert max_norm_err(v, colsum) < 1e-5
+            else:
+                assert np.all(v == 0.0), k
+
+
+def test_causality_on_gpu():
+    shape = W[1].with_(name="bf16_causal", n_layers=2, hidden=256, n_heads=4, head_dim=64, ffn=512,
+                       seq=192, batch=2)
+    print(f"[case] causality {shape}", flush=True)
+    params, xs, dys = _inputs(shape)
+    y0, _, _ = gpu_run(shape, params, xs, dys)
+    t = 100
+    x2 = xs[0].copy()
+    x2[0, t:, :] = synth.make_x(shape, 7)[0, t:, :]
+    y1, _, _ = gpu_run(shape, params, [x2], dys)
+    assert np.array_equal(y0[0][0, :t], y1[0][0, :t])
+    assert np.array_equal(y0[0][1], y1[0][1])
+    assert not np.array_equal(y0[0][0, t:], y1[0][0, t:])
+
+
+# ------------------------------------------------------ full-size workloads ----
+def test_workload2_full_size():
+    shape = W[1]
+    print(f"[case] full {shape}", flush=True)
+    params, xs, dys = _inputs(shape)
+    got = gpu_run(shape, params, xs, dys)
+    ref = oracle_run(shape, params, xs, dys)
+    _report(shape.name, compare(shape, got, ref))
+
+
+# ------------------------------------------------------- single operations ----
+@pytest.mark.parametrize("dtype,T,H", [("fp32", 37, 128), ("fp32", 5, 4104), ("bf16", 130, 1024),
+                                       ("bf16", 64, 12288), ("bf16", 3, 8), ("fp32", 600, 16384)])
+def test_op_layernorm(dtype, T, H):
+    print(f"[case] layernorm {dtype} T={T} H={H}", flush=True)
+    dt = B.GPTS_BF16 if dtype == "bf16" else B.GPTS_FP32
+    x = synth.to_storage(synth.make_aux(0, 1, (T, H)) * 2 + 0.5, dtype)
+    gam = synth.to_storage(1 + synth.make_aux(0, 2, (H,), 0.2), dtype)
+    bet = synth.to_storage(synth.make_aux(0, 3, (H,), 0.2), dtype)
+    dout = synth.to_storage(synth.make_aux(0, 4, (T, H)), dtype)
+    dres = synth.to_storage(synth.make_aux(0, 5, (T, H)), dtype)
+    dx_, dg_, db_ = (B.to_device(a, dtype) for a in (x, gam, bet))
+    out = torch.empty_like(dx_)
+    mean = torch.empty(T, dtype=torch.float32, device="cuda")
+    rstd = torch.empty_like(mean)
+    B.gpt_stage_op_layernorm_fwd(dt, T, H, 1e-5, dx_, dg_, db_, out, mean, rstd)
+    ref_out, xhat, r = orc.layernorm_fwd(x, gam, bet, 1e-5)
+    tol = TOL[dtype]
+    assert max_norm_err(B.to_host(out), ref_out) <= tol
+    assert max_norm_err(B.to_host(rstd), r[:, 0]) <= 1e-5
+    assert max_norm_err(B.to_host(mean), x.astype(np.float64).mean(-1)) <= 1e-5
+    part = torch.empty(B.gpt_stage_op_layernorm_bwd_scratch_bytes(T, H), dtype=torch.uint8, device="cuda")
+    dgam = torch.full((H,), 1.0, dtype=torch.float32, device="cuda")     # pre-filled: += semantics
+    dbet = torch.full((H,), -2.0, dtype=torch.float32, device="cuda")
+    dxo = torch.empty_like(dx_)
+    B.gpt_stage_op_layernorm_bwd(dt, T, H, B.to_device(dout, dtype), dx_, mean, rstd, dg_,
+                                 B.to_device(dres, dtype), dxo, dgam, dbet, part)
+    rdx, rdg, rdb = orc.layernorm_bwd(dout, xhat, r, gam)
+    assert max_norm_err(B.to_host(dxo), rdx + dres) <= tol
+    assert max_norm_err(B.to_host(dgam), rdg + 1.0) <= max(tol * 0.1, 1e-5)
+    assert max_norm_err(B.to_host(dbet), rdb - 2.0) <= max(tol * 0.1, 1e-5)
+
+
+GEMM_SHAPES = [(64, 64, 64), (200, 136, 72), (256, 256, 256), (320, 448, 192), (512, 1024, 320),
+               (1024, 768, 2048)]
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_op_gemm_forms(dtype, M, N, K):
+    print(f"[case] gemm {dtype} M={M} N={N} K={K}", flush=True)
+    dt = B.GPTS_BF16 if dtype == "bf16" else B.GPTS_FP32
+    tol = TOL[dtype]
+    st = lambda tag, shp, std=1.0: synth.to_storage(synth.make_aux(1, tag, shp, std), dtype)
+    dev = lambda a: B.to_device(a, dtype)
+    # form 0: C = A B^T + bias (+ residual) ; gelu output
+    A, Bm, bias, res = st(1, (M, K)), st(2, (N, K), 0.05), st(3, (N,), 0.5), st(4, (M, N))
+    Cd = torch.empty((M, N), dtype=dev(A).dtype, device="cuda")
+    B.gpt_stage_op_gemm(dt, 0, M, N, K, dev(A), dev(Bm), Cd, bias=dev(bias), residual=dev(res))
+    ref = A.astype(np.float64) @ Bm.astype(np.float64).T + bias + res
+    assert max_norm_err(B.to_host(Cd), ref) <= tol
+    for kind, variant in ((B.GPTS_GELU_TANH, "tanh"), (B.GPTS_GELU_ERF, "erf")):
+        C2 = torch.empty_like(Cd)
+        B.gpt_stage_op_gemm(dt, 0, M, N, K, dev(A), dev(Bm), Cd, bias=dev(bias), C2=C2, gelu_kind=kind)
+        u = A.astype(np.float64) @ Bm.astype(np.float64).T + bias
+        assert max_norm_err(B.to_host(Cd), u) <= tol
+        assert max_norm_err(B.to_host(C2), orc.gelu(u, variant)) <= tol
+    # form 1: C = A B (B is [K, N]) ; with the gelu' factor
+    Bn, U = st(5, (K, N), 0.05), st(6, (M, N))
+    B.gpt_stage_op_gemm(dt, 1, M, N, K, dev(A), dev(Bn), Cd)
+    ref = A.astype(np.float64) @ Bn.astype(np.float64)
+    assert max_norm_err(B.to_host(Cd), ref) <= tol
+    B.gpt_stage_op_gemm(dt, 1, M, N, K, dev(A), dev(Bn), Cd, dgelu_u=dev(U))
+    assert max_norm_err(B.to_host(Cd), ref * orc.gelu_grad(U, "tanh")) <= tol
+    # form 2: Cf32 += A^T B, A is [K, M]
+    At = st(7, (K, M))
+    Cf = torch.full((M, N), 0.25, dtype=torch.float32, device="cuda")
+    B.gpt_stage_op_gemm(dt, 2, M, N, K, dev(At), dev(Bn), Cf)
+    ref = At.astype(np.float64).T @ Bn.astype(np.float64) + 0.25
+    assert max_norm_err(B.to_host(Cf), ref) <= (1e-5 if dtype == "fp32" else 1e-4)
+
+
+@pytest.mark.parametrize("dtype,M,N", [("fp32", 100, 136), ("bf16", 4096, 1024), ("bf16", 7, 8), ("bf16", 1000, 4608)])
+def test_op_colsum(dtype, M, N):
+    print(f"[case] colsum {dtype} M={M} N={N}", flush=True)
+    dt = B.GPTS_BF16 if dtype == "bf16" else B.GPTS_FP32
+    A = synth.to_storage(synth.make_aux(2, 1, (M, N)), dtype)
+    out = torch.full((N,), 3.0, dtype=torch.float32, device="cuda")
+    part = torch.empty(B.gpt_stage_op_colsum_scratch_bytes(M, N), dtype=torch.uint8, device="cuda")
+    B.gpt_stage_op_colsum(dt, M, N, B.to_device(A, dtype), out, part)
+    assert max_norm_err(B.to_host(out), A.astype(np.float64).sum(0) + 3.0) <= 1e-5
+
+
+@pytest.mark.parametrize("dtype,Bn,S,a,d", [("fp32", 2, 64, 4, 32), ("fp32", 1, 97, 2, 64), ("bf16", 2, 256, 3, 64),
+                                            ("bf16", 1, 384, 2, 128), ("bf16", 1, 1, 2, 64), ("fp32", 1, 130, 1, 128)])
+def test_op_attention(dtype, Bn, S, a, d):
+    print(f"[case] attention {dtype} B={Bn} S={S} a={a} d={d}", flush=True)
+    dt = B.GPTS_BF16 if dtype == "bf16" else B.GPTS_FP32
+    tol = TOL[dtype]
+    P = a * d
+    qkv = synth.to_storage(synth.make_aux(3, 1, (Bn, S, 3 * P)), dtype)
+    dout = synth.to_storage(synth.make_aux(3, 2, (Bn, S, P)), dtype)
+    qd = B.to_device(qkv, dtype)
+    out = torch.empty((Bn, S, P), dtype=qd.dtype, device="cuda")
+    lse = torch.empty((Bn, a, S), dtype=torch.float32, device="cuda")
+    B.gpt_stage_op_attention_fwd(dt, Bn, S, a, d, qd, out, lse)
+    ref = orc.attention_fwd(qkv, a, d)
+    assert max_norm_err(B.to_host(out), ref) <= tol
+    # lse against its definition: log sum_{j<=i} exp(q_i.k_j/sqrt(d))
+    q64 = qkv.astype(np.float64)
+    ref_lse = np.empty((Bn, a, S))
+    for b in range(Bn):
+        for n in range(a):
+            s = q64[b, :, n * d:(n + 1) * d] @ q64[b, :, P + n * d:P + (n + 1) * d].T / np.sqrt(d)
+            s = np.where(np.tril(np.ones((S, S), bool)), s, -np.inf)
+            m = s.max(1)
+            ref_lse[b, n] = m + np.log(np.exp(s - m[:, None]).sum(1))
+    assert np.abs(B.to_host(lse) - ref_lse).max() <= 1e-4 * max(1.0, np.abs(ref_lse).max())
+    dqkv = torch.empty_like(qd)
+    delta = torch.empty_like(lse)
+    B.gpt_stage_op_attention_bwd(dt, Bn, S, a, d, qd, out, lse, B.to_device(dout, dtype), dqkv, delta)
+    rd = orc.attention_bwd(qkv, dout, a, d)
+    got = B.to_host(dqkv)
+    for i, nm in enumerate("qkv"):
+        assert max_norm_err(got[..., i * P:(i + 1) * P], rd[..., i * P:(i + 1) * P]) <= tol, f"d{nm}"
