@@ -1,13 +1,372 @@
-// bf16 MFMA matrix products (placeholder until the tiled kernels land: reports
-// every shape as unsupported so the plain FMA path is used).
+// bf16 matrix products on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16,
+// fp32 accumulation) for the three forms the stage needs:
+//   NT  C[M,N]   = A[M,K] B[N,K]^T     forward linears   (both operands K-contiguous)
+//   NN  C[M,N]   = A[M,K] B[K,N]       data gradients    (B is K-major)
+//   TN  Cf[M,N] += A[K,M]^T B[K,N]     weight gradients  (both operands K-major)
+//
+// Design (one workgroup = 4 waves in a 2x2 grid, one BMxBN output tile):
+//  * K is walked in slices of 64.  Each slice of both operands is copied
+//    global -> LDS by the DMA path (global_load_lds_dwordx4: no registers, no
+//    ds_write), double buffered, one barrier per slice.
+//  * The DMA writes 16-byte slots in lane order, so bank-conflict avoidance is
+//    done by choosing WHICH global chunk a lane fetches (an XOR swizzle of the
+//    chunk index), never by padding.
+//  * K-contiguous operands are stored [row][64 k] and fragments are read with
+//    ds_read_b128.  K-major operands are stored as they sit in memory
+//    ([k][rows]) and fragments are read with the transposing LDS load
+//    ds_read_b64_tr_b16, so no operand is ever transposed in HBM.  The order of
+//    k inside a fragment is a free choice as long as both operands agree; it is
+//    chosen per form so the transposing reads hit 8 consecutive k-rows.
+//  * The two MFMA operands are swapped (D = B-fragment x A-fragment), which
+//    makes each lane own 4 consecutive output columns of one row: 8-byte bf16 /
+//    16-byte fp32 global accesses in the epilogue, where bias, GeLU, GeLU',
+//    residual and the fp32 accumulation are fused.
+//  * Workgroup -> tile map: consecutive workgroup ids land on different XCDs, so
+//    ids are first regrouped per XCD and then walked in bands of 4 tile rows to
+//    keep each XCD's L2 working set to a compact patch of the output.
 #include "kernels.hpp"
 
 namespace gpts {
+namespace {
 
-bool gemm_mfma_supported(int, int, int, int) { return false; }
-hipError_t gemm_mfma(int, int, int, int, const void*, const void*, void*, const GemmEpilogue&,
-                     hipStream_t) {
-  return hipErrorNotSupported;
+constexpr int BK = 64;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void* lds_ptr;
+typedef __attribute__((address_space(1))) const void* glb_ptr;
+
+// epilogue kinds
+enum { EPI_BIAS_RES = 0, EPI_GELU_TANH, EPI_GELU_ERF, EPI_PLAIN, EPI_DGELU_TANH, EPI_DGELU_ERF, EPI_ACCUM };
+
+struct MfmaArgs {
+  const bf16* A;
+  const bf16* B;
+  void* C;
+  int M, N, K;
+  const bf16* bias;
+  const bf16* residual;
+  bf16* gelu_out;
+  const bf16* dgelu_u;
+};
+
+// 16-byte chunk swizzle of a K-contiguous tile row (8 chunks per 128-byte row).
+__device__ __forceinline__ int swz_kc(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+// 32-byte unit swizzle of a K-major tile row, as a function of the k-row.
+template <bool NAT> __device__ __forceinline__ int swz_km(int k) {
+  return ((k & 3) << 1) | ((NAT ? (k >> 3) : (k >> 2)) & 1);
+}
+// k (within a 16-wide MFMA step) held in element 4t+j of the fragment of k-group kg.
+// NAT: the order a K-contiguous 16-byte read gives (8kg + 4t + j); otherwise 8t + 4kg + j.
+template <bool NAT> __device__ __forceinline__ int kperm(int kg, int t, int j) {
+  return NAT ? 8 * kg + 4 * t + j : 8 * t + 4 * kg + j;
+}
+
+// Per-lane state of one operand: global offsets for the DMA and LDS offsets for
+// the fragment reads.  R = tile rows (BM or BN), WR = rows per wave, KMAJOR as above.
+template <int R, int WR, bool KMAJOR, bool NAT> struct Operand {
+  static constexpr int NI = R / 32;       // DMA instructions per wave and slice
+  static constexpr int TILES = WR / 32;   // 32-row MFMA sub-tiles per wave
+  static constexpr int ROWB = R * 2;      // bytes per k-row of a K-major tile
+  uint32_t goff[NI];                      // element offset of this lane's chunk, slice 0
+  uint32_t rd[KMAJOR ? 2 * TILES : 4];    // LDS read offsets (see frag())
+  uint32_t rdbase;
+
+  __device__ __forceinline__ void init(int r0, int rtotal, size_t ld, int wave, int lane, int wr0) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int ii = wave * NI + i;
+      if constexpr (!KMAJOR) {
+        const int row = ii * 8 + (lane >> 3);
+        const int chunk = (lane & 7) ^ swz_kc(row);
+        int gr = r0 + row;
+        gr = gr < rtotal ? gr : rtotal - 1;
+        goff[i] = (uint32_t)((size_t)gr * ld + chunk * 8);
+      } else {
+        const int byte = (ii * 64 + lane) * 16;
+        const int k = byte / ROWB, wb = byte % ROWB;
+        const int u = (wb >> 5) ^ swz_km<NAT>(k);
+        const int col = u * 16 + ((wb >> 4) & 1) * 8;
+        const int gc = (r0 + col < rtotal) ? r0 + col : 0;
+        goff[i] = (uint32_t)((size_t)k * ld + gc);
+      }
+    }
+    if constexpr (!KMAJOR) {
+      const int row = wr0 + (lane & 31);
+      rdbase = row * 128;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) rd[ks] = ((2 * ks + (lane >> 5)) ^ swz_kc(row)) << 4;
+    } else {
+      const int g = lane >> 4, i = lane & 15, mh = g & 1, kg = g >> 1, j = i >> 2, q = i & 3;
+      rdbase = q * 8;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int k = kperm<NAT>(kg, t, j);
+#pragma unroll
+        for (int rb = 0; rb < TILES; ++rb) {
+          const int u = (wr0 >> 4) + rb * 2 + mh;
+          rd[t * TILES + rb] = k * ROWB + ((u ^ swz_km<NAT>(k)) << 5);
+        }
+      }
+    }
+  }
+
+  // enqueue the DMA of slice `kt` into `tile`
+  __device__ __forceinline__ void issue(const bf16* __restrict__ X, size_t ld, int kt, char* tile,
+                                        int wave) const {
+    const bf16* base = KMAJOR ? X + (size_t)kt * BK * ld : X + (size_t)kt * BK;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      __builtin_amdgcn_global_load_lds((glb_ptr)(base + goff[i]),
+                                       (lds_ptr)(tile + (wave * NI + i) * 1024), 16, 0, 0);
+    }
+  }
+
+  // fragment of sub-tile rb for MFMA step ks (16 k): 8 bf16 per lane
+  __device__ __forceinline__ bf16x8 frag(const char* tile, int rb, int ks) const {
+    if constexpr (!KMAJOR) {
+      return *reinterpret_cast<const bf16x8*>(tile + rdbase + rb * 4096 + rd[ks]);
+    } else {
+      const char* p = tile + rdbase + ks * 16 * ROWB;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (s16x4 __attribute__((address_space(3)))*)(p + rd[rb]));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (s16x4 __attribute__((address_space(3)))*)(p + rd[TILES + rb]));
+      typedef short s16x8 __attribute__((ext_vector_type(8)));
+      const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      return __builtin_bit_cast(bf16x8, v);
+    }
+  }
+};
+
+// Scheduling hint for one MFMA step: spread the LDS reads that fetch the next
+// step's fragments (and, with N_DMA > 0, the DMA instructions of a later slice)
+// between the MFMAs of the current step, one read after each of the first MFMAs.
+// (mask 0x008 = MFMA, 0x100 = DS read, 0x020 = VMEM read)
+template <int N_PAIR, int N_DS, int N_MMA, int N_DMA, int I = 0>
+__device__ __forceinline__ void sched_pairs() {
+  if constexpr (I < N_PAIR) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, I == N_PAIR - 1 ? N_DS - N_PAIR + 1 : 1, 0);
+    if constexpr (N_DMA > 0)
+      __builtin_amdgcn_sched_group_barrier(0x020, N_DMA / N_PAIR + (I < N_DMA % N_PAIR ? 1 : 0), 0);
+    sched_pairs<N_PAIR, N_DS, N_MMA, N_DMA, I + 1>();
+  } else if constexpr (N_MMA > N_PAIR) {
+    __builtin_amdgcn_sched_group_barrier(0x008, N_MMA - N_PAIR, 0);
+  }
+}
+
+template <int BM, int BN, bool A_KMAJOR, bool B_KMAJOR, int EPI>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(const MfmaArgs a) {
+  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+  // k order inside fragments: natural unless both operands are K-major
+  constexpr bool NAT = !(A_KMAJOR && B_KMAJOR);
+  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+  __shared__ __attribute__((aligned(1024))) char lds[2 * (A_BYTES + B_BYTES)];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform (SGPR)
+  const int wm = wave >> 1, wn = wave & 1;
+
+  // ---- workgroup -> tile --------------------------------------------------------
+  const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+  const int nb = tiles_m * tiles_n;
+  int id = blockIdx.x;
+  if ((nb & 7) == 0) id = (id & 7) * (nb >> 3) + (id >> 3);  // contiguous range per XCD
+  constexpr int GROUP = 4;
+  const int per_group = GROUP * tiles_n;
+  const int grp = id / per_group, first_m = grp * GROUP;
+  const int gsz = min(tiles_m - first_m, GROUP);
+  const int tm_i = first_m + (id % per_group) % gsz, tn_i = (id % per_group) / gsz;
+  const int m0 = tm_i * BM, n0 = tn_i * BN;
+
+  const size_t lda = A_KMAJOR ? (size_t)a.M : (size_t)a.K;
+  const size_t ldb = B_KMAJOR ? (size_t)a.N : (size_t)a.K;
+  Operand<BM, WM, A_KMAJOR, NAT> opA;
+  Operand<BN, WN, B_KMAJOR, NAT> opB;
+  opA.init(m0, a.M, lda, wave, lane, wm * WM);
+  opB.init(n0, a.N, ldb, wave, lane, wn * WN);
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int nk = a.K / BK;
+  constexpr int STAGE = A_BYTES + B_BYTES;  // one slice of both operands
+  // LDS reads per MFMA step and how many MFMAs to pair with each in the schedule
+  constexpr int N_DS = (A_KMAJOR ? 2 : 1) * TM + (B_KMAJOR ? 2 : 1) * TN;
+  constexpr int N_MMA = TM * TN;
+
+  auto load_frags = [&](bf16x8(&fa)[TM], bf16x8(&fb)[TN], const char* stage, int ks) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[i] = opA.frag(stage, i, ks);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[j] = opB.frag(stage + A_BYTES, j, ks);
+  };
+  auto mma = [&](const bf16x8(&fa)[TM], const bf16x8(&fb)[TN]) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+  };
+  // Ask the scheduler to spread the LDS reads of the next step between the MFMAs
+  // of the current one (mask 0x100 = DS read, 0x008 = MFMA, 0x020 = VMEM read).
+  constexpr int N_PAIR = N_DS < N_MMA ? N_DS : N_MMA;  // (MFMA, DS read) pairs per step
+  constexpr int N_DMA = (BM + BN) / 32;                // DMA instructions per wave and slice
+  auto sched_compute = [&]() { sched_pairs<N_PAIR, N_DS, N_MMA, 0>(); };
+  auto sched_compute_dma = [&]() { sched_pairs<N_PAIR, N_DS, N_MMA, N_DMA>(); };
+
+  // Software pipeline.  Invariant at the top of iteration kt: slice kt is complete
+  // in stage kt&1, the DMA of slice kt+1 is in flight into the other stage, and F0
+  // holds the fragments of (slice kt, step 0).
+  opA.issue(a.A, lda, 0, lds, wave);
+  opB.issue(a.B, ldb, 0, lds + A_BYTES, wave);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  // (slice indices past the end are clamped: the copy is redundant but keeps the
+  // loop body free of branches)
+  opA.issue(a.A, lda, min(1, nk - 1), lds + STAGE, wave);
+  opB.issue(a.B, ldb, min(1, nk - 1), lds + STAGE + A_BYTES, wave);
+  bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+  load_frags(fa0, fb0, lds, 0);
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    const char* st = lds + cur * STAGE;
+    load_frags(fa1, fb1, st, 1);
+    mma(fa0, fb0);
+    sched_compute();
+    load_frags(fa0, fb0, st, 2);
+    mma(fa1, fb1);
+    sched_compute();
+    load_frags(fa1, fb1, st, 3);
+    mma(fa0, fb0);
+    sched_compute();
+    // Every wave now holds its last fragments of this stage in registers; once the
+    // DMA of the next slice has landed the stage can be recycled.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    const int nxt = min(kt + 2, nk - 1);
+    opA.issue(a.A, lda, nxt, lds + cur * STAGE, wave);
+    opB.issue(a.B, ldb, nxt, lds + cur * STAGE + A_BYTES, wave);
+    load_frags(fa0, fb0, lds + (cur ^ 1) * STAGE, 0);
+    mma(fa1, fb1);
+    sched_compute_dma();
+  }
+  // no DMA may still be writing LDS when the workgroup retires
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+  // ---- epilogue: lane owns row m = ..+(lane&31), columns n = ..+8g+4(lane>>5)+0..3 ----
+  const int mrow = m0 + wm * WM + (lane & 31);
+  const int ncol = n0 + wn * WN + (lane >> 5) * 4;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int m = mrow + i * 32;
+    if (m >= a.M) continue;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int n = ncol + j * 32 + g * 8;
+        if (n >= a.N) continue;
+        const size_t o = (size_t)m * a.N + n;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e];
+        if constexpr (EPI == EPI_ACCUM) {
+          float* C = static_cast<float*>(a.C);
+          f32x4 c = *reinterpret_cast<const f32x4*>(C + o);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) c[e] += v[e];
+          *reinterpret_cast<f32x4*>(C + o) = c;
+        } else {
+          bf16* C = static_cast<bf16*>(a.C);
+          if constexpr (EPI == EPI_BIAS_RES || EPI == EPI_GELU_TANH || EPI == EPI_GELU_ERF) {
+            if (a.bias) {
+              const bf16x4 b = *reinterpret_cast<const bf16x4*>(a.bias + n);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) v[e] += (float)b[e];
+            }
+          }
+          if constexpr (EPI == EPI_GELU_TANH || EPI == EPI_GELU_ERF) {
+            bf16x4 u, gq;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              u[e] = (bf16)v[e];
+              gq[e] = (bf16)gelu_f<EPI == EPI_GELU_TANH ? 0 : 1>(v[e]);
+            }
+            *reinterpret_cast<bf16x4*>(C + o) = u;
+            *reinterpret_cast<bf16x4*>(a.gelu_out + o) = gq;
+          } else {
+            if constexpr (EPI == EPI_DGELU_TANH || EPI == EPI_DGELU_ERF) {
+              const bf16x4 u = *reinterpret_cast<const bf16x4*>(a.dgelu_u + o);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f<EPI == EPI_DGELU_TANH ? 0 : 1>((float)u[e]);
+            }
+            if constexpr (EPI == EPI_BIAS_RES) {
+              if (a.residual) {
+                const bf16x4 r = *reinterpret_cast<const bf16x4*>(a.residual + o);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] += (float)r[e];
+              }
+            }
+            bf16x4 out;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) out[e] = (bf16)v[e];
+            *reinterpret_cast<bf16x4*>(C + o) = out;
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, bool AK, bool BKM, int EPI>
+hipError_t launch(const MfmaArgs& a, hipStream_t st) {
+  const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+  hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, AK, BKM, EPI>), dim3(tiles), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+// Tile choice: 256x256 when that still gives every CU a tile (or the matrix is
+// huge), else 128x128 to recover occupancy on small problems.
+template <bool AK, bool BKM, int EPI> hipError_t pick_tile(const MfmaArgs& a, hipStream_t st) {
+  const long t256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
+  if (t256 >= 200) return launch<256, 256, AK, BKM, EPI>(a, st);
+  return launch<128, 128, AK, BKM, EPI>(a, st);
+}
+
+}  // namespace
+
+bool gemm_mfma_supported(int form, int M, int N, int K) {
+  (void)form;
+  return M >= 64 && N >= 64 && K >= 64 && M % 8 == 0 && N % 8 == 0 && K % BK == 0 &&
+         (size_t)M * K < (1ull << 32) && (size_t)N * K < (1ull << 32);
+}
+
+hipError_t gemm_mfma(int form, int M, int N, int K, const void* A, const void* B, void* C,
+                     const GemmEpilogue& ep, hipStream_t st) {
+  MfmaArgs a;
+  a.A = (const bf16*)A; a.B = (const bf16*)B; a.C = C;
+  a.M = M; a.N = N; a.K = K;
+  a.bias = (const bf16*)ep.bias; a.residual = (const bf16*)ep.residual;
+  a.gelu_out = (bf16*)ep.gelu_out; a.dgelu_u = (const bf16*)ep.dgelu_u;
+  if (form == 0) {
+    if (ep.gelu_out)
+      return ep.gelu_kind == 0 ? pick_tile<false, false, EPI_GELU_TANH>(a, st)
+                               : pick_tile<false, false, EPI_GELU_ERF>(a, st);
+    return pick_tile<false, false, EPI_BIAS_RES>(a, st);
+  }
+  if (form == 1) {
+    if (ep.dgelu_u)
+      return ep.gelu_kind == 0 ? pick_tile<false, true, EPI_DGELU_TANH>(a, st)
+                               : pick_tile<false, true, EPI_DGELU_ERF>(a, st);
+    return pick_tile<false, true, EPI_PLAIN>(a, st);
+  }
+  return pick_tile<true, true, EPI_ACCUM>(a, st);
 }
 
 }  // namespace gpts

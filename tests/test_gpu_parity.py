@@ -168,7 +168,8 @@ def test_op_layernorm(dtype, T, H):
 
 
 GEMM_SHAPES = [(64, 64, 64), (200, 136, 72), (256, 256, 256), (320, 448, 192), (512, 1024, 320),
-               (1024, 768, 2048)]
+               (1024, 768, 2048),
+               (3904, 3392, 192)]   # large enough for the 256x256 tiles, ragged last tile in M and N
 
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
