@@ -110,6 +110,15 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
     return t.data_ptr()
 
 
+def _event(ev: Optional[torch.cuda.Event]) -> Optional[int]:
+    if ev is None:
+        return None
+    h = ev.cuda_event
+    if not h:
+        raise ValueError("torch.cuda.Event has no hipEvent yet: record it once before passing it")
+    return h
+
+
 def _stream(stream: Optional[torch.cuda.Stream]) -> int:
     s = stream if stream is not None else torch.cuda.current_stream()
     return s.cuda_stream
@@ -181,14 +190,14 @@ def gpt_stage_bwd(cfg, weights, workspace, act_stash, dy, dx, dparams, stream=No
 def gpt_stage_fwd_only(cfg, weights, workspace, x, act_stash, y, stream=None,
                        done_event: Optional[torch.cuda.Event] = None) -> None:
     p = _params(cfg, weights, workspace)
-    ev = done_event.cuda_event if done_event is not None else None
+    ev = _event(done_event)
     _check(lib().gpt_stage_fwd_only(C.byref(p), _ptr(x), _ptr(act_stash), _ptr(y), _stream(stream), ev))
 
 
 def gpt_stage_bwd_only(cfg, weights, workspace, act_stash, dy, dx, dparams, stream=None,
                        wait_event: Optional[torch.cuda.Event] = None) -> None:
     p = _params(cfg, weights, workspace)
-    ev = wait_event.cuda_event if wait_event is not None else None
+    ev = _event(wait_event)
     _check(lib().gpt_stage_bwd_only(C.byref(p), _ptr(act_stash), _ptr(dy), _ptr(dx), _ptr(dparams),
                                     _stream(stream), ev))
 

@@ -22,6 +22,8 @@ class StageRunner:
         self.fwd_stream = torch.cuda.Stream()
         self.bwd_stream = torch.cuda.Stream()
         self.event = torch.cuda.Event()
+        # torch creates the underlying hipEvent lazily, on the first record
+        self.event.record(self.fwd_stream)
 
     def coupled(self, xs: Sequence[torch.Tensor], dys: Sequence[torch.Tensor],
                 ys: Sequence[torch.Tensor], dxs: Sequence[torch.Tensor],

@@ -74,6 +74,37 @@ def test_microbatch_accumulation_and_decoupled_schedule():
     _report(shape.name, compare(shape, b, oracle_run(shape, params, xs, dys)))
 
 
+def test_backward_stream_waits_for_the_forward_event():
+    """The forward stream is held back by a long spin kernel; the backward stream
+    must still see a complete stash because bwd_only waits on the event that the
+    last fwd_only records.  Without that wait it would read the zero-filled stash."""
+    from paper_2507_19845_amd import harness
+    shape = W[1].with_(name="bf16_evt", n_layers=1, hidden=256, n_heads=4, head_dim=64, ffn=512,
+                       seq=128, batch=1, bias_std=0.02)
+    print(f"[case] event plumbing {shape}", flush=True)
+    params, xs, dys = _inputs(shape, n_mb=2)
+    ref = gpu_run(shape, params, xs, dys, decoupled=False)
+    bufs = B.StageBuffers(shape, n_stash=2)
+    bufs.load_params(params)
+    for s_ in bufs.stash:
+        s_.zero_()
+    xd = [B.to_device(x, shape.dtype) for x in xs]
+    dyd = [B.to_device(d, shape.dtype) for d in dys]
+    ys, dxs = [bufs.act() for _ in xs], [bufs.act() for _ in xs]
+    runner = harness.StageRunner(bufs)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(runner.fwd_stream):
+        torch.cuda._sleep(400_000_000)          # ~0.2 s of spinning ahead of the forwards
+    runner.decoupled(xd, dyd, ys, dxs)
+    torch.cuda.synchronize()
+    for i in range(2):
+        assert np.array_equal(B.to_host(ys[i]), ref[0][i])
+        assert np.array_equal(B.to_host(dxs[i]), ref[1][i])
+    for ga, gb in zip(bufs.read_grads(), ref[2]):
+        for k in ga:
+            assert np.array_equal(ga[k], gb[k]), k
+
+
 def test_run_to_run_bitwise_determinism():
     shape = W[1].with_(name="bf16_det", n_layers=1, hidden=256, n_heads=4, head_dim=64, ffn=512,
                        seq=256, batch=2)
