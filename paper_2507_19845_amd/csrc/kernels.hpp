@@ -40,4 +40,11 @@ hipError_t attention_bwd_simple(int dtype, int B, int S, int a, int d, const voi
                                 const void* out, const float* lse, const void* dout, void* dqkv,
                                 float* delta, hipStream_t st);
 
+// bf16 MFMA attention (head_dim 64 or 128).
+hipError_t attention_fwd_mfma(int B, int S, int a, int d, const void* qkv, void* out, float* lse,
+                              hipStream_t st);
+hipError_t attention_bwd_mfma(int B, int S, int a, int d, const void* qkv, const void* out,
+                              const float* lse, const void* dout, void* dqkv, float* delta,
+                              hipStream_t st);
+
 }  // namespace gpts

@@ -130,6 +130,20 @@ hipError_t gemm(int dtype, int form, int M, int N, int K, const void* A, const v
   return gemm_simple(dtype, form, M, N, K, A, B, C, ep, st);
 }
 
+// Attention: MFMA kernels for bf16 with head_dim 64/128, the plain FMA kernels otherwise.
+hipError_t attention_fwd(int dtype, int B, int S, int a, int d, const void* qkv, void* out,
+                         float* lse, hipStream_t st) {
+  if (dtype == GPTS_BF16 && (d == 64 || d == 128)) return attention_fwd_mfma(B, S, a, d, qkv, out, lse, st);
+  return attention_fwd_simple(dtype, B, S, a, d, qkv, out, lse, st);
+}
+hipError_t attention_bwd(int dtype, int B, int S, int a, int d, const void* qkv, const void* out,
+                         const float* lse, const void* dout, void* dqkv, float* delta,
+                         hipStream_t st) {
+  if (dtype == GPTS_BF16 && (d == 64 || d == 128))
+    return attention_bwd_mfma(B, S, a, d, qkv, out, lse, dout, dqkv, delta, st);
+  return attention_bwd_simple(dtype, B, S, a, d, qkv, out, lse, dout, dqkv, delta, st);
+}
+
 int check_call(const gpt_stage_params* p) {
   if (!p) return fail(GPTS_EINVAL, "params is NULL");
   int rc = gpt_stage_validate(&p->cfg);
@@ -167,7 +181,7 @@ int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, 
     GemmEpilogue ep;
     ep.bias = w(l, GPTS_B_QKV);
     GPTS_TRY(gemm(dt, 0, D.T, 3 * D.P, D.H, s + sl.A, w(l, GPTS_W_QKV), s + sl.QKV, ep, st), "qkv gemm");
-    GPTS_TRY(attention_fwd_simple(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
+    GPTS_TRY(attention_fwd(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
                                   reinterpret_cast<float*>(s + sl.LSE), st), "attention fwd");
     ep = GemmEpilogue();
     ep.bias = w(l, GPTS_B_O);
@@ -243,7 +257,7 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     GPTS_TRY(gemm(dt, 2, D.H, D.P, D.T, dX1, s + sl.C, g(l, GPTS_W_O), none, st), "out-proj wgrad");
     GPTS_TRY(colsum(dt, D.T, D.H, dX1, g(l, GPTS_B_O), cs_part, st), "out-proj bias grad");
     // c = attention(qkv)
-    GPTS_TRY(attention_bwd_simple(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
+    GPTS_TRY(attention_bwd(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
                                   reinterpret_cast<const float*>(s + sl.LSE), dC, dQKV, delta, st),
              "attention bwd");
     // qkv = a Wqkv^T + bqkv
@@ -399,7 +413,7 @@ int gpt_stage_op_attention_fwd(int dtype, int B, int S, int n_heads, int head_di
   if (!op_dtype_ok(dtype) || !qkv || !out || !lse) return fail(GPTS_EINVAL, "attention_fwd: bad argument");
   if (B < 1 || S < 1 || n_heads < 1 || (head_dim != 32 && head_dim != 64 && head_dim != 128))
     return fail(GPTS_ESHAPE, "attention_fwd: head_dim must be 32, 64 or 128");
-  GPTS_TRY(attention_fwd_simple(dtype, B, S, n_heads, head_dim, qkv, out, lse, static_cast<hipStream_t>(stream)), "attention_fwd");
+  GPTS_TRY(attention_fwd(dtype, B, S, n_heads, head_dim, qkv, out, lse, static_cast<hipStream_t>(stream)), "attention_fwd");
   return GPTS_OK;
 }
 int gpt_stage_op_attention_bwd(int dtype, int B, int S, int n_heads, int head_dim, const void* qkv,
@@ -408,7 +422,7 @@ int gpt_stage_op_attention_bwd(int dtype, int B, int S, int n_heads, int head_di
   if (!op_dtype_ok(dtype) || !qkv || !out || !lse || !dout || !dqkv || !delta) return fail(GPTS_EINVAL, "attention_bwd: bad argument");
   if (B < 1 || S < 1 || n_heads < 1 || (head_dim != 32 && head_dim != 64 && head_dim != 128))
     return fail(GPTS_ESHAPE, "attention_bwd: head_dim must be 32, 64 or 128");
-  GPTS_TRY(attention_bwd_simple(dtype, B, S, n_heads, head_dim, qkv, out, lse, dout, dqkv, delta,
+  GPTS_TRY(attention_bwd(dtype, B, S, n_heads, head_dim, qkv, out, lse, dout, dqkv, delta,
                                 static_cast<hipStream_t>(stream)), "attention_bwd");
   return GPTS_OK;
 }

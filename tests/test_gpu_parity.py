@@ -250,7 +250,9 @@ def test_op_colsum(dtype, M, N):
 
 
 @pytest.mark.parametrize("dtype,Bn,S,a,d", [("fp32", 2, 64, 4, 32), ("fp32", 1, 97, 2, 64), ("bf16", 2, 256, 3, 64),
-                                            ("bf16", 1, 384, 2, 128), ("bf16", 1, 1, 2, 64), ("fp32", 1, 130, 1, 128)])
+                                            ("bf16", 1, 384, 2, 128), ("bf16", 1, 1, 2, 64), ("fp32", 1, 130, 1, 128),
+                                            ("bf16", 2, 1000, 2, 128), ("bf16", 1, 777, 3, 64), ("bf16", 1, 2048, 1, 128),
+                                            ("bf16", 3, 50, 2, 32)])
 def test_op_attention(dtype, Bn, S, a, d):
     print(f"[case] attention {dtype} B={Bn} S={S} a={a} d={d}", flush=True)
     dt = B.GPTS_BF16 if dtype == "bf16" else B.GPTS_FP32
