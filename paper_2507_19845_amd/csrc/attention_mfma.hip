@@ -54,6 +54,7 @@ __device__ __forceinline__ void dma_tile(const bf16* __restrict__ src, size_t ld
   constexpr int ROWB = D * 2;              // bytes per row
   constexpr int CPR = ROWB / 16;           // chunks per row
   constexpr int NI = BKV * ROWB / 1024 / 4;  // instructions per wave
+  const uint32_t lds_tile = (uint32_t)(size_t)(__attribute__((address_space(3))) char*)tile;
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
     const int slot = (wave * NI + i) * 64 + lane;
@@ -61,8 +62,14 @@ __device__ __forceinline__ void dma_tile(const bf16* __restrict__ src, size_t ld
     const int c = pc ^ swz16(r);
     int gr = row0 + r;
     gr = gr < S ? gr : S - 1;
-    __builtin_amdgcn_global_load_lds((glb_ptr)(src + (size_t)gr * ld + c * 8),
-                                     (lds_ptr)(tile + (wave * NI + i) * 1024), 16, 0, 0);
+    // Inline assembly on purpose: the compiler does not track these copies, so it does
+    // not drain them in front of every transposing LDS read; the kernels wait for them
+    // explicitly (s_waitcnt vmcnt(0)) before the barrier that publishes a tile.
+    const uint32_t off = (uint32_t)(((size_t)gr * ld + c * 8) * 2);
+    const uint32_t dst = lds_tile + (wave * NI + i) * 1024;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 ::"s"(dst), "v"(off), "s"(src)
+                 : "memory");
   }
 }
 
@@ -126,8 +133,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
   dma_tile<D>(base + 2 * P, ld, 0, S, lds + TILE, wave, lane);
 
   for (int kt = 0; kt < nkv; ++kt) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     const int k0 = kt * BKV;
     const char* tK = lds + (kt & 1) * 2 * TILE;
     const char* tV = tK + TILE;
@@ -323,8 +329,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(
 
   for (int qt = qt0; qt < nq; ++qt) {
     const int stage = (qt - qt0) & 1;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     const char* tQ = lds + stage * 2 * TILE;
     const char* tO = tQ + TILE;
     if (qt + 1 < nq) {
@@ -459,8 +464,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
   dma_tile<D>(base + 2 * P, ld, 0, S, lds + TILE, wave, lane);
 
   for (int kt = 0; kt < nkv; ++kt) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     const int k0 = kt * BKV;
     const char* tK = lds + (kt & 1) * 2 * TILE;
     const char* tV = tK + TILE;

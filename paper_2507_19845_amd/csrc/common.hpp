@@ -70,26 +70,27 @@ template <int NW> __device__ __forceinline__ float block_sum(float v, float* red
 }
 
 // ---- GeLU (fp32 evaluation) -----------------------------------------------------
-// tanh form: 0.5 u (1 + tanh(k (u + 0.044715 u^3))), k = sqrt(2/pi); erf form: u Phi(u).
-__device__ __forceinline__ float tanh_fast(float z) {
-  // tanh z = 1 - 2/(exp(2z)+1); exact limits at +-inf, abs error ~1e-7
-  const float e = __expf(2.f * z);
-  return 1.f - 2.f / (e + 1.f);
+// tanh form: 0.5 u (1 + tanh z), z = k (u + 0.044715 u^3), k = sqrt(2/pi).  Since
+// 0.5 (1 + tanh z) = sigma(2z) (logistic function) it is evaluated as u * sigma(2z)
+// with one hardware exp2 and one hardware reciprocal.  erf form: u Phi(u).
+__device__ __forceinline__ float sigmoid2z(float u) {
+  // sigma(2z) = 1 / (1 + 2^(-2 z log2 e)); exact limits 0 and 1 for large |u|
+  const float z2 = (-2.f * 0.7978845608028654f * 1.4426950408889634f) * (u + 0.044715f * u * u * u);
+  return __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(z2));
 }
 template <int KIND> __device__ __forceinline__ float gelu_f(float u) {
   if constexpr (KIND == 0) {
-    const float z = 0.7978845608028654f * (u + 0.044715f * u * u * u);
-    return 0.5f * u * (1.f + tanh_fast(z));
+    return u * sigmoid2z(u);
   } else {
     return 0.5f * u * (1.f + erff(u * 0.7071067811865476f));
   }
 }
 template <int KIND> __device__ __forceinline__ float gelu_grad_f(float u) {
   if constexpr (KIND == 0) {
-    const float z = 0.7978845608028654f * (u + 0.044715f * u * u * u);
-    const float t = tanh_fast(z);
-    return 0.5f * (1.f + t) +
-           0.5f * u * (1.f - t * t) * 0.7978845608028654f * (1.f + 3.f * 0.044715f * u * u);
+    // d/du [u sigma(2z)] = sigma + u sigma (1 - sigma) 2 z'(u),  z' = k (1 + 3*0.044715 u^2)
+    const float s = sigmoid2z(u);
+    const float dz2 = (2.f * 0.7978845608028654f) * (1.f + 3.f * 0.044715f * u * u);
+    return s + u * s * (1.f - s) * dz2;
   } else {
     const float cdf = 0.5f * (1.f + erff(u * 0.7071067811865476f));
     const float pdf = 0.3989422804014327f * __expf(-0.5f * u * u);

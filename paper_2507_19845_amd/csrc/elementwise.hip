@@ -146,15 +146,28 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(
   }
 }
 
-// out[n] += sum_{g<G} partial[g*stride + n]  (g ascending: deterministic)
+// out[c] += sum_{g<G} partial[g*stride + c] for c < N0 (into out0) and N0 <= c < N
+// (into out1[c-N0]).  32 columns x 8 row groups per workgroup; the row groups are
+// combined through LDS in fixed order, so the result is deterministic.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial,
-                                                              float* __restrict__ out, int G,
-                                                              size_t stride, int N) {
-  const int n = blockIdx.x * blockDim.x + threadIdx.x;
-  if (n >= N) return;
+                                                              float* __restrict__ out0,
+                                                              float* __restrict__ out1, int G,
+                                                              size_t stride, int N0, int N) {
+  __shared__ float sm[8][32];
+  const int cx = threadIdx.x & 31, ry = threadIdx.x >> 5;
+  const int c = blockIdx.x * 32 + cx;
   float s = 0.f;
-  for (int g = 0; g < G; ++g) s += partial[(size_t)g * stride + n];
-  out[n] += s;
+  if (c < N)
+    for (int g = ry; g < G; g += 8) s += partial[(size_t)g * stride + c];
+  sm[ry][cx] = s;
+  __syncthreads();
+  if (ry == 0 && c < N) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t += sm[i][cx];
+    if (c < N0) out0[c] += t;
+    else out1[c - N0] += t;
+  }
 }
 
 // ----------------------------------------------------------------- colsum ----
@@ -218,7 +231,7 @@ hipError_t ln_fwd(int dtype, int T_rows, int H, float eps, const void* x, const 
                         (bf16*)out, mean, rstd, st);
 }
 
-int ln_bwd_blocks(int T_rows) { return T_rows < 512 ? T_rows : 512; }
+int ln_bwd_blocks(int T_rows) { return T_rows < 256 ? T_rows : 256; }
 
 template <typename T>
 static hipError_t ln_bwd_t(int T_rows, int H, const T* dout, const T* x, const float* mean,
@@ -239,9 +252,8 @@ static hipError_t ln_bwd_t(int T_rows, int H, const T* dout, const T* x, const f
 #undef GPTS_LN_BWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  dim3 rg((H + 255) / 256), rb(256);
-  hipLaunchKernelGGL(reduce_partials_kernel, rg, rb, 0, st, partial, dgamma, G, (size_t)2 * H, H);
-  hipLaunchKernelGGL(reduce_partials_kernel, rg, rb, 0, st, partial + H, dbeta, G, (size_t)2 * H, H);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * H + 31) / 32), dim3(256), 0, st, partial, dgamma,
+                     dbeta, G, (size_t)2 * H, H, 2 * H);
   return hipGetLastError();
 }
 
@@ -274,8 +286,8 @@ hipError_t colsum(int dtype, int M, int N, const void* A, float* out, float* par
     hipLaunchKernelGGL(colsum_partial_kernel<bf16>, g, b, 0, st, (const bf16*)A, partial, M, N);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((N + 255) / 256), dim3(256), 0, st, partial, out,
-                     G, (size_t)N, N);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((N + 31) / 32), dim3(256), 0, st, partial, out,
+                     (float*)nullptr, G, (size_t)N, N, N);
   return hipGetLastError();
 }
 

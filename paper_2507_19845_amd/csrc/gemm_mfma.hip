@@ -24,12 +24,13 @@
 //  * Workgroup -> tile map: consecutive workgroup ids land on different XCDs, so
 //    ids are first regrouped per XCD and then walked in bands of 4 tile rows to
 //    keep each XCD's L2 working set to a compact patch of the output.
+#include <type_traits>
+
 #include "kernels.hpp"
 
 namespace gpts {
 namespace {
 
-constexpr int BK = 64;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_ptr;
 typedef __attribute__((address_space(1))) const void* glb_ptr;
@@ -48,8 +49,13 @@ struct MfmaArgs {
   const bf16* dgelu_u;
 };
 
-// 16-byte chunk swizzle of a K-contiguous tile row (8 chunks per 128-byte row).
-__device__ __forceinline__ int swz_kc(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+// 16-byte chunk swizzle of a K-contiguous tile row with CPR chunks per row.  Chosen
+// so that 16 consecutive rows read at the same logical chunk hit 16 different
+// (row parity / quarter, chunk) bank groups, for 64- and for 32-bank layouts.
+template <int CPR> __device__ __forceinline__ int swz_kc(int row) {
+  if constexpr (CPR == 8) return (row & 7) ^ ((row >> 3) & 1);
+  else return ((row >> 1) & 3) ^ ((row >> 3) & 1);
+}
 // 32-byte unit swizzle of a K-major tile row, as a function of the k-row.
 template <bool NAT> __device__ __forceinline__ int swz_km(int k) {
   return ((k & 3) << 1) | ((NAT ? (k >> 3) : (k >> 2)) & 1);
@@ -61,39 +67,42 @@ template <bool NAT> __device__ __forceinline__ int kperm(int kg, int t, int j) {
 }
 
 // Per-lane state of one operand: global offsets for the DMA and LDS offsets for
-// the fragment reads.  R = tile rows (BM or BN), WR = rows per wave, KMAJOR as above.
-template <int R, int WR, bool KMAJOR, bool NAT> struct Operand {
-  static constexpr int NI = R / 32;       // DMA instructions per wave and slice
-  static constexpr int TILES = WR / 32;   // 32-row MFMA sub-tiles per wave
-  static constexpr int ROWB = R * 2;      // bytes per k-row of a K-major tile
-  uint32_t goff[NI];                      // element offset of this lane's chunk, slice 0
-  uint32_t rd[KMAJOR ? 2 * TILES : 4];    // LDS read offsets (see frag())
+// the fragment reads.  R = tile rows (BM or BN), WR = rows per wave, BK = slice depth.
+template <int R, int WR, int BK, bool KMAJOR, bool NAT> struct Operand {
+  static constexpr int NI = R * BK / 2048;  // DMA instructions (1 KiB each) per wave and slice
+  static constexpr int TILES = WR / 32;     // 32-row MFMA sub-tiles per wave
+  static constexpr int KS = BK / 16;        // MFMA steps per slice
+  static constexpr int RB = BK * 2;         // bytes per row of a K-contiguous tile
+  static constexpr int CPR = BK / 8;        // 16-byte chunks per such row
+  static constexpr int ROWB = R * 2;        // bytes per k-row of a K-major tile
+  uint32_t goff[NI];                        // byte offset of this lane's chunk, slice 0
+  uint32_t rd[KMAJOR ? 2 * TILES : KS];     // LDS read offsets (see frag())
   uint32_t rdbase;
 
   __device__ __forceinline__ void init(int r0, int rtotal, size_t ld, int wave, int lane, int wr0) {
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-      const int ii = wave * NI + i;
+      const int slot = (wave * NI + i) * 64 + lane;
       if constexpr (!KMAJOR) {
-        const int row = ii * 8 + (lane >> 3);
-        const int chunk = (lane & 7) ^ swz_kc(row);
+        const int row = slot / CPR;
+        const int chunk = (slot % CPR) ^ swz_kc<CPR>(row);
         int gr = r0 + row;
         gr = gr < rtotal ? gr : rtotal - 1;
-        goff[i] = (uint32_t)((size_t)gr * ld + chunk * 8);
+        goff[i] = (uint32_t)(((size_t)gr * ld + chunk * 8) * 2);
       } else {
-        const int byte = (ii * 64 + lane) * 16;
+        const int byte = slot * 16;
         const int k = byte / ROWB, wb = byte % ROWB;
         const int u = (wb >> 5) ^ swz_km<NAT>(k);
         const int col = u * 16 + ((wb >> 4) & 1) * 8;
         const int gc = (r0 + col < rtotal) ? r0 + col : 0;
-        goff[i] = (uint32_t)((size_t)k * ld + gc);
+        goff[i] = (uint32_t)(((size_t)k * ld + gc) * 2);
       }
     }
     if constexpr (!KMAJOR) {
       const int row = wr0 + (lane & 31);
-      rdbase = row * 128;
+      rdbase = row * RB;
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) rd[ks] = ((2 * ks + (lane >> 5)) ^ swz_kc(row)) << 4;
+      for (int ks = 0; ks < KS; ++ks) rd[ks] = ((2 * ks + (lane >> 5)) ^ swz_kc<CPR>(row)) << 4;
     } else {
       const int g = lane >> 4, i = lane & 15, mh = g & 1, kg = g >> 1, j = i >> 2, q = i & 3;
       rdbase = q * 8;
@@ -109,21 +118,30 @@ template <int R, int WR, bool KMAJOR, bool NAT> struct Operand {
     }
   }
 
-  // enqueue the DMA of slice `kt` into `tile`
-  __device__ __forceinline__ void issue(const bf16* __restrict__ X, size_t ld, int kt, char* tile,
-                                        int wave) const {
+  // Enqueue DMA instruction i (a compile-time constant after unrolling) of slice `kt`:
+  // 64 lanes x 16 bytes from X + goff -> 1 KiB of LDS at byte address lds_tile + i*1024
+  // (wave-uniform, passed in M0).  Written as inline assembly on purpose: the compiler
+  // then does not track these copies, so it neither drains them (vmcnt(0)) in front of
+  // LDS reads it cannot prove independent, nor counts them; completion is waited for
+  // explicitly with wait_dma_and_barrier().
+  __device__ __forceinline__ void issue_one(const bf16* __restrict__ X, size_t ld, int kt,
+                                            uint32_t lds_tile, int wave, int i) const {
     const bf16* base = KMAJOR ? X + (size_t)kt * BK * ld : X + (size_t)kt * BK;
+    const uint32_t dst = lds_tile + (wave * NI + i) * 1024;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 ::"s"(dst), "v"(goff[i]), "s"(base)
+                 : "memory");
+  }
+  __device__ __forceinline__ void issue(const bf16* __restrict__ X, size_t ld, int kt, uint32_t lds_tile,
+                                        int wave) const {
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      __builtin_amdgcn_global_load_lds((glb_ptr)(base + goff[i]),
-                                       (lds_ptr)(tile + (wave * NI + i) * 1024), 16, 0, 0);
-    }
+    for (int i = 0; i < NI; ++i) issue_one(X, ld, kt, lds_tile, wave, i);
   }
 
   // fragment of sub-tile rb for MFMA step ks (16 k): 8 bf16 per lane
   __device__ __forceinline__ bf16x8 frag(const char* tile, int rb, int ks) const {
     if constexpr (!KMAJOR) {
-      return *reinterpret_cast<const bf16x8*>(tile + rdbase + rb * 4096 + rd[ks]);
+      return *reinterpret_cast<const bf16x8*>(tile + rdbase + rb * 32 * RB + rd[ks]);
     } else {
       const char* p = tile + rdbase + ks * 16 * ROWB;
       const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
@@ -140,27 +158,37 @@ template <int R, int WR, bool KMAJOR, bool NAT> struct Operand {
 // Scheduling hint for one MFMA step: spread the LDS reads that fetch the next
 // step's fragments (and, with N_DMA > 0, the DMA instructions of a later slice)
 // between the MFMAs of the current step, one read after each of the first MFMAs.
-// (mask 0x008 = MFMA, 0x100 = DS read, 0x020 = VMEM read)
+// (mask 0x008 = MFMA, 0x100 = DS read, 0x010 = any VMEM: the DMA both loads and stores)
 template <int N_PAIR, int N_DS, int N_MMA, int N_DMA, int I = 0>
 __device__ __forceinline__ void sched_pairs() {
   if constexpr (I < N_PAIR) {
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     __builtin_amdgcn_sched_group_barrier(0x100, I == N_PAIR - 1 ? N_DS - N_PAIR + 1 : 1, 0);
-    if constexpr (N_DMA > 0)
-      __builtin_amdgcn_sched_group_barrier(0x020, N_DMA / N_PAIR + (I < N_DMA % N_PAIR ? 1 : 0), 0);
+    if constexpr (((I + 1) * N_DMA) / N_PAIR > (I * N_DMA) / N_PAIR)  // spread evenly
+      __builtin_amdgcn_sched_group_barrier(0x010, ((I + 1) * N_DMA) / N_PAIR - (I * N_DMA) / N_PAIR, 0);
     sched_pairs<N_PAIR, N_DS, N_MMA, N_DMA, I + 1>();
   } else if constexpr (N_MMA > N_PAIR) {
     __builtin_amdgcn_sched_group_barrier(0x008, N_MMA - N_PAIR, 0);
   }
 }
 
-template <int BM, int BN, bool A_KMAJOR, bool B_KMAJOR, int EPI>
+// Wait until at most VM of this wave's DMA instructions are still in flight and all
+// of its LDS reads have returned, then meet the other waves.  (A plain barrier
+// intrinsic would make the compiler drain every outstanding DMA first.)
+template <int VM> __device__ __forceinline__ void wait_dma_and_barrier() {
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::"n"(VM) : "memory");
+}
+
+template <int BM, int BN, int BK, int NS, bool A_KMAJOR, bool B_KMAJOR, int EPI>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(const MfmaArgs a) {
-  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32, KS = BK / 16;
+  static_assert((NS & (NS - 1)) == 0 && KS % 2 == 0, "stages: power of two; even MFMA steps per slice");
   // k order inside fragments: natural unless both operands are K-major
   constexpr bool NAT = !(A_KMAJOR && B_KMAJOR);
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
-  __shared__ __attribute__((aligned(1024))) char lds[2 * (A_BYTES + B_BYTES)];
+  constexpr int STAGE = A_BYTES + B_BYTES;  // one slice of both operands
+  __shared__ __attribute__((aligned(1024))) char lds[NS * STAGE];
+  const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) char*)lds;
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform (SGPR)
@@ -180,8 +208,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const MfmaArgs a) {
 
   const size_t lda = A_KMAJOR ? (size_t)a.M : (size_t)a.K;
   const size_t ldb = B_KMAJOR ? (size_t)a.N : (size_t)a.K;
-  Operand<BM, WM, A_KMAJOR, NAT> opA;
-  Operand<BN, WN, B_KMAJOR, NAT> opB;
+  Operand<BM, WM, BK, A_KMAJOR, NAT> opA;
+  Operand<BN, WN, BK, B_KMAJOR, NAT> opB;
   opA.init(m0, a.M, lda, wave, lane, wm * WM);
   opB.init(n0, a.N, ldb, wave, lane, wn * WN);
 
@@ -194,10 +222,11 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const MfmaArgs a) {
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   const int nk = a.K / BK;
-  constexpr int STAGE = A_BYTES + B_BYTES;  // one slice of both operands
   // LDS reads per MFMA step and how many MFMAs to pair with each in the schedule
   constexpr int N_DS = (A_KMAJOR ? 2 : 1) * TM + (B_KMAJOR ? 2 : 1) * TN;
   constexpr int N_MMA = TM * TN;
+  constexpr int N_PAIR = N_DS < N_MMA ? N_DS : N_MMA;  // (MFMA, DS read) pairs per step
+  constexpr int N_DMA = (BM + BN) * BK / 2048;         // DMA instructions per wave and slice
 
   auto load_frags = [&](bf16x8(&fa)[TM], bf16x8(&fb)[TN], const char* stage, int ks) {
 #pragma unroll
@@ -212,49 +241,93 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const MfmaArgs a) {
       for (int j = 0; j < TN; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
   };
-  // Ask the scheduler to spread the LDS reads of the next step between the MFMAs
-  // of the current one (mask 0x100 = DS read, 0x008 = MFMA, 0x020 = VMEM read).
-  constexpr int N_PAIR = N_DS < N_MMA ? N_DS : N_MMA;  // (MFMA, DS read) pairs per step
-  constexpr int N_DMA = (BM + BN) / 32;                // DMA instructions per wave and slice
-  auto sched_compute = [&]() { sched_pairs<N_PAIR, N_DS, N_MMA, 0>(); };
-  auto sched_compute_dma = [&]() { sched_pairs<N_PAIR, N_DS, N_MMA, N_DMA>(); };
+  // DMA instructions [part*N/PARTS, (part+1)*N/PARTS) of each operand's slice -> stage;
+  // slice indices past the end are clamped: the copy is redundant but keeps the
+  // loop body free of branches.
+  constexpr int NIA = BM * BK / 2048, NIB = BN * BK / 2048;
+  auto issue_all = [&](int slice, int stage) {
+    const int sl = min(slice, nk - 1);
+    opA.issue(a.A, lda, sl, lds_base + stage * STAGE, wave);
+    opB.issue(a.B, ldb, sl, lds_base + stage * STAGE + A_BYTES, wave);
+  };
 
-  // Software pipeline.  Invariant at the top of iteration kt: slice kt is complete
-  // in stage kt&1, the DMA of slice kt+1 is in flight into the other stage, and F0
-  // holds the fragments of (slice kt, step 0).
-  opA.issue(a.A, lda, 0, lds, wave);
-  opB.issue(a.B, ldb, 0, lds + A_BYTES, wave);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-  // (slice indices past the end are clamped: the copy is redundant but keeps the
-  // loop body free of branches)
-  opA.issue(a.A, lda, min(1, nk - 1), lds + STAGE, wave);
-  opB.issue(a.B, ldb, min(1, nk - 1), lds + STAGE + A_BYTES, wave);
   bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-  load_frags(fa0, fb0, lds, 0);
-
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    const char* st = lds + cur * STAGE;
-    load_frags(fa1, fb1, st, 1);
-    mma(fa0, fb0);
-    sched_compute();
-    load_frags(fa0, fb0, st, 2);
-    mma(fa1, fb1);
-    sched_compute();
-    load_frags(fa1, fb1, st, 3);
-    mma(fa0, fb0);
-    sched_compute();
-    // Every wave now holds its last fragments of this stage in registers; once the
-    // DMA of the next slice has landed the stage can be recycled.
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    const int nxt = min(kt + 2, nk - 1);
-    opA.issue(a.A, lda, nxt, lds + cur * STAGE, wave);
-    opB.issue(a.B, ldb, nxt, lds + cur * STAGE + A_BYTES, wave);
-    load_frags(fa0, fb0, lds + (cur ^ 1) * STAGE, 0);
-    mma(fa1, fb1);
-    sched_compute_dma();
+  if constexpr (NS >= 4) {
+    // Deep pipeline: slice t lives in stage t % NS.  At the top of iteration kt slice
+    // kt is complete, slices kt+1 .. kt+NS-2 are in flight and the stage of slice
+    // kt-1 is free: slice kt+NS-1 is fetched into it during this iteration, its DMA
+    // instructions spread evenly between the MFMAs of all steps so that the four
+    // waves never queue up behind each other at the address unit (a wave blocked on
+    // issuing a DMA cannot issue MFMAs either).
+    static_assert(NIA % KS == 0 && NIB % KS == 0, "DMA instructions must split evenly over the steps");
+    constexpr int PA = NIA / KS, PB = NIB / KS, PSTEP = PA + PB;
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) issue_all(s, s);
+    wait_dma_and_barrier<(NS - 2) * N_DMA>();
+    load_frags(fa0, fb0, lds, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+      const char* st = lds + (kt & (NS - 1)) * STAGE;
+      const uint32_t fill = lds_base + ((kt + NS - 1) & (NS - 1)) * STAGE;
+      const int sl = min(kt + NS - 1, nk - 1);
+      // fragment reads of (stage, step ks) with part p of the slice's DMA instructions
+      // woven in between them in program order (the DMA writes LDS, so the compiler
+      // never moves it across an LDS read; the order written here is the order issued)
+      auto load_frags_dma = [&](bf16x8(&fa)[TM], bf16x8(&fb)[TN], const char* stage, int ks, int p) {
+        static_assert(TM % PA == 0 && TN % PB == 0, "fragments per DMA instruction");
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          fa[i] = opA.frag(stage, i, ks);
+          if ((i + 1) % (TM / PA) == 0) opA.issue_one(a.A, lda, sl, fill, wave, p * PA + (i + 1) / (TM / PA) - 1);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          fb[j] = opB.frag(stage + A_BYTES, j, ks);
+          if ((j + 1) % (TN / PB) == 0) opB.issue_one(a.B, ldb, sl, fill + A_BYTES, wave, p * PB + (j + 1) / (TN / PB) - 1);
+        }
+      };
+      if constexpr (KS == 4) {
+        load_frags_dma(fa1, fb1, st, 1, 0); mma(fa0, fb0);
+        sched_pairs<N_PAIR, N_DS, N_MMA, PSTEP>();
+        load_frags_dma(fa0, fb0, st, 2, 1); mma(fa1, fb1);
+        sched_pairs<N_PAIR, N_DS, N_MMA, PSTEP>();
+      }
+      load_frags_dma(fa1, fb1, st, KS - 1, KS - 2); mma(fa0, fb0);
+      sched_pairs<N_PAIR, N_DS, N_MMA, PSTEP>();
+      // slice kt+1 must have landed; younger DMAs may stay in flight
+      wait_dma_and_barrier<(NS - 3) * N_DMA + (KS - 1) * PSTEP>();
+      load_frags_dma(fa0, fb0, lds + ((kt + 1) & (NS - 1)) * STAGE, 0, KS - 1);
+      mma(fa1, fb1);
+      sched_pairs<N_PAIR, N_DS, N_MMA, PSTEP>();
+    }
+  } else {
+    // Two stages: slice kt+2 can only be fetched once every wave has taken its last
+    // fragments of slice kt out of the stage, i.e. after the barrier of iteration kt.
+    static_assert(NS == 2, "2 or >= 4 stages");
+    issue_all(0, 0);
+    issue_all(1, 1);
+    wait_dma_and_barrier<N_DMA>();
+    load_frags(fa0, fb0, lds, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+      const int cur = kt & 1;
+      const char* st = lds + cur * STAGE;
+#pragma unroll
+      for (int ks = 0; ks + 2 < KS; ks += 2) {
+        load_frags(fa1, fb1, st, ks + 1);
+        mma(fa0, fb0);
+        sched_pairs<N_PAIR, N_DS, N_MMA, 0>();
+        load_frags(fa0, fb0, st, ks + 2);
+        mma(fa1, fb1);
+        sched_pairs<N_PAIR, N_DS, N_MMA, 0>();
+      }
+      load_frags(fa1, fb1, st, KS - 1);
+      mma(fa0, fb0);
+      sched_pairs<N_PAIR, N_DS, N_MMA, 0>();
+      wait_dma_and_barrier<0>();
+      issue_all(kt + 2, cur);
+      load_frags(fa0, fb0, lds + (cur ^ 1) * STAGE, 0);
+      mma(fa1, fb1);
+      sched_pairs<N_PAIR, N_DS, N_MMA, N_DMA>();
+    }
   }
   // no DMA may still be writing LDS when the workgroup retires
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -324,27 +397,28 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const MfmaArgs a) {
   }
 }
 
-template <int BM, int BN, bool AK, bool BKM, int EPI>
+template <int BM, int BN, int BK, int NS, bool AK, bool BKM, int EPI>
 hipError_t launch(const MfmaArgs& a, hipStream_t st) {
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-  hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, AK, BKM, EPI>), dim3(tiles), dim3(256), 0, st, a);
+  hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, NS, AK, BKM, EPI>), dim3(tiles), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
-// Tile choice: 256x256 when that still gives every CU a tile (or the matrix is
-// huge), else 128x128 to recover occupancy on small problems.
+// Tile choice: 256x256 (slices of 32, four LDS stages: three slices in flight) when
+// that still gives every CU a tile, else 128x128 (slices of 64, two stages, two
+// workgroups per CU) to recover occupancy on small problems.
 template <bool AK, bool BKM, int EPI> hipError_t pick_tile(const MfmaArgs& a, hipStream_t st) {
   const long t256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
-  if (t256 >= 200) return launch<256, 256, AK, BKM, EPI>(a, st);
-  return launch<128, 128, AK, BKM, EPI>(a, st);
+  if (t256 >= 200) return launch<256, 256, 32, 4, AK, BKM, EPI>(a, st);
+  return launch<128, 128, 64, 2, AK, BKM, EPI>(a, st);
 }
 
 }  // namespace
 
 bool gemm_mfma_supported(int form, int M, int N, int K) {
   (void)form;
-  return M >= 64 && N >= 64 && K >= 64 && M % 8 == 0 && N % 8 == 0 && K % BK == 0 &&
-         (size_t)M * K < (1ull << 32) && (size_t)N * K < (1ull << 32);
+  return M >= 64 && N >= 64 && K >= 64 && M % 8 == 0 && N % 8 == 0 && K % 64 == 0 &&
+         (size_t)M * K < (1ull << 31) && (size_t)N * K < (1ull << 31);
 }
 
 hipError_t gemm_mfma(int form, int M, int N, int K, const void* A, const void* B, void* C,
