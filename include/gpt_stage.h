@@ -28,6 +28,9 @@
  *  - Return value: GPTS_OK (0) or a negative gpts_status; nothing is launched
  *    when validation fails.  No exceptions cross this boundary.
  *  - Results are run-to-run bitwise deterministic (no floating-point atomics).
+ *  - bf16 stages: x, y, dy, dx, weights and every tensor that branches off the
+ *    residual stream are bf16 with fp32 accumulation; LayerNorm statistics, softmax,
+ *    parameter gradients and the residual stream between layers are fp32.
  */
 #ifndef GPT_STAGE_H_
 #define GPT_STAGE_H_
@@ -152,8 +155,10 @@ int gpt_stage_fwd_bwd(const gpt_stage_params* p, const void* x, const void* dy,
  * Exposed so each kernel can be checked and timed on its own.  `dtype` is
  * GPTS_FP32 or GPTS_BF16 as in cfg; all pointers device. */
 
-/* out[t,:] = (x[t,:]-mu_t) * rstd_t * gamma + beta ; mean/rstd fp32 [T] written. */
-int gpt_stage_op_layernorm_fwd(int dtype, int T, int H, float eps, const void* x,
+/* out[t,:] = (x[t,:]-mu_t) * rstd_t * gamma + beta ; mean/rstd fp32 [T] written.
+ * x_f32 != 0: x is fp32 although dtype is bf16 (inside a bf16 stage the residual
+ * stream -- the tensor LayerNorm reads -- is carried in fp32; everything else is bf16). */
+int gpt_stage_op_layernorm_fwd(int dtype, int x_f32, int T, int H, float eps, const void* x,
                                const void* gamma, const void* beta, void* out,
                                float* mean, float* rstd, void* stream);
 
@@ -161,7 +166,7 @@ int gpt_stage_op_layernorm_fwd(int dtype, int T, int H, float eps, const void* x
  * dres may be NULL (treated as 0).  partial: fp32 scratch of
  * gpt_stage_op_layernorm_bwd_scratch_bytes(T,H). */
 size_t gpt_stage_op_layernorm_bwd_scratch_bytes(int T, int H);
-int gpt_stage_op_layernorm_bwd(int dtype, int T, int H, const void* dout, const void* x,
+int gpt_stage_op_layernorm_bwd(int dtype, int x_f32, int T, int H, const void* dout, const void* x,
                                const float* mean, const float* rstd, const void* gamma,
                                const void* dres, void* dx, float* dgamma, float* dbeta,
                                float* partial, void* stream);
@@ -171,10 +176,12 @@ int gpt_stage_op_layernorm_bwd(int dtype, int T, int H, const void* dout, const 
  *                          gelu != 0: also writes C2 = gelu(C) (C keeps the pre-activation)
  *   form 1 (NN, dgrad):    C[M,N]  = A[M,K] B[K,N] ; dgelu_u != NULL: C *= gelu'(dgelu_u[M,N])
  *   form 2 (TN, wgrad):    Cf[M,N] += A[K,M]^T B[K,N]   (Cf fp32, accumulated into)
- * A, B, C, C2, residual, dgelu_u are `dtype`; bias is `dtype`; gelu_kind as cfg.gelu. */
+ * A, B, C, C2, residual, dgelu_u are `dtype`; bias is `dtype`; gelu_kind as cfg.gelu.
+ * f32_flags (bf16, form 0 with a residual only): bit 0 = residual is fp32, bit 1 = C is
+ * written as fp32 (needs bit 0): the epilogues that extend the fp32 residual stream. */
 int gpt_stage_op_gemm(int dtype, int form, int M, int N, int K, const void* A, const void* B,
                       void* C, const void* bias, const void* residual, void* C2,
-                      const void* dgelu_u, int gelu_kind, void* stream);
+                      const void* dgelu_u, int gelu_kind, int f32_flags, void* stream);
 
 /* colsum[n] += sum_m A[m,n]   (bias gradients); A `dtype`, colsum fp32;
  * partial: fp32 scratch of gpt_stage_op_colsum_scratch_bytes(M,N). */

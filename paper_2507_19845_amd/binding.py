@@ -82,10 +82,10 @@ def lib() -> C.CDLL:
         "gpt_stage_fwd_only": (i32, [parp, vp, vp, vp, vp, vp]),
         "gpt_stage_bwd_only": (i32, [parp, vp, vp, vp, vp, vp, vp]),
         "gpt_stage_fwd_bwd": (i32, [parp, vp, vp, vp, vp, vp, vp, vp]),
-        "gpt_stage_op_layernorm_fwd": (i32, [i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp]),
+        "gpt_stage_op_layernorm_fwd": (i32, [i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp]),
         "gpt_stage_op_layernorm_bwd_scratch_bytes": (sz, [i32, i32]),
-        "gpt_stage_op_layernorm_bwd": (i32, [i32, i32, i32] + [vp] * 11),
-        "gpt_stage_op_gemm": (i32, [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp]),
+        "gpt_stage_op_layernorm_bwd": (i32, [i32, i32, i32, i32] + [vp] * 11),
+        "gpt_stage_op_gemm": (i32, [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp]),
         "gpt_stage_op_colsum_scratch_bytes": (sz, [i32, i32]),
         "gpt_stage_op_colsum": (i32, [i32, i32, i32, vp, vp, vp, vp]),
         "gpt_stage_op_attention_fwd": (i32, [i32, i32, i32, i32, i32, vp, vp, vp, vp]),
@@ -209,8 +209,8 @@ def gpt_stage_fwd_bwd(cfg, weights, workspace, x, dy, act_stash, y, dx, dparams,
 
 
 # ---- single operations ----------------------------------------------------------
-def gpt_stage_op_layernorm_fwd(dtype, T, H, eps, x, gamma, beta, out, mean, rstd, stream=None):
-    _check(lib().gpt_stage_op_layernorm_fwd(dtype, T, H, eps, _ptr(x), _ptr(gamma), _ptr(beta),
+def gpt_stage_op_layernorm_fwd(dtype, T, H, eps, x, gamma, beta, out, mean, rstd, stream=None, x_f32=False):
+    _check(lib().gpt_stage_op_layernorm_fwd(dtype, int(x_f32), T, H, eps, _ptr(x), _ptr(gamma), _ptr(beta),
                                             _ptr(out), _ptr(mean), _ptr(rstd), _stream(stream)))
 
 
@@ -219,16 +219,17 @@ def gpt_stage_op_layernorm_bwd_scratch_bytes(T, H) -> int:
 
 
 def gpt_stage_op_layernorm_bwd(dtype, T, H, dout, x, mean, rstd, gamma, dres, dx, dgamma, dbeta,
-                               partial, stream=None):
-    _check(lib().gpt_stage_op_layernorm_bwd(dtype, T, H, _ptr(dout), _ptr(x), _ptr(mean), _ptr(rstd),
+                               partial, stream=None, x_f32=False):
+    _check(lib().gpt_stage_op_layernorm_bwd(dtype, int(x_f32), T, H, _ptr(dout), _ptr(x), _ptr(mean), _ptr(rstd),
                                             _ptr(gamma), _ptr(dres), _ptr(dx), _ptr(dgamma),
                                             _ptr(dbeta), _ptr(partial), _stream(stream)))
 
 
 def gpt_stage_op_gemm(dtype, form, M, N, K, A, B, Cout, bias=None, residual=None, C2=None,
-                      dgelu_u=None, gelu_kind=GPTS_GELU_TANH, stream=None):
+                      dgelu_u=None, gelu_kind=GPTS_GELU_TANH, stream=None, f32_flags=0):
     _check(lib().gpt_stage_op_gemm(dtype, form, M, N, K, _ptr(A), _ptr(B), _ptr(Cout), _ptr(bias),
-                                   _ptr(residual), _ptr(C2), _ptr(dgelu_u), gelu_kind, _stream(stream)))
+                                   _ptr(residual), _ptr(C2), _ptr(dgelu_u), gelu_kind, f32_flags,
+                                   _stream(stream)))
 
 
 def gpt_stage_op_colsum_scratch_bytes(M, N) -> int:

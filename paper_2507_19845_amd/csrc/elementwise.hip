@@ -8,27 +8,52 @@ namespace gpts {
 
 constexpr int kLnThreads = 256;
 
+// 8 consecutive elements <-> fp32 registers (one 16-byte access for bf16, two for fp32)
+__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
+  const f32x4 a = *reinterpret_cast<const f32x4*>(p), b = *reinterpret_cast<const f32x4*>(p + 4);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { v[e] = a[e]; v[4 + e] = b[e]; }
+}
+__device__ __forceinline__ void load8(const bf16* p, float (&v)[8]) {
+  const bf16x8 a = *reinterpret_cast<const bf16x8*>(p);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = (float)a[e];
+}
+__device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
+  f32x4 a, b;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { a[e] = v[e]; b[e] = v[4 + e]; }
+  *reinterpret_cast<f32x4*>(p) = a;
+  *reinterpret_cast<f32x4*>(p + 4) = b;
+}
+__device__ __forceinline__ void store8(bf16* p, const float (&v)[8]) {
+  bf16x8 a;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) a[e] = (bf16)v[e];
+  *reinterpret_cast<bf16x8*>(p) = a;
+}
+
 // ----------------------------------------------------------------- LN fwd ----
 // Per token: mu = mean(x), var = mean((x-mu)^2), r = 1/sqrt(var+eps),
-// out = (x-mu) r gamma + beta.  NCH = 16-byte chunks cached per thread.
-template <typename T, int NCH>
+// out = (x-mu) r gamma + beta.  TX = type of x (the residual stream, fp32 inside
+// bf16 stages), T = type of gamma/beta/out.  NCH = 8-element chunks per thread.
+template <typename TX, typename T, int NCH>
 __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(
-    const T* __restrict__ x, const T* __restrict__ gamma, const T* __restrict__ beta,
+    const TX* __restrict__ x, const T* __restrict__ gamma, const T* __restrict__ beta,
     T* __restrict__ out, float* __restrict__ mean, float* __restrict__ rstd, int H, float eps) {
-  constexpr int V = Vec16<T>::N;
   __shared__ float red[2][kLnThreads / kWave];
   const int row = blockIdx.x;
-  const int nvec = H / V;
-  const T* xr = x + (size_t)row * H;
-  Vec16<T> xv[NCH];
+  const int nvec = H / 8;
+  const TX* xr = x + (size_t)row * H;
+  float xv[NCH][8];
   float s = 0.f;
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
     const int i = threadIdx.x + c * kLnThreads;
     if (i < nvec) {
-      xv[c] = load16(xr + (size_t)i * V);
+      load8(xr + (size_t)i * 8, xv[c]);
 #pragma unroll
-      for (int e = 0; e < V; ++e) s += xv[c].get(e);
+      for (int e = 0; e < 8; ++e) s += xv[c][e];
     }
   }
   const float mu = block_sum<kLnThreads / kWave>(s, red[0]) / (float)H;
@@ -38,8 +63,8 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(
     const int i = threadIdx.x + c * kLnThreads;
     if (i < nvec) {
 #pragma unroll
-      for (int e = 0; e < V; ++e) {
-        const float d = xv[c].get(e) - mu;
+      for (int e = 0; e < 8; ++e) {
+        const float d = xv[c][e] - mu;
         q += d * d;
       }
     }
@@ -51,12 +76,12 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(
   for (int c = 0; c < NCH; ++c) {
     const int i = threadIdx.x + c * kLnThreads;
     if (i < nvec) {
-      const Vec16<T> g = load16(gamma + (size_t)i * V);
-      const Vec16<T> b = load16(beta + (size_t)i * V);
-      Vec16<T> o;
+      float g[8], b[8], o[8];
+      load8(gamma + (size_t)i * 8, g);
+      load8(beta + (size_t)i * 8, b);
 #pragma unroll
-      for (int e = 0; e < V; ++e) o.set(e, (xv[c].get(e) - mu) * r * g.get(e) + b.get(e));
-      store16(orow + (size_t)i * V, o);
+      for (int e = 0; e < 8; ++e) o[e] = (xv[c][e] - mu) * r * g[e] + b[e];
+      store8(orow + (size_t)i * 8, o);
     }
   }
   if (threadIdx.x == 0) {
@@ -71,42 +96,40 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(
 // Each workgroup walks rows blockIdx.x, +gridDim.x, ... and keeps its share of
 // sum_t dout*xhat and sum_t dout in registers; it writes them once to
 // partial[blockIdx.x][0][H] / [1][H] for the fixed-order reduction below.
-template <typename T, int NCH>
+template <typename TX, typename T, int NCH>
 __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(
-    const T* __restrict__ dout, const T* __restrict__ x, const float* __restrict__ mean,
+    const T* __restrict__ dout, const TX* __restrict__ x, const float* __restrict__ mean,
     const float* __restrict__ rstd, const T* __restrict__ gamma, const T* __restrict__ dres,
     T* __restrict__ dx, float* __restrict__ partial, int T_rows, int H) {
-  constexpr int V = Vec16<T>::N;
   __shared__ float red[2][kLnThreads / kWave];
-  const int nvec = H / V;
-  float dg[NCH][V], db[NCH][V];
-  Vec16<T> gam[NCH];
+  const int nvec = H / 8;
+  float dg[NCH][8], db[NCH][8], gam[NCH][8];
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
     const int i = threadIdx.x + c * kLnThreads;
-    if (i < nvec) gam[c] = load16(gamma + (size_t)i * V);
+    if (i < nvec) load8(gamma + (size_t)i * 8, gam[c]);
 #pragma unroll
-    for (int e = 0; e < V; ++e) dg[c][e] = db[c][e] = 0.f;
+    for (int e = 0; e < 8; ++e) dg[c][e] = db[c][e] = 0.f;
   }
   for (int row = blockIdx.x; row < T_rows; row += gridDim.x) {
     const float mu = mean[row], r = rstd[row];
     const size_t base = (size_t)row * H;
-    Vec16<T> dv[NCH], xv[NCH];
+    float dv[NCH][8], xh[NCH][8];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
       const int i = threadIdx.x + c * kLnThreads;
       if (i < nvec) {
-        dv[c] = load16(dout + base + (size_t)i * V);
-        xv[c] = load16(x + base + (size_t)i * V);
+        load8(dout + base + (size_t)i * 8, dv[c]);
+        load8(x + base + (size_t)i * 8, xh[c]);
 #pragma unroll
-        for (int e = 0; e < V; ++e) {
-          const float d = dv[c].get(e);
-          const float xh = (xv[c].get(e) - mu) * r;
-          const float g = d * gam[c].get(e);
+        for (int e = 0; e < 8; ++e) {
+          const float d = dv[c][e];
+          xh[c][e] = (xh[c][e] - mu) * r;
+          const float g = d * gam[c][e];
           s1 += g;
-          s2 += g * xh;
-          dg[c][e] += d * xh;
+          s2 += g * xh[c][e];
+          dg[c][e] += d * xh[c][e];
           db[c][e] += d;
         }
       }
@@ -117,18 +140,15 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(
     for (int c = 0; c < NCH; ++c) {
       const int i = threadIdx.x + c * kLnThreads;
       if (i < nvec) {
-        Vec16<T> o;
-        Vec16<T> rs;
-        if (dres) rs = load16(dres + base + (size_t)i * V);
+        float o[8], rs[8];
+        if (dres) load8(dres + base + (size_t)i * 8, rs);
 #pragma unroll
-        for (int e = 0; e < V; ++e) {
-          const float xh = (xv[c].get(e) - mu) * r;
-          const float g = dv[c].get(e) * gam[c].get(e);
-          float v = r * (g - m1 - xh * m2);
-          if (dres) v += rs.get(e);
-          o.set(e, v);
+        for (int e = 0; e < 8; ++e) {
+          float v = r * (dv[c][e] * gam[c][e] - m1 - xh[c][e] * m2);
+          if (dres) v += rs[e];
+          o[e] = v;
         }
-        store16(dx + base + (size_t)i * V, o);
+        store8(dx + base + (size_t)i * 8, o);
       }
     }
   }
@@ -137,13 +157,20 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(
   for (int c = 0; c < NCH; ++c) {
     const int i = threadIdx.x + c * kLnThreads;
     if (i < nvec) {
-#pragma unroll
-      for (int e = 0; e < V; ++e) {
-        pg[(size_t)i * V + e] = dg[c][e];
-        pg[(size_t)H + (size_t)i * V + e] = db[c][e];
-      }
+      store8(pg + (size_t)i * 8, dg[c]);
+      store8(pg + (size_t)H + (size_t)i * 8, db[c]);
     }
   }
+}
+
+// out[i] = (float) in[i]   (stage input -> fp32 residual stream), 8 elements per thread
+__global__ __launch_bounds__(256) void widen_kernel(const bf16* __restrict__ in, float* __restrict__ out,
+                                                    size_t n8) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n8) return;
+  float v[8];
+  load8(in + i * 8, v);
+  store8(out + i * 8, v);
 }
 
 // out[c] += sum_{g<G} partial[g*stride + c] for c < N0 (into out0) and N0 <= c < N
@@ -205,50 +232,50 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict
 }
 
 // --------------------------------------------------------------- launchers ----
-template <typename T>
-static hipError_t ln_fwd_t(int T_rows, int H, float eps, const T* x, const T* gamma, const T* beta,
+template <typename TX, typename T>
+static hipError_t ln_fwd_t(int T_rows, int H, float eps, const TX* x, const T* gamma, const T* beta,
                            T* out, float* mean, float* rstd, hipStream_t st) {
-  constexpr int V = Vec16<T>::N;
-  const int nch = (H / V + kLnThreads - 1) / kLnThreads;
+  const int nch = (H / 8 + kLnThreads - 1) / kLnThreads;
   dim3 g(T_rows), b(kLnThreads);
-#define GPTS_LN_FWD(N)                                                                       \
-  hipLaunchKernelGGL((ln_fwd_kernel<T, N>), g, b, 0, st, x, gamma, beta, out, mean, rstd, H, eps)
+#define GPTS_LN_FWD(N)                                                                           \
+  hipLaunchKernelGGL((ln_fwd_kernel<TX, T, N>), g, b, 0, st, x, gamma, beta, out, mean, rstd, H, eps)
   if (nch <= 1) GPTS_LN_FWD(1);
   else if (nch <= 2) GPTS_LN_FWD(2);
   else if (nch <= 4) GPTS_LN_FWD(4);
-  else if (nch <= 8) GPTS_LN_FWD(8);
-  else GPTS_LN_FWD(16);
+  else GPTS_LN_FWD(8);
 #undef GPTS_LN_FWD
   return hipGetLastError();
 }
 
-hipError_t ln_fwd(int dtype, int T_rows, int H, float eps, const void* x, const void* gamma,
-                  const void* beta, void* out, float* mean, float* rstd, hipStream_t st) {
+hipError_t ln_fwd(int dtype, bool x_f32, int T_rows, int H, float eps, const void* x,
+                  const void* gamma, const void* beta, void* out, float* mean, float* rstd,
+                  hipStream_t st) {
   if (dtype == 0)
-    return ln_fwd_t<float>(T_rows, H, eps, (const float*)x, (const float*)gamma, (const float*)beta,
-                           (float*)out, mean, rstd, st);
-  return ln_fwd_t<bf16>(T_rows, H, eps, (const bf16*)x, (const bf16*)gamma, (const bf16*)beta,
-                        (bf16*)out, mean, rstd, st);
+    return ln_fwd_t<float, float>(T_rows, H, eps, (const float*)x, (const float*)gamma,
+                                  (const float*)beta, (float*)out, mean, rstd, st);
+  if (x_f32)
+    return ln_fwd_t<float, bf16>(T_rows, H, eps, (const float*)x, (const bf16*)gamma,
+                                 (const bf16*)beta, (bf16*)out, mean, rstd, st);
+  return ln_fwd_t<bf16, bf16>(T_rows, H, eps, (const bf16*)x, (const bf16*)gamma, (const bf16*)beta,
+                              (bf16*)out, mean, rstd, st);
 }
 
 int ln_bwd_blocks(int T_rows) { return T_rows < 256 ? T_rows : 256; }
 
-template <typename T>
-static hipError_t ln_bwd_t(int T_rows, int H, const T* dout, const T* x, const float* mean,
+template <typename TX, typename T>
+static hipError_t ln_bwd_t(int T_rows, int H, const T* dout, const TX* x, const float* mean,
                            const float* rstd, const T* gamma, const T* dres, T* dx, float* dgamma,
                            float* dbeta, float* partial, hipStream_t st) {
-  constexpr int V = Vec16<T>::N;
-  const int nch = (H / V + kLnThreads - 1) / kLnThreads;
+  const int nch = (H / 8 + kLnThreads - 1) / kLnThreads;
   const int G = ln_bwd_blocks(T_rows);
   dim3 g(G), b(kLnThreads);
-#define GPTS_LN_BWD(N)                                                                          \
-  hipLaunchKernelGGL((ln_bwd_kernel<T, N>), g, b, 0, st, dout, x, mean, rstd, gamma, dres, dx, \
+#define GPTS_LN_BWD(N)                                                                              \
+  hipLaunchKernelGGL((ln_bwd_kernel<TX, T, N>), g, b, 0, st, dout, x, mean, rstd, gamma, dres, dx, \
                      partial, T_rows, H)
   if (nch <= 1) GPTS_LN_BWD(1);
   else if (nch <= 2) GPTS_LN_BWD(2);
   else if (nch <= 4) GPTS_LN_BWD(4);
-  else if (nch <= 8) GPTS_LN_BWD(8);
-  else GPTS_LN_BWD(16);
+  else GPTS_LN_BWD(8);
 #undef GPTS_LN_BWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -257,15 +284,26 @@ static hipError_t ln_bwd_t(int T_rows, int H, const T* dout, const T* x, const f
   return hipGetLastError();
 }
 
-hipError_t ln_bwd(int dtype, int T_rows, int H, const void* dout, const void* x, const float* mean,
-                  const float* rstd, const void* gamma, const void* dres, void* dx, float* dgamma,
-                  float* dbeta, float* partial, hipStream_t st) {
+hipError_t ln_bwd(int dtype, bool x_f32, int T_rows, int H, const void* dout, const void* x,
+                  const float* mean, const float* rstd, const void* gamma, const void* dres, void* dx,
+                  float* dgamma, float* dbeta, float* partial, hipStream_t st) {
   if (dtype == 0)
-    return ln_bwd_t<float>(T_rows, H, (const float*)dout, (const float*)x, mean, rstd,
-                           (const float*)gamma, (const float*)dres, (float*)dx, dgamma, dbeta,
-                           partial, st);
-  return ln_bwd_t<bf16>(T_rows, H, (const bf16*)dout, (const bf16*)x, mean, rstd,
-                        (const bf16*)gamma, (const bf16*)dres, (bf16*)dx, dgamma, dbeta, partial, st);
+    return ln_bwd_t<float, float>(T_rows, H, (const float*)dout, (const float*)x, mean, rstd,
+                                  (const float*)gamma, (const float*)dres, (float*)dx, dgamma, dbeta,
+                                  partial, st);
+  if (x_f32)
+    return ln_bwd_t<float, bf16>(T_rows, H, (const bf16*)dout, (const float*)x, mean, rstd,
+                                 (const bf16*)gamma, (const bf16*)dres, (bf16*)dx, dgamma, dbeta,
+                                 partial, st);
+  return ln_bwd_t<bf16, bf16>(T_rows, H, (const bf16*)dout, (const bf16*)x, mean, rstd,
+                              (const bf16*)gamma, (const bf16*)dres, (bf16*)dx, dgamma, dbeta, partial, st);
+}
+
+hipError_t widen_to_f32(const void* in, float* out, size_t n, hipStream_t st) {
+  const size_t n8 = n / 8;
+  hipLaunchKernelGGL(widen_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, st, (const bf16*)in,
+                     out, n8);
+  return hipGetLastError();
 }
 
 size_t ln_bwd_scratch_bytes(int T_rows, int H) {

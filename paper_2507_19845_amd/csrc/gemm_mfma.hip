@@ -36,7 +36,9 @@ typedef __attribute__((address_space(3))) void* lds_ptr;
 typedef __attribute__((address_space(1))) const void* glb_ptr;
 
 // epilogue kinds
-enum { EPI_BIAS_RES = 0, EPI_GELU_TANH, EPI_GELU_ERF, EPI_PLAIN, EPI_DGELU_TANH, EPI_DGELU_ERF, EPI_ACCUM };
+// (RES32: the residual is fp32; OUT32: C is written as fp32 -- the residual stream of a bf16 stage)
+enum { EPI_BIAS_RES = 0, EPI_GELU_TANH, EPI_GELU_ERF, EPI_PLAIN, EPI_DGELU_TANH, EPI_DGELU_ERF, EPI_ACCUM,
+       EPI_BIAS_RES32_OUT32, EPI_BIAS_RES32_OUT16 };
 
 struct MfmaArgs {
   const bf16* A;
@@ -44,7 +46,7 @@ struct MfmaArgs {
   void* C;
   int M, N, K;
   const bf16* bias;
-  const bf16* residual;
+  const void* residual;
   bf16* gelu_out;
   const bf16* dgelu_u;
 };
@@ -357,7 +359,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const MfmaArgs a) {
           *reinterpret_cast<f32x4*>(C + o) = c;
         } else {
           bf16* C = static_cast<bf16*>(a.C);
-          if constexpr (EPI == EPI_BIAS_RES || EPI == EPI_GELU_TANH || EPI == EPI_GELU_ERF) {
+          constexpr bool RES32 = EPI == EPI_BIAS_RES32_OUT32 || EPI == EPI_BIAS_RES32_OUT16;
+          if constexpr (EPI == EPI_BIAS_RES || RES32 || EPI == EPI_GELU_TANH || EPI == EPI_GELU_ERF) {
             if (a.bias) {
               const bf16x4 b = *reinterpret_cast<const bf16x4*>(a.bias + n);
 #pragma unroll
@@ -381,15 +384,27 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const MfmaArgs a) {
             }
             if constexpr (EPI == EPI_BIAS_RES) {
               if (a.residual) {
-                const bf16x4 r = *reinterpret_cast<const bf16x4*>(a.residual + o);
+                const bf16x4 r = *reinterpret_cast<const bf16x4*>(static_cast<const bf16*>(a.residual) + o);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] += (float)r[e];
               }
             }
-            bf16x4 out;
+            if constexpr (RES32) {
+              const f32x4 r = *reinterpret_cast<const f32x4*>(static_cast<const float*>(a.residual) + o);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) out[e] = (bf16)v[e];
-            *reinterpret_cast<bf16x4*>(C + o) = out;
+              for (int e = 0; e < 4; ++e) v[e] += r[e];
+            }
+            if constexpr (EPI == EPI_BIAS_RES32_OUT32) {
+              f32x4 out;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) out[e] = v[e];
+              *reinterpret_cast<f32x4*>(static_cast<float*>(a.C) + o) = out;
+            } else {
+              bf16x4 out;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) out[e] = (bf16)v[e];
+              *reinterpret_cast<bf16x4*>(C + o) = out;
+            }
           }
         }
       }
@@ -426,12 +441,15 @@ hipError_t gemm_mfma(int form, int M, int N, int K, const void* A, const void* B
   MfmaArgs a;
   a.A = (const bf16*)A; a.B = (const bf16*)B; a.C = C;
   a.M = M; a.N = N; a.K = K;
-  a.bias = (const bf16*)ep.bias; a.residual = (const bf16*)ep.residual;
+  a.bias = (const bf16*)ep.bias; a.residual = ep.residual;
   a.gelu_out = (bf16*)ep.gelu_out; a.dgelu_u = (const bf16*)ep.dgelu_u;
   if (form == 0) {
     if (ep.gelu_out)
       return ep.gelu_kind == 0 ? pick_tile<false, false, EPI_GELU_TANH>(a, st)
                                : pick_tile<false, false, EPI_GELU_ERF>(a, st);
+    if (ep.residual && ep.residual_f32)
+      return ep.out_f32 ? pick_tile<false, false, EPI_BIAS_RES32_OUT32>(a, st)
+                        : pick_tile<false, false, EPI_BIAS_RES32_OUT16>(a, st);
     return pick_tile<false, false, EPI_BIAS_RES>(a, st);
   }
   if (form == 1) {

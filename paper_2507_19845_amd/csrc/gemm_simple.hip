@@ -14,7 +14,8 @@ template <typename T, bool A_KCONTIG, bool B_KCONTIG, bool ACCUM_F32, int GELU>
 __global__ __launch_bounds__(256) void gemm_simple_kernel(
     const T* __restrict__ A, const T* __restrict__ B, void* __restrict__ Cv, int M, int N, int K,
     size_t sam, size_t sak, size_t sbk, size_t sbn, const T* __restrict__ bias,
-    const T* __restrict__ residual, T* __restrict__ gelu_out, const T* __restrict__ dgelu_u) {
+    const void* __restrict__ residual, T* __restrict__ gelu_out, const T* __restrict__ dgelu_u,
+    bool res_f32, bool out_f32) {
   __shared__ float As[BK][BM + 4];
   __shared__ float Bs[BK][BN + 4];
   const int tid = threadIdx.x;
@@ -71,8 +72,10 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(
           }
           if (dgelu_u) v *= gelu_grad_f<GELU < 0 ? 0 : GELU>(to_f32(dgelu_u[o]));
         }
-        if (residual) v += to_f32(residual[o]);
-        C[o] = from_f32<T>(v);
+        if (residual)
+          v += res_f32 ? static_cast<const float*>(residual)[o] : to_f32(static_cast<const T*>(residual)[o]);
+        if (out_f32) static_cast<float*>(Cv)[o] = v;
+        else C[o] = from_f32<T>(v);
       }
     }
   }
@@ -83,13 +86,14 @@ static hipError_t gemm_simple_t(int form, int M, int N, int K, const T* A, const
                                 const GemmEpilogue& ep, hipStream_t st) {
   dim3 g((N + BN - 1) / BN, (M + BM - 1) / BM), b(256);
   const T* bias = (const T*)ep.bias;
-  const T* res = (const T*)ep.residual;
+  const void* res = ep.residual;
+  const bool r32 = ep.residual_f32, o32 = ep.out_f32;
   T* go = (T*)ep.gelu_out;
   const T* du = (const T*)ep.dgelu_u;
   const bool act = go || du;
 #define GPTS_SG(AK, BKC, ACC, G, sam, sak, sbk, sbn)                                           \
   hipLaunchKernelGGL((gemm_simple_kernel<T, AK, BKC, ACC, G>), g, b, 0, st, A, B, C, M, N, K,   \
-                     (size_t)(sam), (size_t)(sak), (size_t)(sbk), (size_t)(sbn), bias, res, go, du)
+                     (size_t)(sam), (size_t)(sak), (size_t)(sbk), (size_t)(sbn), bias, res, go, du, r32, o32)
   if (form == 0) {
     if (!act) GPTS_SG(true, true, false, -1, K, 1, 1, K);
     else if (ep.gelu_kind == 0) GPTS_SG(true, true, false, 0, K, 1, 1, K);

@@ -7,12 +7,16 @@ namespace gpts {
 
 // dtype: 0 = fp32 storage, 1 = bf16 storage (fp32 arithmetic in both).
 
-hipError_t ln_fwd(int dtype, int T_rows, int H, float eps, const void* x, const void* gamma,
-                  const void* beta, void* out, float* mean, float* rstd, hipStream_t st);
+// x_f32: the normalised tensor x (the residual stream) is fp32 even when dtype is bf16.
+hipError_t ln_fwd(int dtype, bool x_f32, int T_rows, int H, float eps, const void* x,
+                  const void* gamma, const void* beta, void* out, float* mean, float* rstd,
+                  hipStream_t st);
 size_t ln_bwd_scratch_bytes(int T_rows, int H);
-hipError_t ln_bwd(int dtype, int T_rows, int H, const void* dout, const void* x, const float* mean,
-                  const float* rstd, const void* gamma, const void* dres, void* dx, float* dgamma,
-                  float* dbeta, float* partial, hipStream_t st);
+hipError_t ln_bwd(int dtype, bool x_f32, int T_rows, int H, const void* dout, const void* x,
+                  const float* mean, const float* rstd, const void* gamma, const void* dres, void* dx,
+                  float* dgamma, float* dbeta, float* partial, hipStream_t st);
+// out[i] = (float) in[i] for n bf16 elements (n a multiple of 8)
+hipError_t widen_to_f32(const void* in, float* out, size_t n, hipStream_t st);
 size_t colsum_scratch_bytes(int M, int N);
 hipError_t colsum(int dtype, int M, int N, const void* A, float* out, float* partial,
                   hipStream_t st);
@@ -20,7 +24,9 @@ hipError_t colsum(int dtype, int M, int N, const void* A, float* out, float* par
 // Epilogue description shared by all GEMM implementations.
 struct GemmEpilogue {
   const void* bias = nullptr;      // [N], storage dtype, added to every row
-  const void* residual = nullptr;  // [M,N], storage dtype, added
+  const void* residual = nullptr;  // [M,N], added; storage dtype unless residual_f32
+  bool residual_f32 = false;       // bf16 stages: residual is fp32
+  bool out_f32 = false;            // bf16 stages: C is written as fp32 (forms 0 with residual only)
   void* gelu_out = nullptr;        // [M,N]: if set, C keeps the pre-activation and this gets gelu(C)
   const void* dgelu_u = nullptr;   // [M,N]: if set, C *= gelu'(u)
   int gelu_kind = 0;               // 0 tanh, 1 erf

@@ -15,6 +15,11 @@ thread_local char g_err[256] = "";
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline size_t esize(const gpt_stage_cfg& c) { return c.dtype == GPTS_BF16 ? 2 : 4; }
+// The residual stream (x of every layer and x1) is carried in fp32 inside the stage,
+// also for bf16 stages: rounding it to bf16 after every layer perturbs the attention
+// logits of the following layers enough to cost several percent on their gradients
+// when the logits are large.  Everything that branches off it is still bf16.
+constexpr size_t kResBytes = 4;
 
 struct Dims {
   int L, H, a, d, P, F, S, B, T;
@@ -50,8 +55,8 @@ size_t tensor_off(const Dims& D, int layer, int id) {
 }
 
 // ---- activation stash of one micro-batch: per layer, in this order ----------
-//   X [T,H]  mean1,rstd1 [T]f32  A [T,H]  QKV [T,3P]  C [T,P]  LSE [B,a,S]f32
-//   X1 [T,H] mean2,rstd2 [T]f32  A2 [T,H] U [T,F]  G [T,F]
+//   X [T,H]f32  mean1,rstd1 [T]f32  A [T,H]  QKV [T,3P]  C [T,P]  LSE [B,a,S]f32
+//   X1 [T,H]f32 mean2,rstd2 [T]f32  A2 [T,H] U [T,F]  G [T,F]
 // every region 256-byte aligned.
 struct StashLayer {
   size_t X, stat1, A, QKV, C, LSE, X1, stat2, A2, U, G, end;
@@ -62,13 +67,13 @@ StashLayer stash_layer(const gpt_stage_cfg& c) {
   StashLayer s;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
-  s.X = take((size_t)D.T * D.H * e);
+  s.X = take((size_t)D.T * D.H * kResBytes);
   s.stat1 = take((size_t)2 * D.T * 4);
   s.A = take((size_t)D.T * D.H * e);
   s.QKV = take((size_t)D.T * 3 * D.P * e);
   s.C = take((size_t)D.T * D.P * e);
   s.LSE = take((size_t)D.B * D.a * D.S * 4);
-  s.X1 = take((size_t)D.T * D.H * e);
+  s.X1 = take((size_t)D.T * D.H * kResBytes);
   s.stat2 = take((size_t)2 * D.T * 4);
   s.A2 = take((size_t)D.T * D.H * e);
   s.U = take((size_t)D.T * D.F * e);
@@ -168,15 +173,19 @@ int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, 
   char* stash = static_cast<char*>(act_stash);
   auto w = [&](int l, int id) { return (const void*)(W + tensor_off(D, l, id) * e); };
 
-  // layer 0 keeps its own copy of x so the backward phase never needs the caller's buffer
-  GPTS_TRY(hipMemcpyAsync(stash + sl.X, x, (size_t)D.T * D.H * e, hipMemcpyDeviceToDevice, st), "copy x");
+  // layer 0 keeps its own (fp32) copy of x so the backward phase never needs the caller's buffer
+  const bool bf = dt == GPTS_BF16;
+  if (bf)
+    GPTS_TRY(widen_to_f32(x, reinterpret_cast<float*>(stash + sl.X), (size_t)D.T * D.H, st), "widen x");
+  else
+    GPTS_TRY(hipMemcpyAsync(stash + sl.X, x, (size_t)D.T * D.H * e, hipMemcpyDeviceToDevice, st), "copy x");
   for (int l = 0; l < D.L; ++l) {
     char* s = stash + (size_t)l * sl.end;
     void* X = s + sl.X;
     float* stat1 = reinterpret_cast<float*>(s + sl.stat1);
     float* stat2 = reinterpret_cast<float*>(s + sl.stat2);
     void* Yout = (l == D.L - 1) ? y : (void*)(s + sl.end + sl.X);
-    GPTS_TRY(ln_fwd(dt, D.T, D.H, c.ln_eps, X, w(l, GPTS_LN1_G), w(l, GPTS_LN1_B), s + sl.A, stat1,
+    GPTS_TRY(ln_fwd(dt, bf, D.T, D.H, c.ln_eps, X, w(l, GPTS_LN1_G), w(l, GPTS_LN1_B), s + sl.A, stat1,
                     stat1 + D.T, st), "ln1 fwd");
     GemmEpilogue ep;
     ep.bias = w(l, GPTS_B_QKV);
@@ -186,8 +195,9 @@ int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, 
     ep = GemmEpilogue();
     ep.bias = w(l, GPTS_B_O);
     ep.residual = X;
+    ep.residual_f32 = ep.out_f32 = bf;
     GPTS_TRY(gemm(dt, 0, D.T, D.H, D.P, s + sl.C, w(l, GPTS_W_O), s + sl.X1, ep, st), "out-proj gemm");
-    GPTS_TRY(ln_fwd(dt, D.T, D.H, c.ln_eps, s + sl.X1, w(l, GPTS_LN2_G), w(l, GPTS_LN2_B), s + sl.A2,
+    GPTS_TRY(ln_fwd(dt, bf, D.T, D.H, c.ln_eps, s + sl.X1, w(l, GPTS_LN2_G), w(l, GPTS_LN2_B), s + sl.A2,
                     stat2, stat2 + D.T, st), "ln2 fwd");
     ep = GemmEpilogue();
     ep.bias = w(l, GPTS_B_FC1);
@@ -197,6 +207,8 @@ int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, 
     ep = GemmEpilogue();
     ep.bias = w(l, GPTS_B_FC2);
     ep.residual = s + sl.X1;
+    ep.residual_f32 = bf;
+    ep.out_f32 = bf && l != D.L - 1;   // the stage output y is bf16, the stream between layers fp32
     GPTS_TRY(gemm(dt, 0, D.T, D.H, D.F, s + sl.G, w(l, GPTS_W_FC2), Yout, ep, st), "fc2 gemm");
   }
   return GPTS_OK;
@@ -250,7 +262,7 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     GPTS_TRY(gemm(dt, 2, D.F, D.H, D.T, dU, s + sl.A2, g(l, GPTS_W_FC1), none, st), "fc1 wgrad");
     GPTS_TRY(colsum(dt, D.T, D.F, dU, g(l, GPTS_B_FC1), cs_part, st), "fc1 bias grad");
     // a2 = LN2(x1), x1 also feeds the residual
-    GPTS_TRY(ln_bwd(dt, D.T, D.H, dA, s + sl.X1, stat2, stat2 + D.T, w(l, GPTS_LN2_G), dY, dX1,
+    GPTS_TRY(ln_bwd(dt, dt == GPTS_BF16, D.T, D.H, dA, s + sl.X1, stat2, stat2 + D.T, w(l, GPTS_LN2_G), dY, dX1,
                     g(l, GPTS_LN2_G), g(l, GPTS_LN2_B), ln_part, st), "ln2 bwd");
     // x1 = x + c Wo^T + bo
     GPTS_TRY(gemm(dt, 1, D.T, D.P, D.H, dX1, w(l, GPTS_W_O), dC, none, st), "out-proj dgrad");
@@ -265,7 +277,7 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     GPTS_TRY(gemm(dt, 2, 3 * D.P, D.H, D.T, dQKV, s + sl.A, g(l, GPTS_W_QKV), none, st), "qkv wgrad");
     GPTS_TRY(colsum(dt, D.T, 3 * D.P, dQKV, g(l, GPTS_B_QKV), cs_part, st), "qkv bias grad");
     // a = LN1(x), x also feeds the residual
-    GPTS_TRY(ln_bwd(dt, D.T, D.H, dA, s + sl.X, stat1, stat1 + D.T, w(l, GPTS_LN1_G), dX1, dXout,
+    GPTS_TRY(ln_bwd(dt, dt == GPTS_BF16, D.T, D.H, dA, s + sl.X, stat1, stat1 + D.T, w(l, GPTS_LN1_G), dX1, dXout,
                     g(l, GPTS_LN1_G), g(l, GPTS_LN1_B), ln_part, st), "ln1 bwd");
     dY = dXout;
   }
@@ -369,35 +381,38 @@ int gpt_stage_fwd_bwd(const gpt_stage_params* p, const void* x, const void* dy, 
 // ---- single operations ------------------------------------------------------------
 static int op_dtype_ok(int dtype) { return dtype == GPTS_FP32 || dtype == GPTS_BF16; }
 
-int gpt_stage_op_layernorm_fwd(int dtype, int T, int H, float eps, const void* x, const void* gamma,
+int gpt_stage_op_layernorm_fwd(int dtype, int x_f32, int T, int H, float eps, const void* x, const void* gamma,
                                const void* beta, void* out, float* mean, float* rstd, void* stream) {
   if (!op_dtype_ok(dtype) || !x || !gamma || !beta || !out || !mean || !rstd) return fail(GPTS_EINVAL, "layernorm_fwd: bad argument");
   if (T < 1 || H < 8 || H % 8 || H > 16384) return fail(GPTS_ESHAPE, "layernorm_fwd: H must be a multiple of 8, <= 16384");
-  GPTS_TRY(ln_fwd(dtype, T, H, eps, x, gamma, beta, out, mean, rstd, static_cast<hipStream_t>(stream)), "layernorm_fwd");
+  GPTS_TRY(ln_fwd(dtype, x_f32 != 0, T, H, eps, x, gamma, beta, out, mean, rstd, static_cast<hipStream_t>(stream)), "layernorm_fwd");
   return GPTS_OK;
 }
 size_t gpt_stage_op_layernorm_bwd_scratch_bytes(int T, int H) { return ln_bwd_scratch_bytes(T, H); }
-int gpt_stage_op_layernorm_bwd(int dtype, int T, int H, const void* dout, const void* x,
+int gpt_stage_op_layernorm_bwd(int dtype, int x_f32, int T, int H, const void* dout, const void* x,
                                const float* mean, const float* rstd, const void* gamma,
                                const void* dres, void* dx, float* dgamma, float* dbeta,
                                float* partial, void* stream) {
   if (!op_dtype_ok(dtype) || !dout || !x || !mean || !rstd || !gamma || !dx || !dgamma || !dbeta || !partial)
     return fail(GPTS_EINVAL, "layernorm_bwd: bad argument");
   if (T < 1 || H < 8 || H % 8 || H > 16384) return fail(GPTS_ESHAPE, "layernorm_bwd: H must be a multiple of 8, <= 16384");
-  GPTS_TRY(ln_bwd(dtype, T, H, dout, x, mean, rstd, gamma, dres, dx, dgamma, dbeta, partial,
+  GPTS_TRY(ln_bwd(dtype, x_f32 != 0, T, H, dout, x, mean, rstd, gamma, dres, dx, dgamma, dbeta, partial,
                   static_cast<hipStream_t>(stream)), "layernorm_bwd");
   return GPTS_OK;
 }
 int gpt_stage_op_gemm(int dtype, int form, int M, int N, int K, const void* A, const void* B, void* C,
                       const void* bias, const void* residual, void* C2, const void* dgelu_u,
-                      int gelu_kind, void* stream) {
+                      int gelu_kind, int f32_flags, void* stream) {
   if (!op_dtype_ok(dtype) || form < 0 || form > 2 || !A || !B || !C) return fail(GPTS_EINVAL, "gemm: bad argument");
   if (M < 1 || N < 1 || K < 1) return fail(GPTS_ESHAPE, "gemm: M, N, K must be >= 1");
   if (form == 2 && (bias || residual || C2 || dgelu_u)) return fail(GPTS_EINVAL, "gemm: the wgrad form takes no epilogue");
   if (form == 1 && C2) return fail(GPTS_EINVAL, "gemm: gelu output only with form 0");
   if (form == 0 && dgelu_u) return fail(GPTS_EINVAL, "gemm: dgelu only with form 1");
+  if (f32_flags && (form != 0 || !residual || C2 || (f32_flags & 2 && !(f32_flags & 1)) || f32_flags > 3))
+    return fail(GPTS_EINVAL, "gemm: fp32 residual/output only for form 0 with a residual and no gelu output");
   GemmEpilogue ep;
   ep.bias = bias; ep.residual = residual; ep.gelu_out = C2; ep.dgelu_u = dgelu_u; ep.gelu_kind = gelu_kind;
+  ep.residual_f32 = dtype == GPTS_BF16 && (f32_flags & 1); ep.out_f32 = dtype == GPTS_BF16 && (f32_flags & 2);
   GPTS_TRY(gemm(dtype, form, M, N, K, A, B, C, ep, static_cast<hipStream_t>(stream)), "gemm");
   return GPTS_OK;
 }

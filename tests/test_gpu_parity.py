@@ -165,22 +165,84 @@ def test_workload2_full_size():
     _report(shape.name, compare(shape, got, ref))
 
 
+@pytest.mark.parametrize("idx", [2, 4], ids=["workload3", "workload5"])
+def test_workload3_and_5_full_size(idx):
+    """13B-shaped stage and the tensor-parallel share of a 175B-shaped layer, at full
+    size, every output tensor against the oracle."""
+    shape = W[idx]
+    print(f"[case] full {shape}", flush=True)
+    params, xs, dys = _inputs(shape)
+    got = gpu_run(shape, params, xs, dys)
+    ref = oracle_run(shape, params, xs, dys)
+    _report(shape.name, compare(shape, got, ref))
+
+
+def test_workload4_full_size_decoupled():
+    """The decoupled workload at full size in the launch configuration the benchmark
+    times (8 micro-batches, all forwards on one stream then all backwards on another,
+    8 stash slots, one gradient buffer).  The oracle cannot run all 8 micro-batches in
+    test time, so:
+      * micro-batch 0 is checked tensor by tensor against the oracle: y, dx, and the
+        parameter gradients of a single-micro-batch run;
+      * the 8-micro-batch gradients must equal, bit for bit, the fp32 sum (in call
+        order) of the 8 single-micro-batch gradient buffers -- accumulation is `+=`
+        into fp32, so this holds exactly and pins the accumulation semantics;
+      * y and dx of every micro-batch in the decoupled run equal the coupled
+        single-micro-batch runs bit for bit."""
+    shape = W[3]
+    n = shape.n_microbatches
+    print(f"[case] full {shape}", flush=True)
+    params = synth.make_params(shape, 0)
+    xs = [synth.make_x(shape, 0, m) for m in range(n)]
+    dys = [synth.make_dy(shape, 0, m) for m in range(n)]
+    bufs = B.StageBuffers(shape, n_stash=n)
+    bufs.load_params(params)
+    ys, dxs, g_all = gpu_run(shape, params, xs, dys, decoupled=True, bufs=bufs)
+    print("[step] decoupled 8 micro-batches done", flush=True)
+    acc = None
+    g0 = None
+    for m in range(n):
+        y1, dx1, g1 = gpu_run(shape, params, [xs[m]], [dys[m]], decoupled=False, bufs=bufs)
+        assert np.array_equal(y1[0], ys[m]) and np.array_equal(dx1[0], dxs[m]), m
+        flat = [{k: v.astype(np.float32) for k, v in layer.items()} for layer in g1]
+        if m == 0:
+            g0 = g1
+            acc = flat
+        else:
+            for la, lb in zip(acc, flat):
+                for k in la:
+                    la[k] = la[k] + lb[k]          # fp32 adds in call order
+    for la, lb in zip(acc, g_all):
+        for k in la:
+            assert np.array_equal(la[k].astype(np.float64), lb[k]), k
+    print("[step] accumulation property holds; running the oracle on micro-batch 0", flush=True)
+    del bufs
+    torch.cuda.empty_cache()
+    ref = oracle_run(shape, params, xs[:1], dys[:1])
+    _report(shape.name, compare(shape, ([ys[0]], [dxs[0]], g0), ref))
+
+
 # ------------------------------------------------------- single operations ----
-@pytest.mark.parametrize("dtype,T,H", [("fp32", 37, 128), ("fp32", 5, 4104), ("bf16", 130, 1024),
-                                       ("bf16", 64, 12288), ("bf16", 3, 8), ("fp32", 600, 16384)])
-def test_op_layernorm(dtype, T, H):
-    print(f"[case] layernorm {dtype} T={T} H={H}", flush=True)
+@pytest.mark.parametrize("dtype,T,H,x_f32", [("fp32", 37, 128, False), ("fp32", 5, 4104, False),
+                                             ("bf16", 130, 1024, False), ("bf16", 64, 12288, True),
+                                             ("bf16", 3, 8, False), ("fp32", 600, 16384, False),
+                                             ("bf16", 130, 1024, True), ("bf16", 7, 16384, True)])
+def test_op_layernorm(dtype, T, H, x_f32):
+    """x_f32: x is fp32 while gamma/beta/out/gradients are bf16 (the residual stream
+    inside a bf16 stage)."""
+    print(f"[case] layernorm {dtype} T={T} H={H} x_f32={x_f32}", flush=True)
     dt = B.GPTS_BF16 if dtype == "bf16" else B.GPTS_FP32
-    x = synth.to_storage(synth.make_aux(0, 1, (T, H)) * 2 + 0.5, dtype)
+    x = synth.to_storage(synth.make_aux(0, 1, (T, H)) * 2 + 0.5, "fp32" if x_f32 else dtype)
     gam = synth.to_storage(1 + synth.make_aux(0, 2, (H,), 0.2), dtype)
     bet = synth.to_storage(synth.make_aux(0, 3, (H,), 0.2), dtype)
     dout = synth.to_storage(synth.make_aux(0, 4, (T, H)), dtype)
     dres = synth.to_storage(synth.make_aux(0, 5, (T, H)), dtype)
-    dx_, dg_, db_ = (B.to_device(a, dtype) for a in (x, gam, bet))
-    out = torch.empty_like(dx_)
+    dx_ = B.to_device(x, "fp32" if x_f32 else dtype)
+    dg_, db_ = B.to_device(gam, dtype), B.to_device(bet, dtype)
+    out = torch.empty_like(dg_.new_empty((T, H)))
     mean = torch.empty(T, dtype=torch.float32, device="cuda")
     rstd = torch.empty_like(mean)
-    B.gpt_stage_op_layernorm_fwd(dt, T, H, 1e-5, dx_, dg_, db_, out, mean, rstd)
+    B.gpt_stage_op_layernorm_fwd(dt, T, H, 1e-5, dx_, dg_, db_, out, mean, rstd, x_f32=x_f32)
     ref_out, xhat, r = orc.layernorm_fwd(x, gam, bet, 1e-5)
     tol = TOL[dtype]
     assert max_norm_err(B.to_host(out), ref_out) <= tol
@@ -189,9 +251,9 @@ def test_op_layernorm(dtype, T, H):
     part = torch.empty(B.gpt_stage_op_layernorm_bwd_scratch_bytes(T, H), dtype=torch.uint8, device="cuda")
     dgam = torch.full((H,), 1.0, dtype=torch.float32, device="cuda")     # pre-filled: += semantics
     dbet = torch.full((H,), -2.0, dtype=torch.float32, device="cuda")
-    dxo = torch.empty_like(dx_)
+    dxo = torch.empty_like(out)
     B.gpt_stage_op_layernorm_bwd(dt, T, H, B.to_device(dout, dtype), dx_, mean, rstd, dg_,
-                                 B.to_device(dres, dtype), dxo, dgam, dbet, part)
+                                 B.to_device(dres, dtype), dxo, dgam, dbet, part, x_f32=x_f32)
     rdx, rdg, rdb = orc.layernorm_bwd(dout, xhat, r, gam)
     assert max_norm_err(B.to_host(dxo), rdx + dres) <= tol
     assert max_norm_err(B.to_host(dgam), rdg + 1.0) <= max(tol * 0.1, 1e-5)
@@ -217,6 +279,15 @@ def test_op_gemm_forms(dtype, M, N, K):
     B.gpt_stage_op_gemm(dt, 0, M, N, K, dev(A), dev(Bm), Cd, bias=dev(bias), residual=dev(res))
     ref = A.astype(np.float64) @ Bm.astype(np.float64).T + bias + res
     assert max_norm_err(B.to_host(Cd), ref) <= tol
+    if dtype == "bf16":   # epilogues that extend the fp32 residual stream of a bf16 stage
+        res32 = synth.make_aux(1, 8, (M, N))
+        r32 = torch.from_numpy(res32).cuda()
+        ref32 = A.astype(np.float64) @ Bm.astype(np.float64).T + bias + res32
+        C32 = torch.empty((M, N), dtype=torch.float32, device="cuda")
+        B.gpt_stage_op_gemm(dt, 0, M, N, K, dev(A), dev(Bm), C32, bias=dev(bias), residual=r32, f32_flags=3)
+        assert max_norm_err(B.to_host(C32), ref32) <= 1e-3
+        B.gpt_stage_op_gemm(dt, 0, M, N, K, dev(A), dev(Bm), Cd, bias=dev(bias), residual=r32, f32_flags=1)
+        assert max_norm_err(B.to_host(Cd), ref32) <= tol
     for kind, variant in ((B.GPTS_GELU_TANH, "tanh"), (B.GPTS_GELU_ERF, "erf")):
         C2 = torch.empty_like(Cd)
         B.gpt_stage_op_gemm(dt, 0, M, N, K, dev(A), dev(Bm), Cd, bias=dev(bias), C2=C2, gelu_kind=kind)
