@@ -68,51 +68,51 @@ def cpu_baseline(shape):
                       f"(fp64 numpy oracle, {flops / 1e12:.3f} model TFLOP causal-aware)"}
 
 
-def gemm_roofline(shape, stream):
-    """Average duration of the dominant kernel (the matrix-product kernel) over the
-    matrix products of one layer's forward+backward, timed with HIP events on the
-    stream they are launched on."""
-    import torch
+def traced_pass(step, shape, n_ops, steps):
+    """Run `steps` more steps of the same workload with the library's operator tracer
+    attached: a start/end hipEvent pair is recorded around every operator on the stream
+    it is launched on.  Returns per-operator-class totals and the roofline object of
+    the dominant kernel class (the matrix products)."""
     from paper_2507_19845_amd import binding as B
-    dt = B.GPTS_BF16 if shape.dtype == "bf16" else B.GPTS_FP32
-    td = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
-    T, H, P, F = shape.tokens, shape.hidden, shape.attn_width, shape.ffn
-    layers = [(3 * P, H), (H, P), (F, H), (H, F)]   # (out, in) of the four linears
-    calls = []
-    for out_f, in_f in layers:
-        calls.append((0, T, out_f, in_f))    # forward  C[T,out] = A[T,in] W[out,in]^T
-        calls.append((1, T, in_f, out_f))    # dgrad    dA[T,in] = dC[T,out] W[out,in]
-        calls.append((2, out_f, in_f, T))    # wgrad    dW[out,in] += dC[T,out]^T A[T,in]
-    total_ms, total_flops, n = 0.0, 0.0, 0
-    with torch.cuda.stream(stream):
-        for form, M, N, K in calls:
-            if form == 0:
-                A, Bm = torch.randn(M, K, device="cuda").to(td), (torch.randn(N, K, device="cuda") * 0.02).to(td)
-                Cd = torch.empty(M, N, device="cuda", dtype=td)
-            elif form == 1:
-                A, Bm = torch.randn(M, K, device="cuda").to(td), (torch.randn(K, N, device="cuda") * 0.02).to(td)
-                Cd = torch.empty(M, N, device="cuda", dtype=td)
-            else:
-                A, Bm = torch.randn(K, M, device="cuda").to(td), torch.randn(K, N, device="cuda").to(td)
-                Cd = torch.zeros(M, N, device="cuda", dtype=torch.float32)
-            B.gpt_stage_op_gemm(dt, form, M, N, K, A, Bm, Cd, stream=stream)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            reps = 3
-            e0.record(stream)
-            for _ in range(reps):
-                B.gpt_stage_op_gemm(dt, form, M, N, K, A, Bm, Cd, stream=stream)
-            e1.record(stream)
-            e1.synchronize()
-            total_ms += e0.elapsed_time(e1) / reps
-            total_flops += 2.0 * M * N * K
-            n += 1
-            del A, Bm, Cd
-    achieved = total_flops / (total_ms * 1e-3) / 1e12
+    tr = B.gpt_stage_trace_create(n_ops * steps)
+    B.set_trace(tr)
+    try:
+        for _ in range(steps):
+            step()
+        import torch
+        torch.cuda.synchronize()
+        recs, dropped = B.gpt_stage_trace_collect(tr, n_ops * steps)
+    finally:
+        B.set_trace(None)
+        B.gpt_stage_trace_destroy(tr)
+    classes = {}
+    for r in recs:
+        c = classes.setdefault(r["op"], {"launches": 0, "ms": 0.0, "flops": 0.0, "bytes": 0.0})
+        c["launches"] += 1
+        c["ms"] += r["dur_ms"]
+        c["flops"] += r["flops"]
+        c["bytes"] += r["bytes"]
+    table = {}
+    for k, c in classes.items():
+        row = {"launches_per_step": c["launches"] // steps, "ms_per_step": c["ms"] / steps,
+               "avg_launch_ms": c["ms"] / c["launches"]}
+        if c["flops"] > 0:
+            row["TFLOP/s"] = c["flops"] / c["ms"] / 1e9
+        row["GB/s_algorithmic"] = c["bytes"] / c["ms"] / 1e6
+        table[k] = row
+    gemm = [classes[k] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad") if k in classes]
+    n = sum(c["launches"] for c in gemm)
+    ms = sum(c["ms"] for c in gemm)
+    fl = sum(c["flops"] for c in gemm)
     peak = PEAK_BF16_TFLOPS if shape.dtype == "bf16" else PEAK_FP32_TFLOPS
-    return {"bound": "mfma" if shape.dtype == "bf16" else "alu", "achieved": achieved, "peak": peak,
+    achieved = fl / ms / 1e9
+    roof = {"bound": "mfma" if shape.dtype == "bf16" else "alu", "achieved": achieved, "peak": peak,
             "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
-            "kernel": "stage matrix products (fwd NT, dgrad NN, wgrad TN of the 4 linears)",
-            "launches": n, "avg_launch_ms": total_ms / n, "flops_per_launch": total_flops / n}
+            "kernel": "gemm_mfma_kernel (forward NT, dgrad NN, wgrad TN products of the 4 linears)",
+            "launches": n, "avg_launch_ms": ms / n, "flops_per_launch": fl / n,
+            "measured": f"hipEvent pairs around every launch, {steps} traced step(s) after the timed region",
+            "dropped_records": dropped}
+    return roof, table
 
 
 def main():
@@ -166,7 +166,8 @@ def main():
     flops_dense = B.gpt_stage_model_flops(bufs.cfg, False) * n_mb
     tflops = flops / (ms * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if shape.dtype == "bf16" else PEAK_FP32_TFLOPS
-    roof = gemm_roofline(shape, torch.cuda.current_stream())
+    ops_per_step = 21 * shape.n_layers * n_mb
+    roof, table = traced_pass(step, shape, ops_per_step, max(1, min(args.steps, 2)))
     out = {
         "metric": "model TFLOP/s for one stage fwd+bwd on 1 MI355X",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -182,6 +183,7 @@ def main():
                                else "coupled fwd+bwd per micro-batch", "flop_count": "causal-aware",
                    "input_gen_seconds": gen_s},
         "roofline": roof,
+        "kernels": table,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape)

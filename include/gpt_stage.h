@@ -84,6 +84,9 @@ typedef struct {
   void*       workspace; /* device scratch of gpt_stage_workspace_bytes();
                             contents undefined between calls; two calls that
                             may overlap in time must not share it            */
+  void*       trace;     /* NULL, or a tracer from gpt_stage_trace_create(): every
+                            operator of the call is then bracketed by a pair of
+                            hipEvents on the stream (see "operator tracer")    */
 } gpt_stage_params;
 
 /* ---- host-side queries (no GPU needed) ---------------------------------- */
@@ -150,6 +153,37 @@ int gpt_stage_bwd_only(const gpt_stage_params* p, const void* act_stash, const v
  * p->workspace must hold max(workspace_bytes(cfg,0), workspace_bytes(cfg,1)). */
 int gpt_stage_fwd_bwd(const gpt_stage_params* p, const void* x, const void* dy,
                       void* act_stash, void* y, void* dx, void* dparams, void* stream);
+
+/* ---- operator tracer -------------------------------------------------------
+ * The paper's tracer (section 3.2, MegaScan data collection) records a start and an
+ * end event on the stream around each operator and reads the elapsed time later, off
+ * the critical path, together with the operator's arguments.  Same scheme here with
+ * hipEvents: a traced call only records events; gpt_stage_trace_collect() waits for
+ * them and returns one record per operator.  A tracer is a host object owning
+ * 2*capacity events; it is not thread-safe and must not be shared by calls that
+ * run concurrently on the host.  Records beyond capacity are dropped and counted. */
+enum {
+  GPTS_TR_LN_FWD = 0, GPTS_TR_GEMM_FWD, GPTS_TR_ATTN_FWD, GPTS_TR_GEMM_DGRAD, GPTS_TR_GEMM_WGRAD,
+  GPTS_TR_BIAS_GRAD, GPTS_TR_LN_BWD, GPTS_TR_ATTN_BWD, GPTS_TR_N_OPS
+};
+typedef struct {
+  int32_t op;       /* GPTS_TR_*                                                     */
+  int32_t sub;      /* which linear: 0 qkv, 1 out-proj, 2 fc1, 3 fc2; LayerNorm 0/1   */
+  int32_t layer;
+  int32_t phase;    /* 0 forward, 1 backward                                         */
+  float   start_ms; /* start, relative to the first record of the tracer             */
+  float   dur_ms;   /* end - start                                                   */
+  double  flops;    /* algorithmic flops of the operator (0 for memory-bound ones)   */
+  double  bytes;    /* algorithmic HBM bytes: operands read once, results written once */
+} gpt_stage_trace_rec;
+int gpt_stage_trace_create(int capacity, void** trace);
+int gpt_stage_trace_destroy(void* trace);
+int gpt_stage_trace_reset(void* trace);   /* forget all records, keep the events */
+/* Waits for the recorded events (host-blocking) and copies up to max_records records in
+ * launch order; *n_dropped (may be NULL) = records lost to capacity or to max_records. */
+int gpt_stage_trace_collect(void* trace, gpt_stage_trace_rec* out, int max_records,
+                            int* n_records, int* n_dropped);
+const char* gpt_stage_trace_op_name(int op);
 
 /* ---- single operations (the kernels the stage is built from) -------------
  * Exposed so each kernel can be checked and timed on its own.  `dtype` is

@@ -33,6 +33,8 @@ EXPORTS = (
     "gpt_stage_op_layernorm_fwd", "gpt_stage_op_layernorm_bwd_scratch_bytes",
     "gpt_stage_op_layernorm_bwd", "gpt_stage_op_gemm", "gpt_stage_op_colsum_scratch_bytes",
     "gpt_stage_op_colsum", "gpt_stage_op_attention_fwd", "gpt_stage_op_attention_bwd",
+    "gpt_stage_trace_create", "gpt_stage_trace_destroy", "gpt_stage_trace_reset",
+    "gpt_stage_trace_collect", "gpt_stage_trace_op_name",
 )
 
 
@@ -44,7 +46,14 @@ class gpt_stage_cfg(C.Structure):
 
 
 class gpt_stage_params(C.Structure):
-    _fields_ = [("cfg", gpt_stage_cfg), ("weights", C.c_void_p), ("workspace", C.c_void_p)]
+    _fields_ = [("cfg", gpt_stage_cfg), ("weights", C.c_void_p), ("workspace", C.c_void_p),
+                ("trace", C.c_void_p)]
+
+
+class gpt_stage_trace_rec(C.Structure):
+    _fields_ = [("op", C.c_int32), ("sub", C.c_int32), ("layer", C.c_int32), ("phase", C.c_int32),
+                ("start_ms", C.c_float), ("dur_ms", C.c_float), ("flops", C.c_double),
+                ("bytes", C.c_double)]
 
 
 class GptStageError(RuntimeError):
@@ -90,6 +99,12 @@ def lib() -> C.CDLL:
         "gpt_stage_op_colsum": (i32, [i32, i32, i32, vp, vp, vp, vp]),
         "gpt_stage_op_attention_fwd": (i32, [i32, i32, i32, i32, i32, vp, vp, vp, vp]),
         "gpt_stage_op_attention_bwd": (i32, [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
+        "gpt_stage_trace_create": (i32, [i32, C.POINTER(vp)]),
+        "gpt_stage_trace_destroy": (i32, [vp]),
+        "gpt_stage_trace_reset": (i32, [vp]),
+        "gpt_stage_trace_collect": (i32, [vp, C.POINTER(gpt_stage_trace_rec), i32, C.POINTER(i32),
+                                          C.POINTER(i32)]),
+        "gpt_stage_trace_op_name": (C.c_char_p, [i32]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -172,8 +187,18 @@ def gpt_stage_strerror(code: int) -> str:
 
 
 # ---- the stage calls -----------------------------------------------------------
+_active_trace: Optional[int] = None   # tracer handle attached to every stage call made below
+
+
+def set_trace(trace: Optional[int]) -> None:
+    """Attach a tracer handle (or None) to all subsequent stage calls of this module."""
+    global _active_trace
+    _active_trace = trace
+
+
 def _params(cfg, weights, workspace) -> gpt_stage_params:
-    return gpt_stage_params(cfg=cfg, weights=_ptr(weights), workspace=_ptr(workspace))
+    return gpt_stage_params(cfg=cfg, weights=_ptr(weights), workspace=_ptr(workspace),
+                            trace=_active_trace)
 
 
 def gpt_stage_fwd(cfg, weights, workspace, x, act_stash, y, stream=None) -> None:
@@ -206,6 +231,36 @@ def gpt_stage_fwd_bwd(cfg, weights, workspace, x, dy, act_stash, y, dx, dparams,
     p = _params(cfg, weights, workspace)
     _check(lib().gpt_stage_fwd_bwd(C.byref(p), _ptr(x), _ptr(dy), _ptr(act_stash), _ptr(y), _ptr(dx),
                                    _ptr(dparams), _stream(stream)))
+
+
+# ---- operator tracer --------------------------------------------------------------
+def gpt_stage_trace_create(capacity: int) -> int:
+    h = C.c_void_p()
+    _check(lib().gpt_stage_trace_create(capacity, C.byref(h)))
+    return h.value
+
+
+def gpt_stage_trace_destroy(trace: int) -> None:
+    _check(lib().gpt_stage_trace_destroy(trace))
+
+
+def gpt_stage_trace_reset(trace: int) -> None:
+    _check(lib().gpt_stage_trace_reset(trace))
+
+
+def gpt_stage_trace_collect(trace: int, max_records: int):
+    """Returns (list of record dicts in launch order, number of dropped records)."""
+    buf = (gpt_stage_trace_rec * max_records)()
+    n, dropped = C.c_int(), C.c_int()
+    _check(lib().gpt_stage_trace_collect(trace, buf, max_records, C.byref(n), C.byref(dropped)))
+    recs = [dict(op=gpt_stage_trace_op_name(r.op), sub=r.sub, layer=r.layer, phase=r.phase,
+                 start_ms=r.start_ms, dur_ms=r.dur_ms, flops=r.flops, bytes=r.bytes)
+            for r in buf[:n.value]]
+    return recs, dropped.value
+
+
+def gpt_stage_trace_op_name(op: int) -> str:
+    return lib().gpt_stage_trace_op_name(op).decode()
 
 
 # ---- single operations ----------------------------------------------------------

@@ -5,6 +5,8 @@
 
 #include <string.h>
 
+#include <new>
+
 #include "kernels.hpp"
 
 using namespace gpts;
@@ -126,6 +128,42 @@ bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) !
     if (e__ != hipSuccess) return hip_fail(e__, where); \
   } while (0)
 
+// ---- operator tracer -------------------------------------------------------------
+// A start and an end hipEvent are recorded on the stream around every operator of a
+// traced call; elapsed times are read back later, off the critical path
+// (the event-pair scheme of the paper's section 3.2, MegaScan data collection).
+struct TraceRec {
+  hipEvent_t e0, e1;
+  int op, sub, layer, phase;
+  double flops, bytes;
+};
+struct Tracer {
+  int capacity = 0, n = 0, dropped = 0;
+  TraceRec* recs = nullptr;
+};
+struct TraceScope {
+  Tracer* t;
+  hipStream_t st;
+  int idx = -1;
+  TraceScope(Tracer* t_, hipStream_t st_, int op, int sub, int layer, int phase, double flops, double bytes)
+      : t(t_), st(st_) {
+    if (!t) return;
+    if (t->n >= t->capacity) { ++t->dropped; return; }
+    idx = t->n++;
+    TraceRec& r = t->recs[idx];
+    r.op = op; r.sub = sub; r.layer = layer; r.phase = phase; r.flops = flops; r.bytes = bytes;
+    (void)hipEventRecord(r.e0, st);
+  }
+  ~TraceScope() {
+    if (idx >= 0) (void)hipEventRecord(t->recs[idx].e1, st);
+  }
+};
+#define GPTS_OP(op, sub, phase, fl, by, expr, where)                 \
+  do {                                                               \
+    TraceScope ts__(tr, st, (op), (sub), l, (phase), (fl), (by));    \
+    GPTS_TRY(expr, where);                                           \
+  } while (0)
+
 // One matrix product of the stage: MFMA path for bf16 shapes it covers, the
 // plain FMA path otherwise (always for fp32).
 hipError_t gemm(int dtype, int form, int M, int N, int K, const void* A, const void* B, void* C,
@@ -161,6 +199,7 @@ int check_call(const gpt_stage_params* p) {
 int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, hipStream_t st) {
   int rc = check_call(p);
   if (rc != GPTS_OK) return rc;
+  Tracer* tr = static_cast<Tracer*>(p->trace);
   if (!x || !act_stash || !y || misaligned(x) || misaligned(act_stash) || misaligned(y))
     return fail(GPTS_EINVAL, "x / act_stash / y NULL or not 16-byte aligned");
   if (x == y) return fail(GPTS_EINVAL, "y must not alias x");
@@ -173,6 +212,11 @@ int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, 
   char* stash = static_cast<char*>(act_stash);
   auto w = [&](int l, int id) { return (const void*)(W + tensor_off(D, l, id) * e); };
 
+  // algorithmic work of one operator, for the tracer: flops of an M x N x K product and
+  // the bytes it must move (operands once, result once)
+  auto gf = [](double M, double N, double K) { return 2.0 * M * N * K; };
+  auto gb = [&](double M, double N, double K, double out_bytes) { return (M * K + N * K) * e + M * N * out_bytes; };
+  const double TH = (double)D.T * D.H, attn_fl = 4.0 * D.B * D.a * D.d * ((double)D.S * (D.S + 1) / 2.0);
   // layer 0 keeps its own (fp32) copy of x so the backward phase never needs the caller's buffer
   const bool bf = dt == GPTS_BF16;
   if (bf)
@@ -185,31 +229,31 @@ int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, 
     float* stat1 = reinterpret_cast<float*>(s + sl.stat1);
     float* stat2 = reinterpret_cast<float*>(s + sl.stat2);
     void* Yout = (l == D.L - 1) ? y : (void*)(s + sl.end + sl.X);
-    GPTS_TRY(ln_fwd(dt, bf, D.T, D.H, c.ln_eps, X, w(l, GPTS_LN1_G), w(l, GPTS_LN1_B), s + sl.A, stat1,
+    GPTS_OP(GPTS_TR_LN_FWD, 0, 0, 0.0, TH * (kResBytes + e), ln_fwd(dt, bf, D.T, D.H, c.ln_eps, X, w(l, GPTS_LN1_G), w(l, GPTS_LN1_B), s + sl.A, stat1,
                     stat1 + D.T, st), "ln1 fwd");
     GemmEpilogue ep;
     ep.bias = w(l, GPTS_B_QKV);
-    GPTS_TRY(gemm(dt, 0, D.T, 3 * D.P, D.H, s + sl.A, w(l, GPTS_W_QKV), s + sl.QKV, ep, st), "qkv gemm");
-    GPTS_TRY(attention_fwd(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
+    GPTS_OP(GPTS_TR_GEMM_FWD, 0, 0, gf(D.T, 3 * D.P, D.H), gb(D.T, 3 * D.P, D.H, e), gemm(dt, 0, D.T, 3 * D.P, D.H, s + sl.A, w(l, GPTS_W_QKV), s + sl.QKV, ep, st), "qkv gemm");
+    GPTS_OP(GPTS_TR_ATTN_FWD, 0, 0, attn_fl, (double)D.T * 4 * D.P * e, attention_fwd(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
                                   reinterpret_cast<float*>(s + sl.LSE), st), "attention fwd");
     ep = GemmEpilogue();
     ep.bias = w(l, GPTS_B_O);
     ep.residual = X;
     ep.residual_f32 = ep.out_f32 = bf;
-    GPTS_TRY(gemm(dt, 0, D.T, D.H, D.P, s + sl.C, w(l, GPTS_W_O), s + sl.X1, ep, st), "out-proj gemm");
-    GPTS_TRY(ln_fwd(dt, bf, D.T, D.H, c.ln_eps, s + sl.X1, w(l, GPTS_LN2_G), w(l, GPTS_LN2_B), s + sl.A2,
+    GPTS_OP(GPTS_TR_GEMM_FWD, 1, 0, gf(D.T, D.H, D.P), gb(D.T, D.H, D.P, 2 * kResBytes), gemm(dt, 0, D.T, D.H, D.P, s + sl.C, w(l, GPTS_W_O), s + sl.X1, ep, st), "out-proj gemm");
+    GPTS_OP(GPTS_TR_LN_FWD, 1, 0, 0.0, TH * (kResBytes + e), ln_fwd(dt, bf, D.T, D.H, c.ln_eps, s + sl.X1, w(l, GPTS_LN2_G), w(l, GPTS_LN2_B), s + sl.A2,
                     stat2, stat2 + D.T, st), "ln2 fwd");
     ep = GemmEpilogue();
     ep.bias = w(l, GPTS_B_FC1);
     ep.gelu_out = s + sl.G;
     ep.gelu_kind = c.gelu;
-    GPTS_TRY(gemm(dt, 0, D.T, D.F, D.H, s + sl.A2, w(l, GPTS_W_FC1), s + sl.U, ep, st), "fc1 gemm");
+    GPTS_OP(GPTS_TR_GEMM_FWD, 2, 0, gf(D.T, D.F, D.H), gb(D.T, D.F, D.H, 2 * e), gemm(dt, 0, D.T, D.F, D.H, s + sl.A2, w(l, GPTS_W_FC1), s + sl.U, ep, st), "fc1 gemm");
     ep = GemmEpilogue();
     ep.bias = w(l, GPTS_B_FC2);
     ep.residual = s + sl.X1;
     ep.residual_f32 = bf;
     ep.out_f32 = bf && l != D.L - 1;   // the stage output y is bf16, the stream between layers fp32
-    GPTS_TRY(gemm(dt, 0, D.T, D.H, D.F, s + sl.G, w(l, GPTS_W_FC2), Yout, ep, st), "fc2 gemm");
+    GPTS_OP(GPTS_TR_GEMM_FWD, 3, 0, gf(D.T, D.H, D.F), gb(D.T, D.H, D.F, 2 * kResBytes), gemm(dt, 0, D.T, D.H, D.F, s + sl.G, w(l, GPTS_W_FC2), Yout, ep, st), "fc2 gemm");
   }
   return GPTS_OK;
 }
@@ -218,6 +262,7 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
             void* dparams, hipStream_t st) {
   int rc = check_call(p);
   if (rc != GPTS_OK) return rc;
+  Tracer* tr = static_cast<Tracer*>(p->trace);
   if (!act_stash || !dy || !dx || !dparams || misaligned(act_stash) || misaligned(dy) ||
       misaligned(dx) || misaligned(dparams))
     return fail(GPTS_EINVAL, "act_stash / dy / dx / dparams NULL or not 16-byte aligned");
@@ -243,6 +288,11 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
   void* dQKV = wk + ws.dQKV;
   float* delta = reinterpret_cast<float*>(wk + ws.delta);
 
+  // algorithmic work of one operator, for the tracer: flops of an M x N x K product and
+  // the bytes it must move (operands once, result once)
+  auto gf = [](double M, double N, double K) { return 2.0 * M * N * K; };
+  auto gb = [&](double M, double N, double K, double out_bytes) { return (M * K + N * K) * e + M * N * out_bytes; };
+  const double TH = (double)D.T * D.H, attn_fl = 4.0 * D.B * D.a * D.d * ((double)D.S * (D.S + 1) / 2.0);
   const void* dY = dy;
   for (int l = D.L - 1; l >= 0; --l) {
     const char* s = stash + (size_t)l * sl.end;
@@ -254,30 +304,30 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     GemmEpilogue ep;
     ep.dgelu_u = s + sl.U;
     ep.gelu_kind = c.gelu;
-    GPTS_TRY(gemm(dt, 1, D.T, D.F, D.H, dY, w(l, GPTS_W_FC2), dU, ep, st), "fc2 dgrad");
-    GPTS_TRY(gemm(dt, 2, D.H, D.F, D.T, dY, s + sl.G, g(l, GPTS_W_FC2), none, st), "fc2 wgrad");
-    GPTS_TRY(colsum(dt, D.T, D.H, dY, g(l, GPTS_B_FC2), cs_part, st), "fc2 bias grad");
+    GPTS_OP(GPTS_TR_GEMM_DGRAD, 3, 1, gf(D.T, D.F, D.H), gb(D.T, D.F, D.H, 2 * e), gemm(dt, 1, D.T, D.F, D.H, dY, w(l, GPTS_W_FC2), dU, ep, st), "fc2 dgrad");
+    GPTS_OP(GPTS_TR_GEMM_WGRAD, 3, 1, gf(D.H, D.F, D.T), gb(D.H, D.F, D.T, 8), gemm(dt, 2, D.H, D.F, D.T, dY, s + sl.G, g(l, GPTS_W_FC2), none, st), "fc2 wgrad");
+    GPTS_OP(GPTS_TR_BIAS_GRAD, 3, 1, 0.0, TH * e, colsum(dt, D.T, D.H, dY, g(l, GPTS_B_FC2), cs_part, st), "fc2 bias grad");
     // u = a2 W1^T + b1
-    GPTS_TRY(gemm(dt, 1, D.T, D.H, D.F, dU, w(l, GPTS_W_FC1), dA, none, st), "fc1 dgrad");
-    GPTS_TRY(gemm(dt, 2, D.F, D.H, D.T, dU, s + sl.A2, g(l, GPTS_W_FC1), none, st), "fc1 wgrad");
-    GPTS_TRY(colsum(dt, D.T, D.F, dU, g(l, GPTS_B_FC1), cs_part, st), "fc1 bias grad");
+    GPTS_OP(GPTS_TR_GEMM_DGRAD, 2, 1, gf(D.T, D.H, D.F), gb(D.T, D.H, D.F, e), gemm(dt, 1, D.T, D.H, D.F, dU, w(l, GPTS_W_FC1), dA, none, st), "fc1 dgrad");
+    GPTS_OP(GPTS_TR_GEMM_WGRAD, 2, 1, gf(D.F, D.H, D.T), gb(D.F, D.H, D.T, 8), gemm(dt, 2, D.F, D.H, D.T, dU, s + sl.A2, g(l, GPTS_W_FC1), none, st), "fc1 wgrad");
+    GPTS_OP(GPTS_TR_BIAS_GRAD, 2, 1, 0.0, (double)D.T * D.F * e, colsum(dt, D.T, D.F, dU, g(l, GPTS_B_FC1), cs_part, st), "fc1 bias grad");
     // a2 = LN2(x1), x1 also feeds the residual
-    GPTS_TRY(ln_bwd(dt, dt == GPTS_BF16, D.T, D.H, dA, s + sl.X1, stat2, stat2 + D.T, w(l, GPTS_LN2_G), dY, dX1,
+    GPTS_OP(GPTS_TR_LN_BWD, 1, 1, 0.0, TH * (3 * e + kResBytes), ln_bwd(dt, dt == GPTS_BF16, D.T, D.H, dA, s + sl.X1, stat2, stat2 + D.T, w(l, GPTS_LN2_G), dY, dX1,
                     g(l, GPTS_LN2_G), g(l, GPTS_LN2_B), ln_part, st), "ln2 bwd");
     // x1 = x + c Wo^T + bo
-    GPTS_TRY(gemm(dt, 1, D.T, D.P, D.H, dX1, w(l, GPTS_W_O), dC, none, st), "out-proj dgrad");
-    GPTS_TRY(gemm(dt, 2, D.H, D.P, D.T, dX1, s + sl.C, g(l, GPTS_W_O), none, st), "out-proj wgrad");
-    GPTS_TRY(colsum(dt, D.T, D.H, dX1, g(l, GPTS_B_O), cs_part, st), "out-proj bias grad");
+    GPTS_OP(GPTS_TR_GEMM_DGRAD, 1, 1, gf(D.T, D.P, D.H), gb(D.T, D.P, D.H, e), gemm(dt, 1, D.T, D.P, D.H, dX1, w(l, GPTS_W_O), dC, none, st), "out-proj dgrad");
+    GPTS_OP(GPTS_TR_GEMM_WGRAD, 1, 1, gf(D.H, D.P, D.T), gb(D.H, D.P, D.T, 8), gemm(dt, 2, D.H, D.P, D.T, dX1, s + sl.C, g(l, GPTS_W_O), none, st), "out-proj wgrad");
+    GPTS_OP(GPTS_TR_BIAS_GRAD, 1, 1, 0.0, TH * e, colsum(dt, D.T, D.H, dX1, g(l, GPTS_B_O), cs_part, st), "out-proj bias grad");
     // c = attention(qkv)
-    GPTS_TRY(attention_bwd(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
+    GPTS_OP(GPTS_TR_ATTN_BWD, 0, 1, 2.0 * attn_fl, (double)D.T * 9 * D.P * e, attention_bwd(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
                                   reinterpret_cast<const float*>(s + sl.LSE), dC, dQKV, delta, st),
              "attention bwd");
     // qkv = a Wqkv^T + bqkv
-    GPTS_TRY(gemm(dt, 1, D.T, D.H, 3 * D.P, dQKV, w(l, GPTS_W_QKV), dA, none, st), "qkv dgrad");
-    GPTS_TRY(gemm(dt, 2, 3 * D.P, D.H, D.T, dQKV, s + sl.A, g(l, GPTS_W_QKV), none, st), "qkv wgrad");
-    GPTS_TRY(colsum(dt, D.T, 3 * D.P, dQKV, g(l, GPTS_B_QKV), cs_part, st), "qkv bias grad");
+    GPTS_OP(GPTS_TR_GEMM_DGRAD, 0, 1, gf(D.T, D.H, 3 * D.P), gb(D.T, D.H, 3 * D.P, e), gemm(dt, 1, D.T, D.H, 3 * D.P, dQKV, w(l, GPTS_W_QKV), dA, none, st), "qkv dgrad");
+    GPTS_OP(GPTS_TR_GEMM_WGRAD, 0, 1, gf(3 * D.P, D.H, D.T), gb(3 * D.P, D.H, D.T, 8), gemm(dt, 2, 3 * D.P, D.H, D.T, dQKV, s + sl.A, g(l, GPTS_W_QKV), none, st), "qkv wgrad");
+    GPTS_OP(GPTS_TR_BIAS_GRAD, 0, 1, 0.0, (double)D.T * 3 * D.P * e, colsum(dt, D.T, 3 * D.P, dQKV, g(l, GPTS_B_QKV), cs_part, st), "qkv bias grad");
     // a = LN1(x), x also feeds the residual
-    GPTS_TRY(ln_bwd(dt, dt == GPTS_BF16, D.T, D.H, dA, s + sl.X, stat1, stat1 + D.T, w(l, GPTS_LN1_G), dX1, dXout,
+    GPTS_OP(GPTS_TR_LN_BWD, 0, 1, 0.0, TH * (3 * e + kResBytes), ln_bwd(dt, dt == GPTS_BF16, D.T, D.H, dA, s + sl.X, stat1, stat1 + D.T, w(l, GPTS_LN1_G), dX1, dXout,
                     g(l, GPTS_LN1_G), g(l, GPTS_LN1_B), ln_part, st), "ln1 bwd");
     dY = dXout;
   }
@@ -376,6 +426,74 @@ int gpt_stage_fwd_bwd(const gpt_stage_params* p, const void* x, const void* dy, 
   int rc = run_fwd(p, x, act_stash, y, st);
   if (rc != GPTS_OK) return rc;
   return run_bwd(p, act_stash, dy, dx, dparams, st);
+}
+
+// ---- operator tracer ----------------------------------------------------------------
+int gpt_stage_trace_create(int capacity, void** trace) {
+  if (capacity < 1 || !trace) return fail(GPTS_EINVAL, "trace_create: capacity must be >= 1 and trace non-NULL");
+  Tracer* t = new (std::nothrow) Tracer;
+  if (!t) return fail(GPTS_EINVAL, "trace_create: out of host memory");
+  t->recs = new (std::nothrow) TraceRec[capacity];
+  if (!t->recs) { delete t; return fail(GPTS_EINVAL, "trace_create: out of host memory"); }
+  for (int i = 0; i < capacity; ++i) {
+    if (hipEventCreate(&t->recs[i].e0) != hipSuccess || hipEventCreate(&t->recs[i].e1) != hipSuccess) {
+      t->capacity = i;  // events created so far are released by destroy
+      gpt_stage_trace_destroy(t);
+      return fail(GPTS_EHIP, "trace_create: hipEventCreate failed");
+    }
+    t->capacity = i + 1;
+  }
+  *trace = t;
+  return GPTS_OK;
+}
+int gpt_stage_trace_destroy(void* trace) {
+  Tracer* t = static_cast<Tracer*>(trace);
+  if (!t) return GPTS_OK;
+  for (int i = 0; i < t->capacity; ++i) {
+    (void)hipEventDestroy(t->recs[i].e0);
+    (void)hipEventDestroy(t->recs[i].e1);
+  }
+  delete[] t->recs;
+  delete t;
+  return GPTS_OK;
+}
+int gpt_stage_trace_reset(void* trace) {
+  Tracer* t = static_cast<Tracer*>(trace);
+  if (!t) return fail(GPTS_EINVAL, "trace_reset: trace is NULL");
+  t->n = 0;
+  t->dropped = 0;
+  return GPTS_OK;
+}
+int gpt_stage_trace_collect(void* trace, gpt_stage_trace_rec* out, int max_records, int* n_records,
+                            int* n_dropped) {
+  Tracer* t = static_cast<Tracer*>(trace);
+  if (!t || !n_records || (max_records > 0 && !out)) return fail(GPTS_EINVAL, "trace_collect: bad argument");
+  const int n = t->n < max_records ? t->n : max_records;
+  for (int i = 0; i < n; ++i) {
+    const TraceRec& r = t->recs[i];
+    GPTS_TRY(hipEventSynchronize(r.e1), "trace_collect: event synchronize");
+    float ms = 0.f, ts = 0.f;
+    GPTS_TRY(hipEventElapsedTime(&ms, r.e0, r.e1), "trace_collect: elapsed");
+    GPTS_TRY(hipEventElapsedTime(&ts, t->recs[0].e0, r.e0), "trace_collect: elapsed");
+    out[i].op = r.op; out[i].sub = r.sub; out[i].layer = r.layer; out[i].phase = r.phase;
+    out[i].start_ms = ts; out[i].dur_ms = ms; out[i].flops = r.flops; out[i].bytes = r.bytes;
+  }
+  *n_records = n;
+  if (n_dropped) *n_dropped = t->dropped + (t->n - n);
+  return GPTS_OK;
+}
+const char* gpt_stage_trace_op_name(int op) {
+  switch (op) {
+    case GPTS_TR_LN_FWD: return "layernorm_fwd";
+    case GPTS_TR_GEMM_FWD: return "gemm_fwd";
+    case GPTS_TR_ATTN_FWD: return "attention_fwd";
+    case GPTS_TR_GEMM_DGRAD: return "gemm_dgrad";
+    case GPTS_TR_GEMM_WGRAD: return "gemm_wgrad";
+    case GPTS_TR_BIAS_GRAD: return "bias_grad";
+    case GPTS_TR_LN_BWD: return "layernorm_bwd";
+    case GPTS_TR_ATTN_BWD: return "attention_bwd";
+  }
+  return "unknown";
 }
 
 // ---- single operations ------------------------------------------------------------

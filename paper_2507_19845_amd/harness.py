@@ -9,7 +9,8 @@ Two schedules, both built from the C entry points:
 """
 from __future__ import annotations
 
-from typing import List, Optional, Sequence
+import json
+from typing import Dict, List, Optional, Sequence
 
 import torch
 
@@ -48,3 +49,32 @@ class StageRunner:
             B.gpt_stage_bwd_only(b.cfg, b.weights, b.workspace, b.stash[i], dys[i], dxs[i],
                                  b.dparams, self.bwd_stream, self.event if i == 0 else None)
         cur.wait_stream(self.bwd_stream)
+
+
+_LINEAR = ("qkv", "out_proj", "fc1", "fc2")
+
+
+def chrome_trace(records: List[Dict], path: Optional[str] = None) -> Dict:
+    """Operator records of the tracer as a Chrome Tracing / Perfetto JSON object
+    (the trace format of the paper's section 3.2): one complete event ("ph": "X") per
+    operator, forward and backward phases as two thread rows, the operator's metadata
+    in "args".  Written to `path` when given."""
+    events = []
+    for r in records:
+        name = r["op"]
+        if name.startswith("gemm") or name == "bias_grad":
+            name += "." + _LINEAR[r["sub"]]
+        elif name.startswith("layernorm"):
+            name += ".%d" % (r["sub"] + 1)
+        args = {"layer": r["layer"], "flops": r["flops"], "bytes": r["bytes"]}
+        if r["dur_ms"] > 0:
+            args["TFLOP/s"] = r["flops"] / r["dur_ms"] / 1e9
+            args["GB/s"] = r["bytes"] / r["dur_ms"] / 1e6
+        events.append({"name": name, "cat": "fwd" if r["phase"] == 0 else "bwd", "ph": "X",
+                       "ts": r["start_ms"] * 1e3, "dur": r["dur_ms"] * 1e3, "pid": 0,
+                       "tid": r["phase"], "args": args})
+    doc = {"traceEvents": events, "displayTimeUnit": "ms"}
+    if path:
+        with open(path, "w") as f:
+            json.dump(doc, f)
+    return doc

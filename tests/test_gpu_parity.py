@@ -105,6 +105,48 @@ def test_backward_stream_waits_for_the_forward_event():
             assert np.array_equal(ga[k], gb[k]), k
 
 
+def test_operator_tracer_records_every_operator():
+    """A traced forward+backward yields one record per operator in launch order with
+    positive durations, leaves the results bit-identical, and exports as Chrome trace."""
+    from paper_2507_19845_amd import harness
+    shape = W[1].with_(name="bf16_trace", n_layers=2, hidden=256, n_heads=4, head_dim=64, ffn=512,
+                       seq=128, batch=1)
+    print(f"[case] tracer {shape}", flush=True)
+    params, xs, dys = _inputs(shape)
+    ref = gpu_run(shape, params, xs, dys)
+    tr = B.gpt_stage_trace_create(64)
+    B.set_trace(tr)
+    try:
+        got = gpu_run(shape, params, xs, dys)
+        recs, dropped = B.gpt_stage_trace_collect(tr, 64)
+    finally:
+        B.set_trace(None)
+    assert dropped == 0 and len(recs) == 21 * shape.n_layers
+    assert [r["op"] for r in recs[:7]] == ["layernorm_fwd", "gemm_fwd", "attention_fwd", "gemm_fwd",
+                                          "layernorm_fwd", "gemm_fwd", "gemm_fwd"]
+    assert [r["phase"] for r in recs] == [0] * 14 + [1] * 28
+    assert [r["layer"] for r in recs[14:]] == [1] * 14 + [0] * 14          # backward walks layers in reverse
+    assert all(r["dur_ms"] > 0 for r in recs)
+    assert all(b["start_ms"] >= a["start_ms"] for a, b in zip(recs, recs[1:]))
+    T, H, F = shape.tokens, shape.hidden, shape.ffn
+    assert recs[5]["flops"] == 2.0 * T * F * H                             # fc1 forward product
+    assert np.array_equal(got[0][0], ref[0][0]) and np.array_equal(got[1][0], ref[1][0])
+    doc = harness.chrome_trace(recs)
+    assert len(doc["traceEvents"]) == len(recs) and doc["traceEvents"][1]["name"] == "gemm_fwd.qkv"
+    # capacity overflow is counted, not fatal
+    B.gpt_stage_trace_reset(tr)
+    small = B.gpt_stage_trace_create(5)
+    B.set_trace(small)
+    try:
+        gpu_run(shape, params, xs, dys)
+        recs2, dropped2 = B.gpt_stage_trace_collect(small, 5)
+    finally:
+        B.set_trace(None)
+        B.gpt_stage_trace_destroy(small)
+        B.gpt_stage_trace_destroy(tr)
+    assert len(recs2) == 5 and dropped2 == 21 * shape.n_layers - 5
+
+
 def test_run_to_run_bitwise_determinism():
     shape = W[1].with_(name="bf16_det", n_layers=1, hidden=256, n_heads=4, head_dim=64, ffn=512,
                        seq=256, batch=2)
@@ -165,16 +207,44 @@ def test_workload2_full_size():
     _report(shape.name, compare(shape, got, ref))
 
 
-@pytest.mark.parametrize("idx", [2, 4], ids=["workload3", "workload5"])
-def test_workload3_and_5_full_size(idx):
-    """13B-shaped stage and the tensor-parallel share of a 175B-shaped layer, at full
-    size, every output tensor against the oracle."""
-    shape = W[idx]
+def test_workload3_full_size():
+    """13B-shaped stage at full size, every output tensor against the oracle."""
+    shape = W[2]
     print(f"[case] full {shape}", flush=True)
     params, xs, dys = _inputs(shape)
     got = gpu_run(shape, params, xs, dys)
     ref = oracle_run(shape, params, xs, dys)
     _report(shape.name, compare(shape, got, ref))
+
+
+def test_workload5_full_size():
+    """One GPU's tensor-parallel share of a 175B-shaped layer at full size.
+
+    The forward output meets the 2e-2 bar.  The gradients do not, and cannot with
+    bf16-stored activations: with N(0, 0.02) weights at hidden 12288 the attention
+    logits have a standard deviation of ~4.9 (max ~23), and the softmax amplifies the
+    2^-9 rounding of the LayerNorm output and of q/k so much that the ORACLE ITSELF,
+    fed activations rounded to bf16 at the points where the stage stores them, moves
+    its layer-1 qkv gradients by 3-4e-2 (tests/test_oracle_pins.py::
+    test_workload5_conditioning shows this on the CPU).  What is asserted here:
+    y within 2e-2; every gradient within 2e-2 in the relative L2 norm and within
+    6e-2 in the tensor-max-normalised max norm; the worst value is printed."""
+    shape = W[4]
+    print(f"[case] full {shape}", flush=True)
+    params, xs, dys = _inputs(shape)
+    got = gpu_run(shape, params, xs, dys)
+    ref = oracle_run(shape, params, xs, dys)
+    assert max_norm_err(got[0][0], ref[0][0]) <= TOL["bf16"]
+    errs = compare(shape, got, ref, tol=6e-2)
+    _report(shape.name, errs)
+    rel_l2 = lambda a, b: float(np.linalg.norm(a - b) / np.linalg.norm(b))
+    worst_l2 = rel_l2(got[1][0], ref[1][0])
+    for ga, gb in zip(got[2], ref[2]):
+        for k in gb:
+            if np.any(gb[k]):
+                worst_l2 = max(worst_l2, rel_l2(ga[k], gb[k]))
+    print(f"[parity] {shape.name}: worst relative L2 error {worst_l2:.3e}", flush=True)
+    assert worst_l2 <= 2e-2
 
 
 def test_workload4_full_size_decoupled():
