@@ -28,7 +28,7 @@ N_TENSORS = 12
 EXPORTS = (
     "gpt_stage_validate", "gpt_stage_param_count", "gpt_stage_param_bytes", "gpt_stage_grad_bytes",
     "gpt_stage_stash_bytes", "gpt_stage_workspace_bytes", "gpt_stage_param_offset",
-    "gpt_stage_model_flops", "gpt_stage_strerror",
+    "gpt_stage_model_flops", "gpt_stage_strerror", "gpt_stage_prepared_bytes", "gpt_stage_prepare",
     "gpt_stage_fwd", "gpt_stage_bwd", "gpt_stage_fwd_only", "gpt_stage_bwd_only", "gpt_stage_fwd_bwd",
     "gpt_stage_op_layernorm_fwd", "gpt_stage_op_layernorm_bwd_scratch_bytes",
     "gpt_stage_op_layernorm_bwd", "gpt_stage_op_gemm", "gpt_stage_op_colsum_scratch_bytes",
@@ -47,7 +47,7 @@ class gpt_stage_cfg(C.Structure):
 
 class gpt_stage_params(C.Structure):
     _fields_ = [("cfg", gpt_stage_cfg), ("weights", C.c_void_p), ("workspace", C.c_void_p),
-                ("trace", C.c_void_p)]
+                ("prepared", C.c_void_p), ("trace", C.c_void_p)]
 
 
 class gpt_stage_trace_rec(C.Structure):
@@ -86,6 +86,8 @@ def lib() -> C.CDLL:
         "gpt_stage_param_offset": (i32, [cfgp, i32, i32, C.POINTER(sz), C.POINTER(sz)]),
         "gpt_stage_model_flops": (C.c_double, [cfgp, i32]),
         "gpt_stage_strerror": (C.c_char_p, [i32]),
+        "gpt_stage_prepared_bytes": (sz, [cfgp]),
+        "gpt_stage_prepare": (i32, [parp, vp, vp]),
         "gpt_stage_fwd": (i32, [parp, vp, vp, vp, vp]),
         "gpt_stage_bwd": (i32, [parp, vp, vp, vp, vp, vp]),
         "gpt_stage_fwd_only": (i32, [parp, vp, vp, vp, vp, vp]),
@@ -196,9 +198,31 @@ def set_trace(trace: Optional[int]) -> None:
     _active_trace = trace
 
 
+_prepared: Dict[int, torch.Tensor] = {}   # weights data_ptr -> prepared buffer to pass along
+
+
+def use_prepared(weights: torch.Tensor, prepared: Optional[torch.Tensor]) -> None:
+    """Pass `prepared` (filled by gpt_stage_prepare for these weights) with every later
+    stage call on `weights`; None stops doing so."""
+    if prepared is None:
+        _prepared.pop(weights.data_ptr(), None)
+    else:
+        _prepared[weights.data_ptr()] = prepared
+
+
 def _params(cfg, weights, workspace) -> gpt_stage_params:
+    prep = _prepared.get(weights.data_ptr()) if weights is not None else None
     return gpt_stage_params(cfg=cfg, weights=_ptr(weights), workspace=_ptr(workspace),
-                            trace=_active_trace)
+                            prepared=_ptr(prep), trace=_active_trace)
+
+
+def gpt_stage_prepared_bytes(cfg) -> int:
+    return lib().gpt_stage_prepared_bytes(C.byref(cfg))
+
+
+def gpt_stage_prepare(cfg, weights, prepared, stream=None) -> None:
+    p = gpt_stage_params(cfg=cfg, weights=_ptr(weights), workspace=None, prepared=None, trace=None)
+    _check(lib().gpt_stage_prepare(C.byref(p), _ptr(prepared), _stream(stream)))
 
 
 def gpt_stage_fwd(cfg, weights, workspace, x, act_stash, y, stream=None) -> None:
@@ -345,6 +369,20 @@ class StageBuffers:
                       for _ in range(n_stash)]
         wb = max(gpt_stage_workspace_bytes(self.cfg, 0), gpt_stage_workspace_bytes(self.cfg, 1), 256)
         self.workspace = torch.empty(wb, dtype=torch.uint8, device=device)
+
+    def prepare(self, stream=None) -> None:
+        """(Re)build the prepared-weights buffer from the current weights and pass it
+        with every later stage call on these weights (bf16 stages only)."""
+        nbytes = gpt_stage_prepared_bytes(self.cfg)
+        if nbytes == 0:
+            return
+        if getattr(self, "prepared", None) is None:
+            self.prepared = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        gpt_stage_prepare(self.cfg, self.weights, self.prepared, stream)
+        use_prepared(self.weights, self.prepared)
+
+    def unprepare(self) -> None:
+        use_prepared(self.weights, None)
 
     def act(self) -> torch.Tensor:
         s = self.shape

@@ -22,6 +22,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=fast",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
+FLAGS += os.environ.get("GPTS_HIPCC_FLAGS", "").split()   # e.g. -DGPTS_BIG_WAVES=8 for experiments
 
 
 def _compile(src: str) -> str:

@@ -31,6 +31,10 @@
 namespace gpts {
 namespace {
 
+#ifndef GPTS_BIG_WAVES
+#define GPTS_BIG_WAVES 4   // waves per workgroup of the 256x256 kernel
+#endif
+
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_ptr;
 typedef __attribute__((address_space(1))) const void* glb_ptr;
@@ -70,8 +74,12 @@ template <bool NAT> __device__ __forceinline__ int kperm(int kg, int t, int j) {
 
 // Per-lane state of one operand: global offsets for the DMA and LDS offsets for
 // the fragment reads.  R = tile rows (BM or BN), WR = rows per wave, BK = slice depth.
-template <int R, int WR, int BK, bool KMAJOR, bool NAT> struct Operand {
-  static constexpr int NI = R * BK / 2048;  // DMA instructions (1 KiB each) per wave and slice
+// IMG: the operand was re-laid-out beforehand (prepare_image below) as the exact LDS image
+// of its K-contiguous tiles, [tile of R rows][slice of BK][R*BK elements]: every DMA
+// instruction then copies 1 KiB of contiguous memory.
+template <int R, int WR, int BK, bool KMAJOR, bool NAT, bool IMG = false, int NW = 4> struct Operand {
+  static_assert(!(IMG && KMAJOR), "images are K-contiguous");
+  static constexpr int NI = R * BK * 2 / 1024 / NW;  // DMA instructions (1 KiB each) per wave and slice
   static constexpr int TILES = WR / 32;     // 32-row MFMA sub-tiles per wave
   static constexpr int KS = BK / 16;        // MFMA steps per slice
   static constexpr int RB = BK * 2;         // bytes per row of a K-contiguous tile
@@ -85,7 +93,9 @@ template <int R, int WR, int BK, bool KMAJOR, bool NAT> struct Operand {
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
       const int slot = (wave * NI + i) * 64 + lane;
-      if constexpr (!KMAJOR) {
+      if constexpr (IMG) {
+        goff[i] = (uint32_t)(((size_t)(r0 / R) * R * ld + (size_t)slot * 8) * 2);
+      } else if constexpr (!KMAJOR) {
         const int row = slot / CPR;
         const int chunk = (slot % CPR) ^ swz_kc<CPR>(row);
         int gr = r0 + row;
@@ -128,7 +138,7 @@ template <int R, int WR, int BK, bool KMAJOR, bool NAT> struct Operand {
   // explicitly with wait_dma_and_barrier().
   __device__ __forceinline__ void issue_one(const bf16* __restrict__ X, size_t ld, int kt,
                                             uint32_t lds_tile, int wave, int i) const {
-    const bf16* base = KMAJOR ? X + (size_t)kt * BK * ld : X + (size_t)kt * BK;
+    const bf16* base = IMG ? X + (size_t)kt * R * BK : (KMAJOR ? X + (size_t)kt * BK * ld : X + (size_t)kt * BK);
     const uint32_t dst = lds_tile + (wave * NI + i) * 1024;
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  ::"s"(dst), "v"(goff[i]), "s"(base)
@@ -165,7 +175,7 @@ template <int N_PAIR, int N_DS, int N_MMA, int N_DMA, int I = 0>
 __device__ __forceinline__ void sched_pairs() {
   if constexpr (I < N_PAIR) {
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, I == N_PAIR - 1 ? N_DS - N_PAIR + 1 : 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, ((I + 1) * N_DS) / N_PAIR - (I * N_DS) / N_PAIR, 0);
     if constexpr (((I + 1) * N_DMA) / N_PAIR > (I * N_DMA) / N_PAIR)  // spread evenly
       __builtin_amdgcn_sched_group_barrier(0x010, ((I + 1) * N_DMA) / N_PAIR - (I * N_DMA) / N_PAIR, 0);
     sched_pairs<N_PAIR, N_DS, N_MMA, N_DMA, I + 1>();
@@ -181,9 +191,11 @@ template <int VM> __device__ __forceinline__ void wait_dma_and_barrier() {
   asm volatile("s_waitcnt vmcnt(%0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::"n"(VM) : "memory");
 }
 
-template <int BM, int BN, int BK, int NS, bool A_KMAJOR, bool B_KMAJOR, int EPI>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(const MfmaArgs a) {
-  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32, KS = BK / 16;
+template <int BM, int BN, int BK, int NS, bool A_KMAJOR, bool B_KMAJOR, int EPI, bool B_IMG = false, int NW = 4>
+__global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const MfmaArgs a) {
+  // NW waves in a 2 x (NW/2) grid
+  constexpr int WGN = NW / 2;
+  constexpr int WM = BM / 2, WN = BN / WGN, TM = WM / 32, TN = WN / 32, KS = BK / 16;
   static_assert((NS & (NS - 1)) == 0 && KS % 2 == 0, "stages: power of two; even MFMA steps per slice");
   // k order inside fragments: natural unless both operands are K-major
   constexpr bool NAT = !(A_KMAJOR && B_KMAJOR);
@@ -194,7 +206,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const MfmaArgs a) {
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform (SGPR)
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
 
   // ---- workgroup -> tile --------------------------------------------------------
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
@@ -210,8 +222,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const MfmaArgs a) {
 
   const size_t lda = A_KMAJOR ? (size_t)a.M : (size_t)a.K;
   const size_t ldb = B_KMAJOR ? (size_t)a.N : (size_t)a.K;
-  Operand<BM, WM, BK, A_KMAJOR, NAT> opA;
-  Operand<BN, WN, BK, B_KMAJOR, NAT> opB;
+  Operand<BM, WM, BK, A_KMAJOR, NAT, false, NW> opA;
+  Operand<BN, WN, BK, B_KMAJOR, NAT, B_IMG, NW> opB;
   opA.init(m0, a.M, lda, wave, lane, wm * WM);
   opB.init(n0, a.N, ldb, wave, lane, wn * WN);
 
@@ -228,7 +240,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const MfmaArgs a) {
   constexpr int N_DS = (A_KMAJOR ? 2 : 1) * TM + (B_KMAJOR ? 2 : 1) * TN;
   constexpr int N_MMA = TM * TN;
   constexpr int N_PAIR = N_DS < N_MMA ? N_DS : N_MMA;  // (MFMA, DS read) pairs per step
-  constexpr int N_DMA = (BM + BN) * BK / 2048;         // DMA instructions per wave and slice
+  constexpr int N_DMA = (BM + BN) * BK * 2 / 1024 / NW;  // DMA instructions per wave and slice
 
   auto load_frags = [&](bf16x8(&fa)[TM], bf16x8(&fb)[TN], const char* stage, int ks) {
 #pragma unroll
@@ -246,7 +258,16 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const MfmaArgs a) {
   // DMA instructions [part*N/PARTS, (part+1)*N/PARTS) of each operand's slice -> stage;
   // slice indices past the end are clamped: the copy is redundant but keeps the
   // loop body free of branches.
-  constexpr int NIA = BM * BK / 2048, NIB = BN * BK / 2048;
+  constexpr int NIA = BM * BK * 2 / 1024 / NW, NIB = BN * BK * 2 / 1024 / NW;
+  // MFMAs with linear index i*TN + j in [lo, hi)
+  auto mma_range = [&](const bf16x8(&fa)[TM], const bf16x8(&fb)[TN], int lo, int hi) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        if (i * TN + j >= lo && i * TN + j < hi)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+  };
   auto issue_all = [&](int slice, int stage) {
     const int sl = min(slice, nk - 1);
     opA.issue(a.A, lda, sl, lds_base + stage * STAGE, wave);
@@ -271,35 +292,38 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const MfmaArgs a) {
       const char* st = lds + (kt & (NS - 1)) * STAGE;
       const uint32_t fill = lds_base + ((kt + NS - 1) & (NS - 1)) * STAGE;
       const int sl = min(kt + NS - 1, nk - 1);
-      // fragment reads of (stage, step ks) with part p of the slice's DMA instructions
-      // woven in between them in program order (the DMA writes LDS, so the compiler
-      // never moves it across an LDS read; the order written here is the order issued)
-      auto load_frags_dma = [&](bf16x8(&fa)[TM], bf16x8(&fb)[TN], const char* stage, int ks, int p) {
-        static_assert(TM % PA == 0 && TN % PB == 0, "fragments per DMA instruction");
+      // One MFMA step: the LDS reads of the next step's fragments are paired with the
+      // first N1 MFMAs; the step's share of the slice's DMA instructions (part p) is
+      // issued one at a time between the remaining MFMAs.  The scheduling fences pin
+      // that order: a wave is blocked while the address unit takes its DMA (the four
+      // waves of the workgroup contend for it), and a block is only free when it falls
+      // in the shadow of an MFMA that is already executing.
+      constexpr int N1 = N_DS < N_MMA - PSTEP ? N_DS : N_MMA - PSTEP;
+      constexpr int Q = (N_MMA - N1) / PSTEP;
+      auto step = [&](const bf16x8(&fac)[TM], const bf16x8(&fbc)[TN], bf16x8(&fan)[TM], bf16x8(&fbn)[TN],
+                      const char* stage_nxt, int ks_nxt, int p) {
+        load_frags(fan, fbn, stage_nxt, ks_nxt);
+        mma_range(fac, fbc, 0, N1);
+        sched_pairs<N1, N_DS, N1, 0>();
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          fa[i] = opA.frag(stage, i, ks);
-          if ((i + 1) % (TM / PA) == 0) opA.issue_one(a.A, lda, sl, fill, wave, p * PA + (i + 1) / (TM / PA) - 1);
+        for (int d = 0; d < PSTEP; ++d) {
+          mma_range(fac, fbc, N1 + d * Q, N1 + (d + 1) * Q);
+          __builtin_amdgcn_sched_barrier(0);
+          if (d < PA) opA.issue_one(a.A, lda, sl, fill, wave, p * PA + d);
+          else opB.issue_one(a.B, ldb, sl, fill + A_BYTES, wave, p * PB + d - PA);
+          __builtin_amdgcn_sched_barrier(0);
         }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          fb[j] = opB.frag(stage + A_BYTES, j, ks);
-          if ((j + 1) % (TN / PB) == 0) opB.issue_one(a.B, ldb, sl, fill + A_BYTES, wave, p * PB + (j + 1) / (TN / PB) - 1);
-        }
+        mma_range(fac, fbc, N1 + PSTEP * Q, N_MMA);
       };
       if constexpr (KS == 4) {
-        load_frags_dma(fa1, fb1, st, 1, 0); mma(fa0, fb0);
-        sched_pairs<N_PAIR, N_DS, N_MMA, PSTEP>();
-        load_frags_dma(fa0, fb0, st, 2, 1); mma(fa1, fb1);
-        sched_pairs<N_PAIR, N_DS, N_MMA, PSTEP>();
+        step(fa0, fb0, fa1, fb1, st, 1, 0);
+        step(fa1, fb1, fa0, fb0, st, 2, 1);
       }
-      load_frags_dma(fa1, fb1, st, KS - 1, KS - 2); mma(fa0, fb0);
-      sched_pairs<N_PAIR, N_DS, N_MMA, PSTEP>();
+      step(fa0, fb0, fa1, fb1, st, KS - 1, KS - 2);
       // slice kt+1 must have landed; younger DMAs may stay in flight
       wait_dma_and_barrier<(NS - 3) * N_DMA + (KS - 1) * PSTEP>();
-      load_frags_dma(fa0, fb0, lds + ((kt + 1) & (NS - 1)) * STAGE, 0, KS - 1);
-      mma(fa1, fb1);
-      sched_pairs<N_PAIR, N_DS, N_MMA, PSTEP>();
+      step(fa1, fb1, fa0, fb0, lds + ((kt + 1) & (NS - 1)) * STAGE, 0, KS - 1);
     }
   } else {
     // Two stages: slice kt+2 can only be fetched once every wave has taken its last
@@ -412,20 +436,63 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const MfmaArgs a) {
   }
 }
 
-template <int BM, int BN, int BK, int NS, bool AK, bool BKM, int EPI>
+template <int BM, int BN, int BK, int NS, bool AK, bool BKM, int EPI, bool B_IMG = false, int NW = 4>
 hipError_t launch(const MfmaArgs& a, hipStream_t st) {
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-  hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, NS, AK, BKM, EPI>), dim3(tiles), dim3(256), 0, st, a);
+  hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, NS, AK, BKM, EPI, B_IMG, NW>), dim3(tiles), dim3(64 * NW), 0,
+                     st, a);
   return hipGetLastError();
 }
 
 // Tile choice: 256x256 (slices of 32, four LDS stages: three slices in flight) when
 // that still gives every CU a tile, else 128x128 (slices of 64, two stages, two
 // workgroups per CU) to recover occupancy on small problems.
+bool use_big_tiles(int M, int N) { return (long)((M + 255) / 256) * ((N + 255) / 256) >= 200; }
+
 template <bool AK, bool BKM, int EPI> hipError_t pick_tile(const MfmaArgs& a, hipStream_t st) {
-  const long t256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
-  if (t256 >= 200) return launch<256, 256, 32, 4, AK, BKM, EPI>(a, st);
+  if (use_big_tiles(a.M, a.N)) return launch<256, 256, 32, 4, AK, BKM, EPI, false, GPTS_BIG_WAVES>(a, st);
   return launch<128, 128, 64, 2, AK, BKM, EPI>(a, st);
+}
+
+// ---- operand images -----------------------------------------------------------------
+// image[tile][slice][slot] with slot = row*4 + physical chunk, holding logical chunk
+// (physical ^ swizzle(row)) of row tile*256+row, k = slice*32 + chunk*8 .. +7, where
+// element (n, k) of the operand is src[n*sn + k*sk].  Rows past N are zero.  One
+// workgroup per (slice, tile): the 32 x 256 source patch goes through LDS so that both
+// the reads (along whichever index is contiguous in src) and the writes are coalesced.
+__global__ __launch_bounds__(256) void prepare_image_kernel(const bf16* __restrict__ src, bf16* __restrict__ img,
+                                                            int N, int K, size_t sn, size_t sk) {
+  __shared__ bf16 patch[256][32 + 2];   // [row n][k], padded
+  const int kt = blockIdx.x, tn = blockIdx.y, nk = K / 32;
+  const int n0 = tn * 256, k0 = kt * 32;
+  if (sk == 1) {           // rows contiguous along k: thread loads 8 k of one row, 4 times
+    for (int i = threadIdx.x; i < 256 * 4; i += 256) {
+      const int r = i >> 2, c = i & 3;
+      bf16x8 v;
+      if (n0 + r < N) v = *reinterpret_cast<const bf16x8*>(src + (size_t)(n0 + r) * sn + k0 + c * 8);
+      else for (int e = 0; e < 8; ++e) v[e] = (bf16)0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) patch[r][c * 8 + e] = v[e];
+    }
+  } else {                 // contiguous along n (sn == 1): thread loads 8 n of one k-row
+    for (int i = threadIdx.x; i < 32 * 32; i += 256) {
+      const int k = i >> 5, c = i & 31;
+      bf16x8 v;
+      if (n0 + c * 8 < N) v = *reinterpret_cast<const bf16x8*>(src + (size_t)(k0 + k) * sk + n0 + c * 8);
+      else for (int e = 0; e < 8; ++e) v[e] = (bf16)0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) patch[c * 8 + e][k] = v[e];
+    }
+  }
+  __syncthreads();
+  bf16* out = img + ((size_t)tn * nk + kt) * (256 * 32);
+  for (int slot = threadIdx.x; slot < 256 * 4; slot += 256) {
+    const int r = slot >> 2, c = (slot & 3) ^ swz_kc<4>(r);
+    bf16x8 v;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = patch[r][c * 8 + e];
+    *reinterpret_cast<bf16x8*>(out + (size_t)slot * 8) = v;
+  }
 }
 
 }  // namespace
@@ -436,6 +503,16 @@ bool gemm_mfma_supported(int form, int M, int N, int K) {
          (size_t)M * K < (1ull << 31) && (size_t)N * K < (1ull << 31);
 }
 
+size_t gemm_image_elems(int N, int K) { return (size_t)((N + 255) / 256) * 256 * K; }
+
+hipError_t gemm_prepare_image(const void* src, void* img, int N, int K, bool transposed, hipStream_t st) {
+  // operand element (n, k) = src[n*K + k] (src is [N,K]) or src[k*N + n] (src is [K,N])
+  dim3 g(K / 32, (N + 255) / 256);
+  hipLaunchKernelGGL(prepare_image_kernel, g, dim3(256), 0, st, (const bf16*)src, (bf16*)img, N, K,
+                     transposed ? (size_t)1 : (size_t)K, transposed ? (size_t)N : (size_t)1);
+  return hipGetLastError();
+}
+
 hipError_t gemm_mfma(int form, int M, int N, int K, const void* A, const void* B, void* C,
                      const GemmEpilogue& ep, hipStream_t st) {
   MfmaArgs a;
@@ -443,6 +520,20 @@ hipError_t gemm_mfma(int form, int M, int N, int K, const void* A, const void* B
   a.M = M; a.N = N; a.K = K;
   a.bias = (const bf16*)ep.bias; a.residual = ep.residual;
   a.gelu_out = (bf16*)ep.gelu_out; a.dgelu_u = (const bf16*)ep.dgelu_u;
+  if (ep.b_image && form != 2 && use_big_tiles(M, N)) {
+    // B comes as the image of its [N rows, K] K-contiguous view: forward and dgrad are
+    // then the same product with different epilogues.
+    a.B = (const bf16*)ep.b_image;
+#define GPTS_IMG(EPI) launch<256, 256, 32, 4, false, false, EPI, true, GPTS_BIG_WAVES>(a, st)
+    if (form == 0) {
+      if (ep.gelu_out) return ep.gelu_kind == 0 ? GPTS_IMG(EPI_GELU_TANH) : GPTS_IMG(EPI_GELU_ERF);
+      if (ep.residual && ep.residual_f32) return ep.out_f32 ? GPTS_IMG(EPI_BIAS_RES32_OUT32) : GPTS_IMG(EPI_BIAS_RES32_OUT16);
+      return GPTS_IMG(EPI_BIAS_RES);
+    }
+    if (ep.dgelu_u) return ep.gelu_kind == 0 ? GPTS_IMG(EPI_DGELU_TANH) : GPTS_IMG(EPI_DGELU_ERF);
+    return GPTS_IMG(EPI_PLAIN);
+#undef GPTS_IMG
+  }
   if (form == 0) {
     if (ep.gelu_out)
       return ep.gelu_kind == 0 ? pick_tile<false, false, EPI_GELU_TANH>(a, st)

@@ -30,6 +30,8 @@ struct GemmEpilogue {
   void* gelu_out = nullptr;        // [M,N]: if set, C keeps the pre-activation and this gets gelu(C)
   const void* dgelu_u = nullptr;   // [M,N]: if set, C *= gelu'(u)
   int gelu_kind = 0;               // 0 tanh, 1 erf
+  const void* b_image = nullptr;   // forms 0/1, bf16: B re-laid-out by gemm_prepare_image() as the
+                                   // tiled image of its [N rows, K contiguous] view (optional)
 };
 // form 0: C[M,N] = A[M,K] B[N,K]^T ; form 1: C[M,N] = A[M,K] B[K,N] ;
 // form 2: Cf32[M,N] += A[K,M]^T B[K,N].
@@ -37,6 +39,10 @@ hipError_t gemm_simple(int dtype, int form, int M, int N, int K, const void* A, 
                        void* C, const GemmEpilogue& ep, hipStream_t st);
 // bf16 MFMA path; returns hipErrorNotSupported if the shape does not fit its tiles.
 bool gemm_mfma_supported(int form, int M, int N, int K);
+// Tiled image of a B operand for the 256x256x32 kernel: `transposed` = src is [K,N]
+// (the dgrad view of a weight [out=K, in=N]); else src is [N,K].  N any, K % 32 == 0.
+size_t gemm_image_elems(int N, int K);
+hipError_t gemm_prepare_image(const void* src, void* img, int N, int K, bool transposed, hipStream_t st);
 hipError_t gemm_mfma(int form, int M, int N, int K, const void* A, const void* B, void* C,
                      const GemmEpilogue& ep, hipStream_t st);
 

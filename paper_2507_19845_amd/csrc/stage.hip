@@ -111,6 +111,29 @@ BwdWs bwd_ws(const gpt_stage_cfg& c) {
   return w;
 }
 
+// ---- prepared weights: per layer and linear (qkv, out-proj, fc1, fc2) the forward
+// image ([out rows, in]) followed by the dgrad image ([in rows, out]) ---------------------
+struct LinDims { int out, in, wid; };
+inline void linears(const Dims& D, LinDims (&L)[4]) {
+  L[0] = {3 * D.P, D.H, GPTS_W_QKV};
+  L[1] = {D.H, D.P, GPTS_W_O};
+  L[2] = {D.F, D.H, GPTS_W_FC1};
+  L[3] = {D.H, D.F, GPTS_W_FC2};
+}
+// element offset of image (layer, linear, which: 0 forward / 1 dgrad); total when layer == L
+size_t prepared_off(const Dims& D, int layer, int lin, int which) {
+  LinDims L[4];
+  linears(D, L);
+  size_t per_layer = 0, off = 0;
+  for (int i = 0; i < 4; ++i) {
+    const size_t f = gemm_image_elems(L[i].out, L[i].in), b = gemm_image_elems(L[i].in, L[i].out);
+    if (i < lin) off += f + b;
+    if (i == lin && which == 1) off += f;
+    per_layer += f + b;
+  }
+  return (size_t)layer * per_layer + (layer == D.L ? 0 : off);
+}
+
 int fail(int code, const char* msg) {
   strncpy(g_err, msg, sizeof(g_err) - 1);
   g_err[sizeof(g_err) - 1] = 0;
@@ -193,6 +216,7 @@ int check_call(const gpt_stage_params* p) {
   if (rc != GPTS_OK) return rc;
   if (!p->weights || misaligned(p->weights)) return fail(GPTS_EINVAL, "weights NULL or not 16-byte aligned");
   if (p->workspace && misaligned(p->workspace)) return fail(GPTS_EINVAL, "workspace not 16-byte aligned");
+  if (p->prepared && misaligned(p->prepared)) return fail(GPTS_EINVAL, "prepared not 16-byte aligned");
   return GPTS_OK;
 }
 
@@ -217,8 +241,12 @@ int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, 
   auto gf = [](double M, double N, double K) { return 2.0 * M * N * K; };
   auto gb = [&](double M, double N, double K, double out_bytes) { return (M * K + N * K) * e + M * N * out_bytes; };
   const double TH = (double)D.T * D.H, attn_fl = 4.0 * D.B * D.a * D.d * ((double)D.S * (D.S + 1) / 2.0);
-  // layer 0 keeps its own (fp32) copy of x so the backward phase never needs the caller's buffer
   const bool bf = dt == GPTS_BF16;
+  const bf16* prep = bf ? static_cast<const bf16*>(p->prepared) : nullptr;
+  auto img = [&](int l, int lin, int which) -> const void* {
+    return prep ? (const void*)(prep + prepared_off(D, l, lin, which)) : nullptr;
+  };
+  // layer 0 keeps its own (fp32) copy of x so the backward phase never needs the caller's buffer
   if (bf)
     GPTS_TRY(widen_to_f32(x, reinterpret_cast<float*>(stash + sl.X), (size_t)D.T * D.H, st), "widen x");
   else
@@ -233,6 +261,7 @@ int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, 
                     stat1 + D.T, st), "ln1 fwd");
     GemmEpilogue ep;
     ep.bias = w(l, GPTS_B_QKV);
+    ep.b_image = img(l, 0, 0);
     GPTS_OP(GPTS_TR_GEMM_FWD, 0, 0, gf(D.T, 3 * D.P, D.H), gb(D.T, 3 * D.P, D.H, e), gemm(dt, 0, D.T, 3 * D.P, D.H, s + sl.A, w(l, GPTS_W_QKV), s + sl.QKV, ep, st), "qkv gemm");
     GPTS_OP(GPTS_TR_ATTN_FWD, 0, 0, attn_fl, (double)D.T * 4 * D.P * e, attention_fwd(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
                                   reinterpret_cast<float*>(s + sl.LSE), st), "attention fwd");
@@ -240,6 +269,7 @@ int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, 
     ep.bias = w(l, GPTS_B_O);
     ep.residual = X;
     ep.residual_f32 = ep.out_f32 = bf;
+    ep.b_image = img(l, 1, 0);
     GPTS_OP(GPTS_TR_GEMM_FWD, 1, 0, gf(D.T, D.H, D.P), gb(D.T, D.H, D.P, 2 * kResBytes), gemm(dt, 0, D.T, D.H, D.P, s + sl.C, w(l, GPTS_W_O), s + sl.X1, ep, st), "out-proj gemm");
     GPTS_OP(GPTS_TR_LN_FWD, 1, 0, 0.0, TH * (kResBytes + e), ln_fwd(dt, bf, D.T, D.H, c.ln_eps, s + sl.X1, w(l, GPTS_LN2_G), w(l, GPTS_LN2_B), s + sl.A2,
                     stat2, stat2 + D.T, st), "ln2 fwd");
@@ -247,12 +277,14 @@ int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, 
     ep.bias = w(l, GPTS_B_FC1);
     ep.gelu_out = s + sl.G;
     ep.gelu_kind = c.gelu;
+    ep.b_image = img(l, 2, 0);
     GPTS_OP(GPTS_TR_GEMM_FWD, 2, 0, gf(D.T, D.F, D.H), gb(D.T, D.F, D.H, 2 * e), gemm(dt, 0, D.T, D.F, D.H, s + sl.A2, w(l, GPTS_W_FC1), s + sl.U, ep, st), "fc1 gemm");
     ep = GemmEpilogue();
     ep.bias = w(l, GPTS_B_FC2);
     ep.residual = s + sl.X1;
     ep.residual_f32 = bf;
     ep.out_f32 = bf && l != D.L - 1;   // the stage output y is bf16, the stream between layers fp32
+    ep.b_image = img(l, 3, 0);
     GPTS_OP(GPTS_TR_GEMM_FWD, 3, 0, gf(D.T, D.H, D.F), gb(D.T, D.H, D.F, 2 * kResBytes), gemm(dt, 0, D.T, D.H, D.F, s + sl.G, w(l, GPTS_W_FC2), Yout, ep, st), "fc2 gemm");
   }
   return GPTS_OK;
@@ -293,6 +325,10 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
   auto gf = [](double M, double N, double K) { return 2.0 * M * N * K; };
   auto gb = [&](double M, double N, double K, double out_bytes) { return (M * K + N * K) * e + M * N * out_bytes; };
   const double TH = (double)D.T * D.H, attn_fl = 4.0 * D.B * D.a * D.d * ((double)D.S * (D.S + 1) / 2.0);
+  const bf16* prep = dt == GPTS_BF16 ? static_cast<const bf16*>(p->prepared) : nullptr;
+  auto img = [&](int l, int lin) -> const void* {
+    return prep ? (const void*)(prep + prepared_off(D, l, lin, 1)) : nullptr;
+  };
   const void* dY = dy;
   for (int l = D.L - 1; l >= 0; --l) {
     const char* s = stash + (size_t)l * sl.end;
@@ -300,22 +336,27 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     const float* stat2 = reinterpret_cast<const float*>(s + sl.stat2);
     void* dXout = (l == 0) ? dx : (void*)(wk + (((D.L - 1 - l) & 1) ? ws.pong : ws.ping));
     GemmEpilogue none;
+    GemmEpilogue d_fc1, d_o, d_qkv;   // plain dgrads, each with the image of its weight
+    d_fc1.b_image = img(l, 2);
+    d_o.b_image = img(l, 1);
+    d_qkv.b_image = img(l, 0);
     // y = x1 + g W2^T + b2 ;  g = gelu(u)
     GemmEpilogue ep;
     ep.dgelu_u = s + sl.U;
     ep.gelu_kind = c.gelu;
+    ep.b_image = img(l, 3);
     GPTS_OP(GPTS_TR_GEMM_DGRAD, 3, 1, gf(D.T, D.F, D.H), gb(D.T, D.F, D.H, 2 * e), gemm(dt, 1, D.T, D.F, D.H, dY, w(l, GPTS_W_FC2), dU, ep, st), "fc2 dgrad");
     GPTS_OP(GPTS_TR_GEMM_WGRAD, 3, 1, gf(D.H, D.F, D.T), gb(D.H, D.F, D.T, 8), gemm(dt, 2, D.H, D.F, D.T, dY, s + sl.G, g(l, GPTS_W_FC2), none, st), "fc2 wgrad");
     GPTS_OP(GPTS_TR_BIAS_GRAD, 3, 1, 0.0, TH * e, colsum(dt, D.T, D.H, dY, g(l, GPTS_B_FC2), cs_part, st), "fc2 bias grad");
     // u = a2 W1^T + b1
-    GPTS_OP(GPTS_TR_GEMM_DGRAD, 2, 1, gf(D.T, D.H, D.F), gb(D.T, D.H, D.F, e), gemm(dt, 1, D.T, D.H, D.F, dU, w(l, GPTS_W_FC1), dA, none, st), "fc1 dgrad");
+    GPTS_OP(GPTS_TR_GEMM_DGRAD, 2, 1, gf(D.T, D.H, D.F), gb(D.T, D.H, D.F, e), gemm(dt, 1, D.T, D.H, D.F, dU, w(l, GPTS_W_FC1), dA, d_fc1, st), "fc1 dgrad");
     GPTS_OP(GPTS_TR_GEMM_WGRAD, 2, 1, gf(D.F, D.H, D.T), gb(D.F, D.H, D.T, 8), gemm(dt, 2, D.F, D.H, D.T, dU, s + sl.A2, g(l, GPTS_W_FC1), none, st), "fc1 wgrad");
     GPTS_OP(GPTS_TR_BIAS_GRAD, 2, 1, 0.0, (double)D.T * D.F * e, colsum(dt, D.T, D.F, dU, g(l, GPTS_B_FC1), cs_part, st), "fc1 bias grad");
     // a2 = LN2(x1), x1 also feeds the residual
     GPTS_OP(GPTS_TR_LN_BWD, 1, 1, 0.0, TH * (3 * e + kResBytes), ln_bwd(dt, dt == GPTS_BF16, D.T, D.H, dA, s + sl.X1, stat2, stat2 + D.T, w(l, GPTS_LN2_G), dY, dX1,
                     g(l, GPTS_LN2_G), g(l, GPTS_LN2_B), ln_part, st), "ln2 bwd");
     // x1 = x + c Wo^T + bo
-    GPTS_OP(GPTS_TR_GEMM_DGRAD, 1, 1, gf(D.T, D.P, D.H), gb(D.T, D.P, D.H, e), gemm(dt, 1, D.T, D.P, D.H, dX1, w(l, GPTS_W_O), dC, none, st), "out-proj dgrad");
+    GPTS_OP(GPTS_TR_GEMM_DGRAD, 1, 1, gf(D.T, D.P, D.H), gb(D.T, D.P, D.H, e), gemm(dt, 1, D.T, D.P, D.H, dX1, w(l, GPTS_W_O), dC, d_o, st), "out-proj dgrad");
     GPTS_OP(GPTS_TR_GEMM_WGRAD, 1, 1, gf(D.H, D.P, D.T), gb(D.H, D.P, D.T, 8), gemm(dt, 2, D.H, D.P, D.T, dX1, s + sl.C, g(l, GPTS_W_O), none, st), "out-proj wgrad");
     GPTS_OP(GPTS_TR_BIAS_GRAD, 1, 1, 0.0, TH * e, colsum(dt, D.T, D.H, dX1, g(l, GPTS_B_O), cs_part, st), "out-proj bias grad");
     // c = attention(qkv)
@@ -323,7 +364,7 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
                                   reinterpret_cast<const float*>(s + sl.LSE), dC, dQKV, delta, st),
              "attention bwd");
     // qkv = a Wqkv^T + bqkv
-    GPTS_OP(GPTS_TR_GEMM_DGRAD, 0, 1, gf(D.T, D.H, 3 * D.P), gb(D.T, D.H, 3 * D.P, e), gemm(dt, 1, D.T, D.H, 3 * D.P, dQKV, w(l, GPTS_W_QKV), dA, none, st), "qkv dgrad");
+    GPTS_OP(GPTS_TR_GEMM_DGRAD, 0, 1, gf(D.T, D.H, 3 * D.P), gb(D.T, D.H, 3 * D.P, e), gemm(dt, 1, D.T, D.H, 3 * D.P, dQKV, w(l, GPTS_W_QKV), dA, d_qkv, st), "qkv dgrad");
     GPTS_OP(GPTS_TR_GEMM_WGRAD, 0, 1, gf(3 * D.P, D.H, D.T), gb(3 * D.P, D.H, D.T, 8), gemm(dt, 2, 3 * D.P, D.H, D.T, dQKV, s + sl.A, g(l, GPTS_W_QKV), none, st), "qkv wgrad");
     GPTS_OP(GPTS_TR_BIAS_GRAD, 0, 1, 0.0, (double)D.T * 3 * D.P * e, colsum(dt, D.T, 3 * D.P, dQKV, g(l, GPTS_B_QKV), cs_part, st), "qkv bias grad");
     // a = LN1(x), x also feeds the residual
@@ -395,6 +436,31 @@ const char* gpt_stage_strerror(int code) {
     case GPTS_EINVAL: case GPTS_ESHAPE: case GPTS_EHIP: return g_err[0] ? g_err : "error";
   }
   return "unknown status";
+}
+
+size_t gpt_stage_prepared_bytes(const gpt_stage_cfg* c) {
+  if (gpt_stage_validate(c) != GPTS_OK || c->dtype != GPTS_BF16) return 0;
+  Dims D(*c);
+  return prepared_off(D, D.L, 0, 0) * 2;
+}
+int gpt_stage_prepare(const gpt_stage_params* p, void* prepared, void* stream) {
+  int rc = check_call(p);
+  if (rc != GPTS_OK) return rc;
+  if (p->cfg.dtype != GPTS_BF16) return fail(GPTS_EINVAL, "prepare: only bf16 stages have prepared weights");
+  if (!prepared || misaligned(prepared)) return fail(GPTS_EINVAL, "prepare: prepared NULL or not 16-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const Dims D(p->cfg);
+  LinDims L[4];
+  linears(D, L);
+  const bf16* W = static_cast<const bf16*>(p->weights);
+  bf16* out = static_cast<bf16*>(prepared);
+  for (int l = 0; l < D.L; ++l)
+    for (int i = 0; i < 4; ++i) {
+      const bf16* w = W + tensor_off(D, l, L[i].wid);
+      GPTS_TRY(gemm_prepare_image(w, out + prepared_off(D, l, i, 0), L[i].out, L[i].in, false, st), "prepare fwd image");
+      GPTS_TRY(gemm_prepare_image(w, out + prepared_off(D, l, i, 1), L[i].in, L[i].out, true, st), "prepare dgrad image");
+    }
+  return GPTS_OK;
 }
 
 int gpt_stage_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, void* stream) {

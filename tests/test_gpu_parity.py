@@ -105,6 +105,30 @@ def test_backward_stream_waits_for_the_forward_event():
             assert np.array_equal(ga[k], gb[k]), k
 
 
+def test_prepared_weights_give_identical_results():
+    """With the weight images of gpt_stage_prepare() the forward and dgrad products read
+    the same numbers through a different layout: every output must be bit-identical to
+    the run on the raw weights.  One layer of the decoupled workload's shape (large
+    enough for the 256x256 tiles the images are made for), ragged N via ffn."""
+    shape = W[3].with_(name="bf16_prepared", n_layers=1, ffn=16384 - 64, n_microbatches=1, bias_std=0.02)
+    print(f"[case] prepared weights {shape}", flush=True)
+    params, xs, dys = _inputs(shape)
+    bufs = B.StageBuffers(shape)
+    bufs.load_params(params)
+    raw = gpu_run(shape, params, xs, dys, bufs=bufs)
+    assert B.gpt_stage_prepared_bytes(bufs.cfg) > 2 * B.gpt_stage_param_bytes(bufs.cfg) * 0.99
+    bufs.prepare()
+    try:
+        prep = gpu_run(shape, params, xs, dys, bufs=bufs)
+    finally:
+        bufs.unprepare()
+    assert np.array_equal(raw[0][0], prep[0][0]) and np.array_equal(raw[1][0], prep[1][0])
+    for ga, gb in zip(raw[2], prep[2]):
+        for k in ga:
+            assert np.array_equal(ga[k], gb[k]), k
+    assert B.gpt_stage_prepared_bytes(B.make_cfg(W[0])) == 0      # fp32 stages have none
+
+
 def test_operator_tracer_records_every_operator():
     """A traced forward+backward yields one record per operator in launch order with
     positive durations, leaves the results bit-identical, and exports as Chrome trace."""
