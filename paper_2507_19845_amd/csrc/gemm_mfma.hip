@@ -358,77 +358,121 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const MfmaArgs a) {
   // no DMA may still be writing LDS when the workgroup retires
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-  // ---- epilogue: lane owns row m = ..+(lane&31), columns n = ..+8g+4(lane>>5)+0..3 ----
-  const int mrow = m0 + wm * WM + (lane & 31);
-  const int ncol = n0 + wn * WN + (lane >> 5) * 4;
+  // ---- epilogue --------------------------------------------------------------------
+  // The accumulators hold a lane-per-row layout (lane owns row lane&31 and four-column
+  // groups), which would store 16-byte pieces scattered over 32 rows.  Each wave instead
+  // transposes its block through the pipeline's LDS (free once every wave has left the
+  // main loop) in passes of RP rows, and reads it back row-major: CW lanes cover one row
+  // of the wave's WN columns, so every global load and store of the epilogue touches
+  // whole cache lines.  The 16-byte chunks of a staged row are XOR-swizzled with the row
+  // so that the column-wise writes spread over the banks.
+  __builtin_amdgcn_s_barrier();
+  constexpr int CW = WN / 4;                                 // 16-byte fp32 chunks per staged row
+  constexpr int RP_FIT = NS * STAGE / NW / (WN * 4);         // rows of the wave's block that fit its LDS share
+  constexpr int RP = RP_FIT >= WM ? WM : RP_FIT / 32 * 32;   // rows per pass
+  static_assert(RP >= 32 && WM % RP == 0 && 64 % CW == 0, "epilogue staging does not fit");
+  constexpr int TI = RP / 32, RPI = 64 / CW;                 // 32-row blocks per pass; rows per read instruction
+  float* stg = reinterpret_cast<float*>(lds + wave * (RP * WN * 4));
+  const int wr_row = lane & 31, wr_half = lane >> 5;
+  const int rd_chunk = lane % CW, rd_row = lane / CW;
+  const int n = n0 + wn * WN + rd_chunk * 4;
+  const bool n_ok = n < a.N;
+  constexpr bool RES32 = EPI == EPI_BIAS_RES32_OUT32 || EPI == EPI_BIAS_RES32_OUT16;
+  constexpr bool GELU = EPI == EPI_GELU_TANH || EPI == EPI_GELU_ERF;
+  constexpr bool DGELU = EPI == EPI_DGELU_TANH || EPI == EPI_DGELU_ERF;
+  float bias_v[4] = {0.f, 0.f, 0.f, 0.f};
+  if constexpr (EPI == EPI_BIAS_RES || RES32 || GELU) {
+    if (a.bias && n_ok) {
+      const bf16x4 b = *reinterpret_cast<const bf16x4*>(a.bias + n);
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int m = mrow + i * 32;
-    if (m >= a.M) continue;
+      for (int e = 0; e < 4; ++e) bias_v[e] = (float)b[e];
+    }
+  }
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
+  for (int pass = 0; pass < WM / RP; ++pass) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int n = ncol + j * 32 + g * 8;
-        if (n >= a.N) continue;
-        const size_t o = (size_t)m * a.N + n;
+    for (int ii = 0; ii < TI; ++ii)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int row = ii * 32 + wr_row, chunk = j * 8 + g * 2 + wr_half;
+          f32x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = acc[pass * TI + ii][j][g * 4 + e];
+          *reinterpret_cast<f32x4*>(stg + row * WN + ((chunk ^ (row & (CW - 1))) * 4)) = v;
+        }
+    // LDS operations of one wave complete in order: no wait is needed between the
+    // writes above and the reads below, only that the compiler keeps their order
+    asm volatile("" ::: "memory");
+    // UB rows at a time: all loads of a batch are issued before the first is used
+    constexpr int UB = 8;
+    static_assert((RP / RPI) % UB == 0, "row batches");
+    for (int it0 = 0; it0 < RP / RPI; it0 += UB) {
+      f32x4 sv[UB], in32[UB];
+      bf16x4 in16[UB];
+      bool ok[UB];
+      size_t o[UB];
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        const int row = (it0 + u) * RPI + rd_row;
+        const int m = m0 + wm * WM + pass * RP + row;
+        sv[u] = *reinterpret_cast<const f32x4*>(stg + row * WN + ((rd_chunk ^ (row & (CW - 1))) * 4));
+        ok[u] = m < a.M && n_ok;
+        o[u] = ok[u] ? (size_t)m * a.N + n : 0;  // element 0 is always a valid address
+        if constexpr (EPI == EPI_ACCUM) in32[u] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(a.C) + o[u]);
+        if constexpr (RES32) in32[u] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(a.residual) + o[u]);
+        if constexpr (DGELU) in16[u] = *reinterpret_cast<const bf16x4*>(a.dgelu_u + o[u]);
+        if constexpr (EPI == EPI_BIAS_RES) {
+          if (a.residual) in16[u] = *reinterpret_cast<const bf16x4*>(static_cast<const bf16*>(a.residual) + o[u]);
+          else
+#pragma unroll
+            for (int e = 0; e < 4; ++e) in16[u][e] = (bf16)0.f;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        if (!ok[u]) continue;
         float v[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e];
+        for (int e = 0; e < 4; ++e) v[e] = sv[u][e] + bias_v[e];
         if constexpr (EPI == EPI_ACCUM) {
-          float* C = static_cast<float*>(a.C);
-          f32x4 c = *reinterpret_cast<const f32x4*>(C + o);
+          f32x4 c;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) c[e] += v[e];
-          *reinterpret_cast<f32x4*>(C + o) = c;
-        } else {
-          bf16* C = static_cast<bf16*>(a.C);
-          constexpr bool RES32 = EPI == EPI_BIAS_RES32_OUT32 || EPI == EPI_BIAS_RES32_OUT16;
-          if constexpr (EPI == EPI_BIAS_RES || RES32 || EPI == EPI_GELU_TANH || EPI == EPI_GELU_ERF) {
-            if (a.bias) {
-              const bf16x4 b = *reinterpret_cast<const bf16x4*>(a.bias + n);
+          for (int e = 0; e < 4; ++e) c[e] = in32[u][e] + v[e];
+          *reinterpret_cast<f32x4*>(static_cast<float*>(a.C) + o[u]) = c;
+        } else if constexpr (GELU) {
+          bf16x4 uq, gq;
 #pragma unroll
-              for (int e = 0; e < 4; ++e) v[e] += (float)b[e];
-            }
+          for (int e = 0; e < 4; ++e) {
+            uq[e] = (bf16)v[e];
+            gq[e] = (bf16)gelu_f<EPI == EPI_GELU_TANH ? 0 : 1>(v[e]);
           }
-          if constexpr (EPI == EPI_GELU_TANH || EPI == EPI_GELU_ERF) {
-            bf16x4 u, gq;
+          *reinterpret_cast<bf16x4*>(static_cast<bf16*>(a.C) + o[u]) = uq;
+          *reinterpret_cast<bf16x4*>(a.gelu_out + o[u]) = gq;
+        } else {
+          if constexpr (DGELU) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              u[e] = (bf16)v[e];
-              gq[e] = (bf16)gelu_f<EPI == EPI_GELU_TANH ? 0 : 1>(v[e]);
-            }
-            *reinterpret_cast<bf16x4*>(C + o) = u;
-            *reinterpret_cast<bf16x4*>(a.gelu_out + o) = gq;
+            for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f<EPI == EPI_DGELU_TANH ? 0 : 1>((float)in16[u][e]);
+          }
+          if constexpr (EPI == EPI_BIAS_RES) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += (float)in16[u][e];
+          }
+          if constexpr (RES32) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += in32[u][e];
+          }
+          if constexpr (EPI == EPI_BIAS_RES32_OUT32) {
+            f32x4 out;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) out[e] = v[e];
+            *reinterpret_cast<f32x4*>(static_cast<float*>(a.C) + o[u]) = out;
           } else {
-            if constexpr (EPI == EPI_DGELU_TANH || EPI == EPI_DGELU_ERF) {
-              const bf16x4 u = *reinterpret_cast<const bf16x4*>(a.dgelu_u + o);
+            bf16x4 out;
 #pragma unroll
-              for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f<EPI == EPI_DGELU_TANH ? 0 : 1>((float)u[e]);
-            }
-            if constexpr (EPI == EPI_BIAS_RES) {
-              if (a.residual) {
-                const bf16x4 r = *reinterpret_cast<const bf16x4*>(static_cast<const bf16*>(a.residual) + o);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] += (float)r[e];
-              }
-            }
-            if constexpr (RES32) {
-              const f32x4 r = *reinterpret_cast<const f32x4*>(static_cast<const float*>(a.residual) + o);
-#pragma unroll
-              for (int e = 0; e < 4; ++e) v[e] += r[e];
-            }
-            if constexpr (EPI == EPI_BIAS_RES32_OUT32) {
-              f32x4 out;
-#pragma unroll
-              for (int e = 0; e < 4; ++e) out[e] = v[e];
-              *reinterpret_cast<f32x4*>(static_cast<float*>(a.C) + o) = out;
-            } else {
-              bf16x4 out;
-#pragma unroll
-              for (int e = 0; e < 4; ++e) out[e] = (bf16)v[e];
-              *reinterpret_cast<bf16x4*>(C + o) = out;
-            }
+            for (int e = 0; e < 4; ++e) out[e] = (bf16)v[e];
+            *reinterpret_cast<bf16x4*>(static_cast<bf16*>(a.C) + o[u]) = out;
           }
         }
       }
