@@ -137,7 +137,9 @@ int gpt_stage_prepare(const gpt_stage_params* p, void* prepared, void* stream);
  *   act_stash device, gpt_stage_stash_bytes(); written; opaque; one per
  *             in-flight micro-batch; stays valid until its backward has run
  *   y         device, [B,S,H] cfg.dtype, written
- * Needs p->workspace of workspace_bytes(cfg, 0) (may be NULL when that is 0). */
+ * Needs p->workspace of workspace_bytes(cfg, 0) (may be NULL when that is 0); it uses
+ * the first workspace_bytes(cfg, 0) bytes.  Concurrent forward calls must not share
+ * a workspace. */
 int gpt_stage_fwd(const gpt_stage_params* p, const void* x, void* act_stash,
                   void* y, void* stream);
 
@@ -147,8 +149,10 @@ int gpt_stage_fwd(const gpt_stage_params* p, const void* x, void* act_stash,
  *   dx        device, [B,S,H] cfg.dtype, written; may alias dy
  *   dparams   device, fp32, gpt_stage_grad_bytes(); ACCUMULATED into (+=): the
  *             caller zeroes it before the first micro-batch
- * Needs p->workspace of workspace_bytes(cfg, 1).  Concurrent backward calls
- * must not share dparams or workspace. */
+ * Needs p->workspace of workspace_bytes(cfg, 1), which includes workspace_bytes(cfg, 0)
+ * at its start: the backward phase only touches the bytes after those, so ONE forward and
+ * ONE backward call may run concurrently (different streams) on the same workspace.
+ * Concurrent backward calls must not share dparams or workspace. */
 int gpt_stage_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy,
                   void* dx, void* dparams, void* stream);
 
@@ -238,13 +242,20 @@ int gpt_stage_op_colsum(int dtype, int M, int N, const void* A, float* colsum,
                         float* partial, void* stream);
 
 /* Causal attention.  qkv [B,S,3P] ([Q|K|V], P = n_heads*head_dim); out [B,S,P];
- * lse fp32 [B,n_heads,S] = log sum_j exp(s_ij) of each causal row. */
+ * lse fp32 [B,n_heads,S] = log sum_j exp(s_ij) of each causal row.
+ * scratch: device memory of gpt_stage_op_attention_scratch_bytes(.., phase) bytes,
+ * 256-byte aligned, phase 0 for the forward and 1 for the backward call (may be NULL
+ * where that size is 0); contents are not kept between calls.  The size query returns
+ * 0 for arguments the calls would reject. */
+size_t gpt_stage_op_attention_scratch_bytes(int dtype, int B, int S, int n_heads, int head_dim,
+                                            int phase);
 int gpt_stage_op_attention_fwd(int dtype, int B, int S, int n_heads, int head_dim,
-                               const void* qkv, void* out, float* lse, void* stream);
-/* dqkv [B,S,3P] written; delta: fp32 scratch [B,n_heads,S]. */
+                               const void* qkv, void* out, float* lse, void* scratch,
+                               void* stream);
+/* dqkv [B,S,3P] written. */
 int gpt_stage_op_attention_bwd(int dtype, int B, int S, int n_heads, int head_dim,
                                const void* qkv, const void* out, const float* lse,
-                               const void* dout, void* dqkv, float* delta, void* stream);
+                               const void* dout, void* dqkv, void* scratch, void* stream);
 
 #ifdef __cplusplus
 }

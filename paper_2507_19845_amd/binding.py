@@ -32,7 +32,8 @@ EXPORTS = (
     "gpt_stage_fwd", "gpt_stage_bwd", "gpt_stage_fwd_only", "gpt_stage_bwd_only", "gpt_stage_fwd_bwd",
     "gpt_stage_op_layernorm_fwd", "gpt_stage_op_layernorm_bwd_scratch_bytes",
     "gpt_stage_op_layernorm_bwd", "gpt_stage_op_gemm", "gpt_stage_op_colsum_scratch_bytes",
-    "gpt_stage_op_colsum", "gpt_stage_op_attention_fwd", "gpt_stage_op_attention_bwd",
+    "gpt_stage_op_colsum", "gpt_stage_op_attention_scratch_bytes", "gpt_stage_op_attention_fwd",
+    "gpt_stage_op_attention_bwd",
     "gpt_stage_trace_create", "gpt_stage_trace_destroy", "gpt_stage_trace_reset",
     "gpt_stage_trace_collect", "gpt_stage_trace_op_name",
 )
@@ -99,7 +100,8 @@ def lib() -> C.CDLL:
         "gpt_stage_op_gemm": (i32, [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp]),
         "gpt_stage_op_colsum_scratch_bytes": (sz, [i32, i32]),
         "gpt_stage_op_colsum": (i32, [i32, i32, i32, vp, vp, vp, vp]),
-        "gpt_stage_op_attention_fwd": (i32, [i32, i32, i32, i32, i32, vp, vp, vp, vp]),
+        "gpt_stage_op_attention_scratch_bytes": (sz, [i32, i32, i32, i32, i32, i32]),
+        "gpt_stage_op_attention_fwd": (i32, [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]),
         "gpt_stage_op_attention_bwd": (i32, [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
         "gpt_stage_trace_create": (i32, [i32, C.POINTER(vp)]),
         "gpt_stage_trace_destroy": (i32, [vp]),
@@ -319,15 +321,19 @@ def gpt_stage_op_colsum(dtype, M, N, A, colsum, partial, stream=None):
     _check(lib().gpt_stage_op_colsum(dtype, M, N, _ptr(A), _ptr(colsum), _ptr(partial), _stream(stream)))
 
 
-def gpt_stage_op_attention_fwd(dtype, B, S, n_heads, head_dim, qkv, out, lse, stream=None):
+def gpt_stage_op_attention_scratch_bytes(dtype, B, S, n_heads, head_dim, phase: int) -> int:
+    return lib().gpt_stage_op_attention_scratch_bytes(dtype, B, S, n_heads, head_dim, phase)
+
+
+def gpt_stage_op_attention_fwd(dtype, B, S, n_heads, head_dim, qkv, out, lse, scratch, stream=None):
     _check(lib().gpt_stage_op_attention_fwd(dtype, B, S, n_heads, head_dim, _ptr(qkv), _ptr(out),
-                                            _ptr(lse), _stream(stream)))
+                                            _ptr(lse), _ptr(scratch), _stream(stream)))
 
 
-def gpt_stage_op_attention_bwd(dtype, B, S, n_heads, head_dim, qkv, out, lse, dout, dqkv, delta,
+def gpt_stage_op_attention_bwd(dtype, B, S, n_heads, head_dim, qkv, out, lse, dout, dqkv, scratch,
                                stream=None):
     _check(lib().gpt_stage_op_attention_bwd(dtype, B, S, n_heads, head_dim, _ptr(qkv), _ptr(out),
-                                            _ptr(lse), _ptr(dout), _ptr(dqkv), _ptr(delta),
+                                            _ptr(lse), _ptr(dout), _ptr(dqkv), _ptr(scratch),
                                             _stream(stream)))
 
 

@@ -52,11 +52,14 @@ hipError_t attention_bwd_simple(int dtype, int B, int S, int a, int d, const voi
                                 const void* out, const float* lse, const void* dout, void* dqkv,
                                 float* delta, hipStream_t st);
 
-// bf16 MFMA attention (head_dim 64 or 128).
+// bf16 MFMA attention (head_dim 64 or 128).  scratch: device memory of
+// attention_mfma_scratch_bytes(B, S, a, d, phase) bytes (phase 0 forward: the transposed
+// image of V; phase 1 backward: delta and the transposed images of Q, K and dO).
+size_t attention_mfma_scratch_bytes(int B, int S, int a, int d, int phase);
 hipError_t attention_fwd_mfma(int B, int S, int a, int d, const void* qkv, void* out, float* lse,
-                              hipStream_t st);
+                              void* scratch, hipStream_t st);
 hipError_t attention_bwd_mfma(int B, int S, int a, int d, const void* qkv, const void* out,
-                              const float* lse, const void* dout, void* dqkv, float* delta,
+                              const float* lse, const void* dout, void* dqkv, void* scratch,
                               hipStream_t st);
 
 }  // namespace gpts

@@ -84,22 +84,30 @@ StashLayer stash_layer(const gpt_stage_cfg& c) {
   return s;
 }
 
-// ---- backward workspace ----------------------------------------------------------
+// ---- workspace ---------------------------------------------------------------------
+// [forward region | backward region]: a forward and a backward call on different streams
+// may share one workspace, their regions are disjoint.  The forward region is the
+// attention kernels' scratch; offsets in BwdWs are relative to the whole workspace.
+size_t attention_scratch_bytes(int dtype, int B, int S, int a, int d, int phase);
+size_t fwd_ws_bytes(const gpt_stage_cfg& c) {
+  Dims D(c);
+  return align_up(attention_scratch_bytes(c.dtype, D.B, D.S, D.a, D.d, 0), 256);
+}
 struct BwdWs {
-  size_t dU, dA, dX1, dC, dQKV, delta, ping, pong, ln_part, cs_part, end;
+  size_t dU, dA, dX1, dC, dQKV, attn, ping, pong, ln_part, cs_part, end;
 };
 BwdWs bwd_ws(const gpt_stage_cfg& c) {
   Dims D(c);
   const size_t e = esize(c);
   BwdWs w;
-  size_t o = 0;
+  size_t o = fwd_ws_bytes(c);
   auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
   w.dU = take((size_t)D.T * D.F * e);
   w.dA = take((size_t)D.T * D.H * e);
   w.dX1 = take((size_t)D.T * D.H * e);
   w.dC = take((size_t)D.T * D.P * e);
   w.dQKV = take((size_t)D.T * 3 * D.P * e);
-  w.delta = take((size_t)D.B * D.a * D.S * 4);
+  w.attn = take(attention_scratch_bytes(c.dtype, D.B, D.S, D.a, D.d, 1));
   w.ping = take((size_t)D.T * D.H * e);
   w.pong = take((size_t)D.T * D.H * e);
   w.ln_part = take(ln_bwd_scratch_bytes(D.T, D.H));
@@ -197,17 +205,23 @@ hipError_t gemm(int dtype, int form, int M, int N, int K, const void* A, const v
 }
 
 // Attention: MFMA kernels for bf16 with head_dim 64/128, the plain FMA kernels otherwise.
+// scratch: attention_scratch_bytes(.., phase) bytes of device memory.
+bool attention_uses_mfma(int dtype, int d) { return dtype == GPTS_BF16 && (d == 64 || d == 128); }
+size_t attention_scratch_bytes(int dtype, int B, int S, int a, int d, int phase) {
+  if (attention_uses_mfma(dtype, d)) return attention_mfma_scratch_bytes(B, S, a, d, phase);
+  return phase == 0 ? 0 : align_up((size_t)B * a * S * sizeof(float), 256);  // delta
+}
 hipError_t attention_fwd(int dtype, int B, int S, int a, int d, const void* qkv, void* out,
-                         float* lse, hipStream_t st) {
-  if (dtype == GPTS_BF16 && (d == 64 || d == 128)) return attention_fwd_mfma(B, S, a, d, qkv, out, lse, st);
+                         float* lse, void* scratch, hipStream_t st) {
+  if (attention_uses_mfma(dtype, d)) return attention_fwd_mfma(B, S, a, d, qkv, out, lse, scratch, st);
   return attention_fwd_simple(dtype, B, S, a, d, qkv, out, lse, st);
 }
 hipError_t attention_bwd(int dtype, int B, int S, int a, int d, const void* qkv, const void* out,
-                         const float* lse, const void* dout, void* dqkv, float* delta,
+                         const float* lse, const void* dout, void* dqkv, void* scratch,
                          hipStream_t st) {
-  if (dtype == GPTS_BF16 && (d == 64 || d == 128))
-    return attention_bwd_mfma(B, S, a, d, qkv, out, lse, dout, dqkv, delta, st);
-  return attention_bwd_simple(dtype, B, S, a, d, qkv, out, lse, dout, dqkv, delta, st);
+  if (attention_uses_mfma(dtype, d))
+    return attention_bwd_mfma(B, S, a, d, qkv, out, lse, dout, dqkv, scratch, st);
+  return attention_bwd_simple(dtype, B, S, a, d, qkv, out, lse, dout, dqkv, static_cast<float*>(scratch), st);
 }
 
 int check_call(const gpt_stage_params* p) {
@@ -227,6 +241,7 @@ int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, 
   if (!x || !act_stash || !y || misaligned(x) || misaligned(act_stash) || misaligned(y))
     return fail(GPTS_EINVAL, "x / act_stash / y NULL or not 16-byte aligned");
   if (x == y) return fail(GPTS_EINVAL, "y must not alias x");
+  if (!p->workspace && fwd_ws_bytes(p->cfg) > 0) return fail(GPTS_EINVAL, "forward needs a workspace");
   const gpt_stage_cfg& c = p->cfg;
   const Dims D(c);
   const size_t e = esize(c);
@@ -264,7 +279,7 @@ int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, 
     ep.b_image = img(l, 0, 0);
     GPTS_OP(GPTS_TR_GEMM_FWD, 0, 0, gf(D.T, 3 * D.P, D.H), gb(D.T, 3 * D.P, D.H, e), gemm(dt, 0, D.T, 3 * D.P, D.H, s + sl.A, w(l, GPTS_W_QKV), s + sl.QKV, ep, st), "qkv gemm");
     GPTS_OP(GPTS_TR_ATTN_FWD, 0, 0, attn_fl, (double)D.T * 4 * D.P * e, attention_fwd(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
-                                  reinterpret_cast<float*>(s + sl.LSE), st), "attention fwd");
+                                  reinterpret_cast<float*>(s + sl.LSE), p->workspace, st), "attention fwd");
     ep = GemmEpilogue();
     ep.bias = w(l, GPTS_B_O);
     ep.residual = X;
@@ -318,7 +333,7 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
   void* dX1 = wk + ws.dX1;
   void* dC = wk + ws.dC;
   void* dQKV = wk + ws.dQKV;
-  float* delta = reinterpret_cast<float*>(wk + ws.delta);
+  void* attn_scratch = wk + ws.attn;
 
   // algorithmic work of one operator, for the tracer: flops of an M x N x K product and
   // the bytes it must move (operands once, result once)
@@ -361,7 +376,7 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     GPTS_OP(GPTS_TR_BIAS_GRAD, 1, 1, 0.0, TH * e, colsum(dt, D.T, D.H, dX1, g(l, GPTS_B_O), cs_part, st), "out-proj bias grad");
     // c = attention(qkv)
     GPTS_OP(GPTS_TR_ATTN_BWD, 0, 1, 2.0 * attn_fl, (double)D.T * 9 * D.P * e, attention_bwd(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
-                                  reinterpret_cast<const float*>(s + sl.LSE), dC, dQKV, delta, st),
+                                  reinterpret_cast<const float*>(s + sl.LSE), dC, dQKV, attn_scratch, st),
              "attention bwd");
     // qkv = a Wqkv^T + bqkv
     GPTS_OP(GPTS_TR_GEMM_DGRAD, 0, 1, gf(D.T, D.H, 3 * D.P), gb(D.T, D.H, 3 * D.P, e), gemm(dt, 1, D.T, D.H, 3 * D.P, dQKV, w(l, GPTS_W_QKV), dA, d_qkv, st), "qkv dgrad");
@@ -410,7 +425,7 @@ size_t gpt_stage_stash_bytes(const gpt_stage_cfg* c) {
 }
 size_t gpt_stage_workspace_bytes(const gpt_stage_cfg* c, int phase) {
   if (gpt_stage_validate(c) != GPTS_OK) return 0;
-  return phase == 0 ? 0 : bwd_ws(*c).end;
+  return phase == 0 ? fwd_ws_bytes(*c) : bwd_ws(*c).end;
 }
 int gpt_stage_param_offset(const gpt_stage_cfg* c, int layer, int tensor_id, size_t* elem_off, size_t* n_elem) {
   int rc = gpt_stage_validate(c);
@@ -607,21 +622,29 @@ int gpt_stage_op_colsum(int dtype, int M, int N, const void* A, float* out, floa
   GPTS_TRY(colsum(dtype, M, N, A, out, partial, static_cast<hipStream_t>(stream)), "colsum");
   return GPTS_OK;
 }
+size_t gpt_stage_op_attention_scratch_bytes(int dtype, int B, int S, int n_heads, int head_dim, int phase) {
+  if (!op_dtype_ok(dtype) || B < 1 || S < 1 || n_heads < 1 || (head_dim != 32 && head_dim != 64 && head_dim != 128) ||
+      (phase != 0 && phase != 1))
+    return 0;
+  return attention_scratch_bytes(dtype, B, S, n_heads, head_dim, phase);
+}
 int gpt_stage_op_attention_fwd(int dtype, int B, int S, int n_heads, int head_dim, const void* qkv,
-                               void* out, float* lse, void* stream) {
+                               void* out, float* lse, void* scratch, void* stream) {
   if (!op_dtype_ok(dtype) || !qkv || !out || !lse) return fail(GPTS_EINVAL, "attention_fwd: bad argument");
   if (B < 1 || S < 1 || n_heads < 1 || (head_dim != 32 && head_dim != 64 && head_dim != 128))
     return fail(GPTS_ESHAPE, "attention_fwd: head_dim must be 32, 64 or 128");
-  GPTS_TRY(attention_fwd(dtype, B, S, n_heads, head_dim, qkv, out, lse, static_cast<hipStream_t>(stream)), "attention_fwd");
+  if (!scratch && attention_scratch_bytes(dtype, B, S, n_heads, head_dim, 0) > 0)
+    return fail(GPTS_EINVAL, "attention_fwd: scratch is NULL");
+  GPTS_TRY(attention_fwd(dtype, B, S, n_heads, head_dim, qkv, out, lse, scratch, static_cast<hipStream_t>(stream)), "attention_fwd");
   return GPTS_OK;
 }
 int gpt_stage_op_attention_bwd(int dtype, int B, int S, int n_heads, int head_dim, const void* qkv,
                                const void* out, const float* lse, const void* dout, void* dqkv,
-                               float* delta, void* stream) {
-  if (!op_dtype_ok(dtype) || !qkv || !out || !lse || !dout || !dqkv || !delta) return fail(GPTS_EINVAL, "attention_bwd: bad argument");
+                               void* scratch, void* stream) {
+  if (!op_dtype_ok(dtype) || !qkv || !out || !lse || !dout || !dqkv || !scratch) return fail(GPTS_EINVAL, "attention_bwd: bad argument");
   if (B < 1 || S < 1 || n_heads < 1 || (head_dim != 32 && head_dim != 64 && head_dim != 128))
     return fail(GPTS_ESHAPE, "attention_bwd: head_dim must be 32, 64 or 128");
-  GPTS_TRY(attention_bwd(dtype, B, S, n_heads, head_dim, qkv, out, lse, dout, dqkv, delta,
+  GPTS_TRY(attention_bwd(dtype, B, S, n_heads, head_dim, qkv, out, lse, dout, dqkv, scratch,
                                 static_cast<hipStream_t>(stream)), "attention_bwd");
   return GPTS_OK;
 }

@@ -430,7 +430,9 @@ def test_op_attention(dtype, Bn, S, a, d):
     qd = B.to_device(qkv, dtype)
     out = torch.empty((Bn, S, P), dtype=qd.dtype, device="cuda")
     lse = torch.empty((Bn, a, S), dtype=torch.float32, device="cuda")
-    B.gpt_stage_op_attention_fwd(dt, Bn, S, a, d, qd, out, lse)
+    scratch = [torch.empty(max(B.gpt_stage_op_attention_scratch_bytes(dt, Bn, S, a, d, ph), 256),
+                           dtype=torch.uint8, device="cuda") for ph in (0, 1)]
+    B.gpt_stage_op_attention_fwd(dt, Bn, S, a, d, qd, out, lse, scratch[0])
     ref = orc.attention_fwd(qkv, a, d)
     assert max_norm_err(B.to_host(out), ref) <= tol
     # lse against its definition: log sum_{j<=i} exp(q_i.k_j/sqrt(d))
@@ -444,8 +446,7 @@ def test_op_attention(dtype, Bn, S, a, d):
             ref_lse[b, n] = m + np.log(np.exp(s - m[:, None]).sum(1))
     assert np.abs(B.to_host(lse) - ref_lse).max() <= 1e-4 * max(1.0, np.abs(ref_lse).max())
     dqkv = torch.empty_like(qd)
-    delta = torch.empty_like(lse)
-    B.gpt_stage_op_attention_bwd(dt, Bn, S, a, d, qd, out, lse, B.to_device(dout, dtype), dqkv, delta)
+    B.gpt_stage_op_attention_bwd(dt, Bn, S, a, d, qd, out, lse, B.to_device(dout, dtype), dqkv, scratch[1])
     rd = orc.attention_bwd(qkv, dout, a, d)
     got = B.to_host(dqkv)
     for i, nm in enumerate("qkv"):
