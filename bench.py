@@ -21,6 +21,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+# HBM traffic of the matrix-product kernel on the default workload, from two rocprofv3 --pmc
+# passes (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, averaged over the 768 launches of a step; the
+# summary under profiles/ has the commands and the per-kernel figures).  Only reported while
+# the kernel source is the one the counters were taken on.
+GEMM_TRAFFIC = {"workload": "decoupled_bf16", "bytes_per_launch": 783.9 * 2**20,
+                "algorithmic_bytes_per_launch": 357.3 * 2**20,
+                "source_sha256_16": "db05079b4d9b5bd8"}
 PEAK_FP32_TFLOPS = 157.3    # MI355X fp32 vector
 DEFAULT_WORKLOAD = "decoupled_bf16"
 
@@ -28,8 +35,8 @@ DEFAULT_WORKLOAD = "decoupled_bf16"
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prepare", action="store_true",
@@ -68,6 +75,21 @@ def cpu_baseline(shape):
             "seconds": dt,
             "sample": f"1 layer, 1 micro-batch, first {s.seq} tokens x batch {s.batch} of {shape.name} "
                       f"(fp64 numpy oracle, {flops / 1e12:.3f} model TFLOP causal-aware)"}
+
+
+def gemm_traffic(shape):
+    """Measured HBM bytes per launch of the matrix-product kernel, or None when no counters
+    exist for this workload or the kernel source has changed since they were taken."""
+    import hashlib
+    src = os.path.join(ROOT, "paper_2507_19845_amd", "csrc", "gemm_mfma.hip")
+    try:
+        sha = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+    except OSError:
+        return None
+    if shape.name != GEMM_TRAFFIC["workload"] or sha != GEMM_TRAFFIC["source_sha256_16"]:
+        return None
+    return {"bytes_per_launch": GEMM_TRAFFIC["bytes_per_launch"],
+            "algorithmic_bytes_per_launch": GEMM_TRAFFIC["algorithmic_bytes_per_launch"], "unit": "B"}
 
 
 def traced_pass(step, shape, n_ops, steps):
@@ -109,7 +131,7 @@ def traced_pass(step, shape, n_ops, steps):
     peak = PEAK_BF16_TFLOPS if shape.dtype == "bf16" else PEAK_FP32_TFLOPS
     achieved = fl / ms / 1e9
     roof = {"bound": "mfma" if shape.dtype == "bf16" else "alu", "achieved": achieved, "peak": peak,
-            "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+            "unit": "TFLOP/s", "frac": achieved / peak, "traffic": gemm_traffic(shape),
             "kernel": "gemm_mfma_kernel (forward NT, dgrad NN, wgrad TN products of the 4 linears)",
             "launches": n, "avg_launch_ms": ms / n, "flops_per_launch": fl / n,
             "measured": f"hipEvent pairs around every launch, {steps} traced step(s) after the timed region",
