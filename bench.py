@@ -26,7 +26,6 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # summary under profiles/ has the commands and the per-kernel figures).  Only reported while
 # the kernel source is the one the counters were taken on.
 GEMM_TRAFFIC = {"workload": "decoupled_bf16", "bytes_per_launch": 783.9 * 2**20,
-                "algorithmic_bytes_per_launch": 357.3 * 2**20,
                 "source_sha256_16": "db05079b4d9b5bd8"}
 PEAK_FP32_TFLOPS = 157.3    # MI355X fp32 vector
 DEFAULT_WORKLOAD = "decoupled_bf16"
@@ -88,8 +87,7 @@ def gemm_traffic(shape):
         return None
     if shape.name != GEMM_TRAFFIC["workload"] or sha != GEMM_TRAFFIC["source_sha256_16"]:
         return None
-    return {"bytes_per_launch": GEMM_TRAFFIC["bytes_per_launch"],
-            "algorithmic_bytes_per_launch": GEMM_TRAFFIC["algorithmic_bytes_per_launch"], "unit": "B"}
+    return GEMM_TRAFFIC["bytes_per_launch"]
 
 
 def traced_pass(step, shape, n_ops, steps):
@@ -133,6 +131,8 @@ def traced_pass(step, shape, n_ops, steps):
     roof = {"bound": "mfma" if shape.dtype == "bf16" else "alu", "achieved": achieved, "peak": peak,
             "unit": "TFLOP/s", "frac": achieved / peak, "traffic": gemm_traffic(shape),
             "kernel": "gemm_mfma_kernel (forward NT, dgrad NN, wgrad TN products of the 4 linears)",
+            "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
+            "algorithmic_bytes_per_launch": sum(c["bytes"] for c in gemm) / n,
             "launches": n, "avg_launch_ms": ms / n, "flops_per_launch": fl / n,
             "measured": f"hipEvent pairs around every launch, {steps} traced step(s) after the timed region",
             "dropped_records": dropped}
