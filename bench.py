@@ -41,6 +41,10 @@ def parse():
     ap.add_argument("--no-prepare", action="store_true",
                     help="run the products on the raw weights instead of the prepared images")
     ap.add_argument("--schedule", choices=["auto", "coupled", "decoupled"], default="auto")
+    ap.add_argument("--dpp", type=int, default=0, metavar="CHUNKS",
+                    help="instead of the stage benchmark: split the workload's layers into CHUNKS model "
+                         "chunks and time the depth-first / breadth-first traversals of the "
+                         "(micro-batch, chunk) task matrix")
     return ap.parse_args()
 
 
@@ -139,6 +143,79 @@ def traced_pass(step, shape, n_ops, steps):
     return roof, table
 
 
+def dpp_bench(args, shape):
+    """Traversal policies over CHUNKS chunks x the workload's micro-batches: wall time per
+    iteration, peak stash, and when each chunk's gradients are complete."""
+    import torch
+    from paper_2507_19845_amd import binding as B
+    from paper_2507_19845_amd import synth
+    C, M = args.dpp, shape.n_microbatches
+    if shape.n_layers % C:
+        raise SystemExit(f"--dpp {C}: the workload has {shape.n_layers} layers")
+    Lc = shape.n_layers // C
+    cs = shape.with_(n_layers=Lc)
+    cfg = B.make_cfg(cs)
+    n = B.gpt_stage_param_count(cfg)
+    tdt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    ws = torch.empty(max(B.gpt_stage_workspace_bytes(cfg, 1), 256), dtype=torch.uint8, device="cuda")
+    weights, prepared, dps, chunks = [], [], [], []
+    for j in range(C):
+        w = torch.empty(n, dtype=tdt, device="cuda")
+        for l in range(Lc):
+            p = synth.make_layer_params(shape, j * Lc + l, 0)
+            for tid, name in enumerate(synth.TENSOR_NAMES):
+                off, cnt = B.gpt_stage_param_offset(cfg, l, tid)
+                w[off:off + cnt].copy_(B.to_device(p[name].reshape(-1), shape.dtype))
+        weights.append(w)
+        dps.append(torch.zeros(n, dtype=torch.float32, device="cuda"))
+        pb = B.gpt_stage_prepared_bytes(cfg)
+        prep = torch.empty(max(pb, 256), dtype=torch.uint8, device="cuda") if pb and not args.no_prepare else None
+        prepared.append(prep)
+        chunks.append(B.gpt_stage_params(cfg=cfg, weights=w.data_ptr(), workspace=ws.data_ptr(),
+                                         prepared=prep.data_ptr() if prep is not None else None, trace=None))
+    xs = [B.to_device(synth.make_x(shape, 0, m), shape.dtype) for m in range(M)]
+    dys = [B.to_device(synth.make_dy(shape, 0, m), shape.dtype) for m in range(M)]
+    ys = [torch.empty_like(x) for x in xs]
+    dxs = [torch.empty_like(x) for x in xs]
+    slot = B.gpt_dpp_stash_slot_bytes(chunks)
+    stash = torch.empty(slot * C * M, dtype=torch.uint8, device="cuda")
+    act = torch.empty(B.gpt_dpp_act_slot_bytes(cfg) * (M + 2), dtype=torch.uint8, device="cuda")
+    flops = B.gpt_stage_model_flops(cfg, True) * C * M
+    rows = {}
+    for name, pol, cap in (("dfc", B.GPT_DPP_DFC, 0), ("bfc", B.GPT_DPP_BFC, 0),
+                           ("bfc_best_effort_cap_half", B.GPT_DPP_BFC_BEST_EFFORT, C * M // 2)):
+        ev0 = torch.cuda.Event(enable_timing=True)
+        ready = [torch.cuda.Event(enable_timing=True) for _ in range(C)]
+        for e in [ev0] + ready:
+            e.record()
+
+        def step(timed_events):
+            for j in range(C):
+                if prepared[j] is not None:
+                    B.gpt_stage_prepare(chunks[j].cfg, weights[j], prepared[j])
+            return B.gpt_dpp_run(pol, chunks, xs, dys, ys, dxs, dps, stash, act, max_live_stash=cap,
+                                 grad_ready=ready if timed_events else None)
+        for _ in range(args.warmup):
+            step(False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            rep = step(False)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        ev0.record()
+        rep = step(True)
+        torch.cuda.synchronize()
+        rows[name] = {"ms_per_iteration": ms, "TFLOP/s": flops / ms / 1e9,
+                      "peak_live_stash": rep.peak_live_stash,
+                      "peak_stash_GiB": rep.peak_live_stash * rep.stash_slot_bytes / 2**30,
+                      "peak_boundary_buffers": rep.peak_live_act,
+                      "grad_ready_ms_after_start": [ev0.elapsed_time(e) for e in ready]}
+    print(json.dumps({"metric": "MegaDPP traversal policies on 1 MI355X", "unit": "ms per iteration",
+                      "config": {"workload": shape.name, "chunks": C, "layers_per_chunk": Lc, "n_microbatches": M},
+                      "steps": args.steps, "warmup": args.warmup, "policies": rows}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -151,6 +228,8 @@ def main():
         raise SystemExit("bench.py needs a GPU")
     B.lib()
     shape = pick_workload(args.workload)
+    if args.dpp:
+        return dpp_bench(args, shape)
     n_mb = shape.n_microbatches
     decoupled = (n_mb > 1) if args.schedule == "auto" else (args.schedule == "decoupled")
     bufs = B.StageBuffers(shape, n_stash=n_mb if decoupled else 1)

@@ -46,7 +46,8 @@ typedef enum {
   GPTS_OK = 0,
   GPTS_EINVAL = -1, /* null or misaligned pointer, bad enum value            */
   GPTS_ESHAPE = -2, /* shape outside what the kernels support (see validate) */
-  GPTS_EHIP = -3    /* a HIP launch failed; text via gpt_stage_strerror      */
+  GPTS_EHIP = -3,   /* a HIP launch failed; text via gpt_stage_strerror      */
+  GPTS_ENOMEM = -4  /* a caller-provided pool or array is too small           */
 } gpts_status;
 
 enum { GPTS_FP32 = 0, GPTS_BF16 = 1 };     /* cfg.dtype */
@@ -256,6 +257,76 @@ int gpt_stage_op_attention_fwd(int dtype, int B, int S, int n_heads, int head_di
 int gpt_stage_op_attention_bwd(int dtype, int B, int S, int n_heads, int head_dim,
                                const void* qkv, const void* out, const float* lse,
                                const void* dout, void* dqkv, void* scratch, void* stream);
+
+/* ---- traversal of the (micro-batch, model chunk) task matrix ---------------------------
+ * Section 5.2 (MegaDPP, "parallel scheduler"): the compute tasks of one iteration form a
+ * matrix indexed by (model chunk, micro-batch) and a schedule is a traversal order of it.
+ * Here the chunks are stages that sit on one GPU one after the other (chunk j+1 consumes the
+ * output of chunk j); every forward task F(i,j) = micro-batch i on chunk j has a backward
+ * task B(i,j).  Dependencies: F(i,j) after F(i,j-1); B(i,j) after F(i,j) and B(i,j+1).
+ *   GPT_DPP_DFC  depth first: the same micro-batch through all chunks, forward then
+ *                backward, before the next micro-batch (earliest backward, smallest stash)
+ *   GPT_DPP_BFC  breadth first: all micro-batches on the same chunk before the next chunk;
+ *                a chunk's gradients are complete as early as possible, the stash is largest
+ *   GPT_DPP_BFC_BEST_EFFORT  breadth first over windows of W consecutive micro-batches, W the
+ *                largest number whose stash fits: W = clamp(max_live_stash / n_chunks, 1, M)
+ *                (section 5.2: breadth first "as long as it does not cause" out-of-memory)
+ * A window of W micro-batches runs F(i,0) for its i, then F(i,1), ..., then B(i,C-1) for its
+ * i, ..., B(i,0); DFC is W = 1, BFC is W = M.  Inside a chunk micro-batches always run in
+ * ascending order, so gradient accumulation order -- and every result bit -- is the same for
+ * all three policies. */
+enum { GPT_DPP_DFC = 0, GPT_DPP_BFC = 1, GPT_DPP_BFC_BEST_EFFORT = 2 };
+enum { GPT_DPP_FWD = 0, GPT_DPP_BWD = 1 };
+typedef struct {
+  int32_t phase;      /* GPT_DPP_FWD or GPT_DPP_BWD */
+  int32_t microbatch; /* i */
+  int32_t chunk;      /* j */
+} gpt_dpp_task;
+
+/* Host only.  Writes the 2*n_chunks*n_microbatches tasks in execution order into tasks
+ * (capacity entries; GPTS_ENOMEM if too few).  max_live_stash: for BEST_EFFORT the number of
+ * (micro-batch, chunk) activation stashes that may be alive at once (ignored otherwise; values
+ * below n_chunks still schedule one micro-batch at a time).  peak_live_stash (may be NULL)
+ * receives the largest number of stashes alive at once under the order written.
+ * Returns the number of tasks, or a negative gpts_status. */
+int gpt_dpp_plan(int policy, int n_chunks, int n_microbatches, int max_live_stash,
+                 gpt_dpp_task* tasks, int capacity, int* peak_live_stash);
+
+typedef struct {
+  int32_t n_chunks, n_microbatches, policy, max_live_stash;
+  const gpt_stage_params* chunks; /* host array [n_chunks]; all chunks share batch, seq,
+                                     hidden and dtype; workspaces may be shared (one stream) */
+  const void* const* x;           /* host array [M] of device pointers: inputs of chunk 0   */
+  const void* const* dy;          /* [M]: gradients w.r.t. the last chunk's outputs         */
+  void* const* y;                 /* [M]: outputs of the last chunk, written                */
+  void* const* dx;                /* [M]: gradients w.r.t. x, written                       */
+  void* const* dparams;           /* [n_chunks]: fp32 gradient buffer of each chunk (+=)    */
+  void* stash_pool;               /* device; slots of gpt_dpp_stash_slot_bytes() each       */
+  size_t stash_pool_bytes;
+  void* act_pool;                 /* device; chunk-boundary activations and gradients,
+                                     slots of gpt_dpp_act_slot_bytes() each                 */
+  size_t act_pool_bytes;
+  void* const* grad_ready;        /* NULL, or [n_chunks] hipEvent_t: event j is recorded when
+                                     the last backward task of chunk j has been enqueued   */
+} gpt_dpp_job;
+
+typedef struct {
+  int32_t n_tasks;
+  int32_t peak_live_stash;   /* stashes alive at once                  */
+  int32_t peak_live_act;     /* boundary buffers alive at once         */
+  size_t  stash_slot_bytes;
+  size_t  act_slot_bytes;
+} gpt_dpp_report;
+
+size_t gpt_dpp_stash_slot_bytes(const gpt_stage_params* chunks, int n_chunks); /* 0 on bad input */
+size_t gpt_dpp_act_slot_bytes(const gpt_stage_cfg* cfg);                        /* 0 on bad input */
+
+/* Enqueues every task of the job on `stream` in the order gpt_dpp_plan gives, through the
+ * decoupled entry points; stash slots and boundary buffers are taken from the two pools and
+ * returned as soon as their consumer has been enqueued (one stream: in-order execution makes
+ * that safe).  GPTS_ENOMEM if a pool is too small for the policy -- nothing has been enqueued
+ * then.  report may be NULL.  Asynchronous like every other call. */
+int gpt_dpp_run(const gpt_dpp_job* job, void* stream, gpt_dpp_report* report);
 
 #ifdef __cplusplus
 }

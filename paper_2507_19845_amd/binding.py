@@ -36,6 +36,7 @@ EXPORTS = (
     "gpt_stage_op_attention_bwd",
     "gpt_stage_trace_create", "gpt_stage_trace_destroy", "gpt_stage_trace_reset",
     "gpt_stage_trace_collect", "gpt_stage_trace_op_name",
+    "gpt_dpp_plan", "gpt_dpp_stash_slot_bytes", "gpt_dpp_act_slot_bytes", "gpt_dpp_run",
 )
 
 
@@ -55,6 +56,30 @@ class gpt_stage_trace_rec(C.Structure):
     _fields_ = [("op", C.c_int32), ("sub", C.c_int32), ("layer", C.c_int32), ("phase", C.c_int32),
                 ("start_ms", C.c_float), ("dur_ms", C.c_float), ("flops", C.c_double),
                 ("bytes", C.c_double)]
+
+
+class gpt_dpp_task(C.Structure):
+    _fields_ = [("phase", C.c_int32), ("microbatch", C.c_int32), ("chunk", C.c_int32)]
+
+
+class gpt_dpp_job(C.Structure):
+    _fields_ = [("n_chunks", C.c_int32), ("n_microbatches", C.c_int32), ("policy", C.c_int32),
+                ("max_live_stash", C.c_int32), ("chunks", C.POINTER(gpt_stage_params)),
+                ("x", C.POINTER(C.c_void_p)), ("dy", C.POINTER(C.c_void_p)),
+                ("y", C.POINTER(C.c_void_p)), ("dx", C.POINTER(C.c_void_p)),
+                ("dparams", C.POINTER(C.c_void_p)), ("stash_pool", C.c_void_p),
+                ("stash_pool_bytes", C.c_size_t), ("act_pool", C.c_void_p),
+                ("act_pool_bytes", C.c_size_t), ("grad_ready", C.POINTER(C.c_void_p))]
+
+
+class gpt_dpp_report(C.Structure):
+    _fields_ = [("n_tasks", C.c_int32), ("peak_live_stash", C.c_int32), ("peak_live_act", C.c_int32),
+                ("stash_slot_bytes", C.c_size_t), ("act_slot_bytes", C.c_size_t)]
+
+
+GPT_DPP_DFC, GPT_DPP_BFC, GPT_DPP_BFC_BEST_EFFORT = 0, 1, 2
+GPT_DPP_FWD, GPT_DPP_BWD = 0, 1
+GPTS_ENOMEM = -4
 
 
 class GptStageError(RuntimeError):
@@ -109,6 +134,10 @@ def lib() -> C.CDLL:
         "gpt_stage_trace_collect": (i32, [vp, C.POINTER(gpt_stage_trace_rec), i32, C.POINTER(i32),
                                           C.POINTER(i32)]),
         "gpt_stage_trace_op_name": (C.c_char_p, [i32]),
+        "gpt_dpp_plan": (i32, [i32, i32, i32, i32, C.POINTER(gpt_dpp_task), i32, C.POINTER(i32)]),
+        "gpt_dpp_stash_slot_bytes": (sz, [parp, i32]),
+        "gpt_dpp_act_slot_bytes": (sz, [cfgp]),
+        "gpt_dpp_run": (i32, [C.POINTER(gpt_dpp_job), vp, C.POINTER(gpt_dpp_report)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -335,6 +364,60 @@ def gpt_stage_op_attention_bwd(dtype, B, S, n_heads, head_dim, qkv, out, lse, do
     _check(lib().gpt_stage_op_attention_bwd(dtype, B, S, n_heads, head_dim, _ptr(qkv), _ptr(out),
                                             _ptr(lse), _ptr(dout), _ptr(dqkv), _ptr(scratch),
                                             _stream(stream)))
+
+
+# ---- traversal of the (micro-batch, chunk) task matrix ---------------------------------
+def gpt_dpp_plan(policy: int, n_chunks: int, n_microbatches: int, max_live_stash: int = 0):
+    """-> ([(phase, microbatch, chunk), ...], peak_live_stash)"""
+    cap = 2 * max(n_chunks, 0) * max(n_microbatches, 0)
+    arr = (gpt_dpp_task * max(cap, 1))()
+    peak = C.c_int(0)
+    n = lib().gpt_dpp_plan(policy, n_chunks, n_microbatches, max_live_stash, arr, cap, C.byref(peak))
+    if n < 0:
+        _check(n)
+    return [(arr[k].phase, arr[k].microbatch, arr[k].chunk) for k in range(n)], peak.value
+
+
+def _params_array(chunks):
+    arr = (gpt_stage_params * len(chunks))()
+    for k, c in enumerate(chunks):
+        arr[k] = c
+    return arr
+
+
+def gpt_dpp_stash_slot_bytes(chunks) -> int:
+    return lib().gpt_dpp_stash_slot_bytes(_params_array(chunks), len(chunks))
+
+
+def gpt_dpp_act_slot_bytes(cfg) -> int:
+    return lib().gpt_dpp_act_slot_bytes(C.byref(cfg))
+
+
+def gpt_dpp_run(policy: int, chunks, xs, dys, ys, dxs, dparams, stash_pool, act_pool,
+                max_live_stash: int = 0, grad_ready=None, stream=None) -> gpt_dpp_report:
+    """chunks: list of gpt_stage_params; xs, dys, ys, dxs: one tensor per micro-batch;
+    dparams: one fp32 tensor per chunk; stash_pool / act_pool: uint8 tensors (act_pool may be
+    None for a single chunk); grad_ready: None or one torch.cuda.Event per chunk."""
+    def ptrs(ts):
+        a = (C.c_void_p * len(ts))()
+        for k, t in enumerate(ts):
+            a[k] = _ptr(t)
+        return a
+    keep = [_params_array(chunks), ptrs(xs), ptrs(dys), ptrs(ys), ptrs(dxs), ptrs(dparams)]
+    ev = None
+    if grad_ready is not None:
+        ev = (C.c_void_p * len(grad_ready))()
+        for k, e in enumerate(grad_ready):
+            ev[k] = _event(e)
+    job = gpt_dpp_job(n_chunks=len(chunks), n_microbatches=len(xs), policy=policy,
+                      max_live_stash=max_live_stash, chunks=keep[0], x=keep[1], dy=keep[2],
+                      y=keep[3], dx=keep[4], dparams=keep[5],
+                      stash_pool=_ptr(stash_pool), stash_pool_bytes=stash_pool.numel() if stash_pool is not None else 0,
+                      act_pool=_ptr(act_pool), act_pool_bytes=act_pool.numel() if act_pool is not None else 0,
+                      grad_ready=ev)
+    rep = gpt_dpp_report()
+    _check(lib().gpt_dpp_run(C.byref(job), _stream(stream), C.byref(rep)))
+    return rep
 
 
 # ---- device-memory plumbing (torch tensors as buffers; no arithmetic) --------------

@@ -62,4 +62,7 @@ hipError_t attention_bwd_mfma(int B, int S, int a, int d, const void* qkv, const
                               const float* lse, const void* dout, void* dqkv, void* scratch,
                               hipStream_t st);
 
+// Records the thread's error text and returns `code` (for sources outside stage.hip).
+int set_error(int code, const char* msg);
+
 }  // namespace gpts

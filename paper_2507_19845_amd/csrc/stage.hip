@@ -392,6 +392,10 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
 
 }  // namespace
 
+namespace gpts {
+int set_error(int code, const char* msg) { return fail(code, msg); }
+}  // namespace gpts
+
 extern "C" {
 
 int gpt_stage_validate(const gpt_stage_cfg* c) {
@@ -448,7 +452,7 @@ double gpt_stage_model_flops(const gpt_stage_cfg* c, int causal_aware) {
 const char* gpt_stage_strerror(int code) {
   switch (code) {
     case GPTS_OK: return "ok";
-    case GPTS_EINVAL: case GPTS_ESHAPE: case GPTS_EHIP: return g_err[0] ? g_err : "error";
+    case GPTS_EINVAL: case GPTS_ESHAPE: case GPTS_EHIP: case GPTS_ENOMEM: return g_err[0] ? g_err : "error";
   }
   return "unknown status";
 }

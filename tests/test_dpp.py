@@ -1,0 +1,199 @@
+"""Traversal of the (micro-batch, chunk) task matrix (section 5.2, MegaDPP "parallel scheduler").
+
+CPU part: the Python oracle of the three traversal orders is pinned to what the paper fixes
+(figure 3: 8 chunks x 8 micro-batches = 64 tasks named "i-j"; row-wise vs column-wise order;
+depth first releases activation memory soonest, breadth first completes a chunk's gradients
+soonest) and to brute force on small matrices; the library's host-side planner must give the
+same order, task for task.  GPU part: the driver runs several chunks through the decoupled
+entry points and must reproduce the oracle of the whole layer stack, bit-identically across
+policies."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import dpp_oracle as dpo
+from paper_2507_19845_amd import binding as B
+from paper_2507_19845_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "dpp_task_matrix.txt")
+POLICY = {"dfc": B.GPT_DPP_DFC, "bfc": B.GPT_DPP_BFC, "bfc_best_effort": B.GPT_DPP_BFC_BEST_EFFORT}
+
+
+def _golden():
+    kv = {}
+    for line in open(GOLDEN):
+        if line.strip() and not line.startswith("#"):
+            k, v = line.split()
+            kv[k] = int(v)
+    return kv
+
+
+def test_figure3_matrix():
+    g = _golden()
+    C, M = g["chunks"], g["microbatches"]
+    mat = dpo.task_matrix(C, M)
+    assert sum(len(r) for r in mat) == g["tasks"] == 64
+    assert mat[3][5] == "3-5"          # "i-j": micro-batch i on chunk j
+    assert len({t for r in mat for t in r}) == 64
+    # executing "along the micro-batch (row) or model-chunk (column) dimension":
+    fwd = lambda order: [dpo.task_name(i, j) for ph, i, j in order if ph == "F"]
+    assert fwd(dpo.depth_first(C, M)) == [t for row in mat for t in row]
+    assert fwd(dpo.breadth_first(C, M)) == [mat[i][j] for j in range(C) for i in range(M)]
+
+
+@pytest.mark.parametrize("C,M", [(1, 1), (1, 5), (4, 1), (2, 3), (8, 8), (3, 7)])
+def test_orders_are_valid_and_have_the_stated_memory_behaviour(C, M):
+    dfc, bfc = dpo.depth_first(C, M), dpo.breadth_first(C, M)
+    assert dpo.dependencies_hold(dfc, C, M) and dpo.dependencies_hold(bfc, C, M)
+    # depth first: one micro-batch in flight; breadth first: every stash alive at the turn
+    assert dpo.peak_live_stash(dfc) == C
+    assert dpo.peak_live_stash(bfc) == C * M
+    # breadth first completes the LAST chunk's gradients after C*M forward + M backward tasks,
+    # depth first only with the last micro-batch
+    assert dpo.gradient_ready_position(bfc, C)[C - 1] == C * M + M - 1
+    assert dpo.gradient_ready_position(dfc, C)[C - 1] == 2 * C * (M - 1) + C
+    for cap in range(0, C * M + 3):
+        be = dpo.best_effort_breadth_first(C, M, cap)
+        assert dpo.dependencies_hold(be, C, M)
+        peak = dpo.peak_live_stash(be)
+        assert peak <= max(cap, C)                 # never above the allowance (one micro-batch minimum)
+        assert peak > cap - C or peak == C * M     # and as breadth-first as the allowance permits
+        if cap >= C * M:
+            assert be == bfc
+        if cap < 2 * C:
+            assert be == dfc
+
+
+def test_orders_against_brute_force():
+    """On a 2x2 matrix enumerate every valid order: depth first has the smallest peak stash
+    among all of them, breadth first the earliest completion of the last chunk's gradients."""
+    C = M = 2
+    tasks = [(p, i, j) for p in "FB" for i in range(M) for j in range(C)]
+    valid = [o for o in itertools.permutations(tasks) if dpo.dependencies_hold(list(o), C, M)]
+    assert len(valid) > 10
+    assert dpo.peak_live_stash(dpo.depth_first(C, M)) == min(dpo.peak_live_stash(o) for o in valid)
+    ready = lambda o: dpo.gradient_ready_position(o, C)[C - 1]
+    assert ready(dpo.breadth_first(C, M)) == min(ready(o) for o in valid)
+
+
+def test_planted_mistake_is_caught():
+    bad = dpo.breadth_first(3, 2)
+    k = bad.index(("B", 0, 2))
+    bad[k], bad[k + 1] = ("B", 0, 1), bad[k]     # backward of chunk 1 before chunk 2
+    assert not dpo.dependencies_hold(bad, 3, 2)
+
+
+@pytest.mark.parametrize("C,M", [(1, 1), (4, 8), (8, 8), (3, 5)])
+def test_library_plan_equals_oracle(C, M):
+    ph = {B.GPT_DPP_FWD: "F", B.GPT_DPP_BWD: "B"}
+    for name, pol in POLICY.items():
+        for cap in ([0] if name != "bfc_best_effort" else [0, C, 2 * C, 2 * C + 1, C * M - 1, C * M, 10 * C * M]):
+            got, peak = B.gpt_dpp_plan(pol, C, M, cap)
+            ref = dpo.traversal(name, C, M, cap)
+            assert [(ph[p], i, j) for p, i, j in got] == ref, (name, cap)
+            assert peak == dpo.peak_live_stash(ref)
+
+
+def test_library_plan_rejects_bad_arguments():
+    with pytest.raises(B.GptStageError):
+        B.gpt_dpp_plan(7, 2, 2, 0)
+    with pytest.raises(B.GptStageError):
+        B.gpt_dpp_plan(B.GPT_DPP_DFC, 0, 2, 0)
+    arr = (B.gpt_dpp_task * 4)()
+    assert B.lib().gpt_dpp_plan(B.GPT_DPP_DFC, 2, 2, 0, arr, 4, None) == B.GPTS_ENOMEM
+
+
+# ---- GPU: the driver ---------------------------------------------------------------------
+def _run_dpp(shape, C, M, policy, cap, params_np):
+    import torch
+    chunk_shape = shape.with_(n_layers=shape.n_layers // C)
+    Lc = chunk_shape.n_layers
+    cfg = B.make_cfg(chunk_shape)
+    nparam = B.gpt_stage_param_count(cfg)
+    ws = torch.empty(max(B.gpt_stage_workspace_bytes(cfg, 1), 256), dtype=torch.uint8, device="cuda")
+    chunks, weights, dps = [], [], []
+    for j in range(C):
+        w = torch.empty(nparam, dtype=torch.bfloat16 if shape.dtype == "bf16" else torch.float32, device="cuda")
+        for l in range(Lc):
+            for tid, name in enumerate(synth.TENSOR_NAMES):
+                off, n = B.gpt_stage_param_offset(cfg, l, tid)
+                w[off:off + n].copy_(B.to_device(params_np[j * Lc + l][name].reshape(-1), shape.dtype))
+        weights.append(w)
+        dps.append(torch.zeros(nparam, dtype=torch.float32, device="cuda"))
+        chunks.append(B.gpt_stage_params(cfg=cfg, weights=w.data_ptr(), workspace=ws.data_ptr(), prepared=None, trace=None))
+    xs = [B.to_device(synth.make_x(shape, 0, m), shape.dtype) for m in range(M)]
+    dys = [B.to_device(synth.make_dy(shape, 0, m), shape.dtype) for m in range(M)]
+    ys = [torch.empty_like(x) for x in xs]
+    dxs = [torch.empty_like(x) for x in xs]
+    _, peak = B.gpt_dpp_plan(policy, C, M, cap)
+    stash = torch.empty(B.gpt_dpp_stash_slot_bytes(chunks) * peak, dtype=torch.uint8, device="cuda")
+    act = torch.empty(B.gpt_dpp_act_slot_bytes(cfg) * (2 * M + 2), dtype=torch.uint8, device="cuda")
+    rep = B.gpt_dpp_run(policy, chunks, xs, dys, ys, dxs, dps, stash, act, max_live_stash=cap)
+    torch.cuda.synchronize()
+    assert rep.n_tasks == 2 * C * M and rep.peak_live_stash == peak
+    return ([B.to_host(t) for t in ys], [B.to_host(t) for t in dxs], [t.cpu().numpy() for t in dps], cfg, rep)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_dpp_driver_matches_oracle_and_policies_agree_bitwise(dtype):
+    from oracle import gpt_stage_oracle as orc
+    from parity_util import TOL, max_norm_err
+    C, M = 3, 4
+    shape = synth.StageShape(name="dpp", n_layers=3, hidden=128, n_heads=2, head_dim=64, ffn=256, seq=128,
+                             batch=1, dtype=dtype, n_microbatches=M, bias_std=0.02, ln_jitter=0.1)
+    print(f"[case] dpp driver {dtype} C={C} M={M}", flush=True)
+    params_np = [{k: synth.to_storage(v, dtype) for k, v in synth.make_layer_params(shape, l, 0).items()}
+                 for l in range(shape.n_layers)]
+    runs = {}
+    for name, cap in (("dfc", 0), ("bfc", 0), ("bfc_best_effort", 2 * C)):
+        runs[name] = _run_dpp(shape, C, M, POLICY[name], cap, params_np)
+    # memory behaviour as planned
+    assert runs["dfc"][4].peak_live_stash == C and runs["bfc"][4].peak_live_stash == C * M
+    assert runs["bfc_best_effort"][4].peak_live_stash == 2 * C
+    # identical bits whatever the traversal
+    for name in ("bfc", "bfc_best_effort"):
+        for a, b in zip(runs["dfc"][:3], runs[name][:3]):
+            for ta, tb in zip(a, b):
+                assert np.array_equal(ta, tb), name
+    # and the oracle of the whole stack
+    p64 = [{k: v.astype(np.float64) for k, v in lp.items()} for lp in params_np]
+    grads = None
+    tol = TOL[dtype]
+    ys, dxs, dps, cfg, _ = runs["dfc"]
+    for m in range(M):
+        x = synth.to_storage(synth.make_x(shape, 0, m), dtype).astype(np.float64)
+        dy = synth.to_storage(synth.make_dy(shape, 0, m), dtype).astype(np.float64)
+        y, dx, grads = orc.stage_fwd_bwd(x, dy, p64, shape.n_heads, shape.head_dim, shape.ln_eps, shape.gelu, grads=grads)
+        assert max_norm_err(ys[m], y) <= tol and max_norm_err(dxs[m], dx) <= tol
+    Lc = shape.n_layers // C
+    for j in range(C):
+        for l in range(Lc):
+            for tid, name in enumerate(synth.TENSOR_NAMES):
+                off, n = B.gpt_stage_param_offset(cfg, l, tid)
+                ref = grads[j * Lc + l][name].reshape(-1)
+                assert max_norm_err(dps[j][off:off + n], ref) <= tol, (j, l, name)
+
+
+@pytest.mark.gpu
+def test_dpp_driver_refuses_small_pools():
+    import torch
+    shape = synth.StageShape(name="dpp", n_layers=1, hidden=128, n_heads=2, head_dim=64, ffn=256, seq=64,
+                             batch=1, dtype="fp32", n_microbatches=2)
+    cfg = B.make_cfg(shape)
+    n = B.gpt_stage_param_count(cfg)
+    w = torch.zeros(n, device="cuda")
+    ws = torch.empty(max(B.gpt_stage_workspace_bytes(cfg, 1), 256), dtype=torch.uint8, device="cuda")
+    chunks = [B.gpt_stage_params(cfg=cfg, weights=w.data_ptr(), workspace=ws.data_ptr(), prepared=None, trace=None)] * 2
+    t = [torch.zeros(1, 64, 128, device="cuda") for _ in range(2)]
+    dps = [torch.zeros(n, device="cuda") for _ in range(2)]
+    slot = B.gpt_dpp_stash_slot_bytes(chunks)
+    stash = torch.empty(slot * 3, dtype=torch.uint8, device="cuda")     # breadth first needs 4
+    act = torch.empty(B.gpt_dpp_act_slot_bytes(cfg) * 4, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.GptStageError) as e:
+        B.gpt_dpp_run(B.GPT_DPP_BFC, chunks, t, t, [torch.empty_like(a) for a in t], [torch.empty_like(a) for a in t], dps, stash, act)
+    assert e.value.code == B.GPTS_ENOMEM
+    B.gpt_dpp_run(B.GPT_DPP_DFC, chunks, t, t, [torch.empty_like(a) for a in t], [torch.empty_like(a) for a in t], dps, stash, act)
+    torch.cuda.synchronize()
