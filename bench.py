@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--no-prepare", action="store_true",
                     help="run the products on the raw weights instead of the prepared images")
     ap.add_argument("--schedule", choices=["auto", "coupled", "decoupled"], default="auto")
+    ap.add_argument("--recompute", action="store_true",
+                    help="activation recomputation: smaller stash, LayerNorm/GeLU outputs rebuilt in backward")
     ap.add_argument("--dpp", type=int, default=0, metavar="CHUNKS",
                     help="instead of the stage benchmark: split the workload's layers into CHUNKS model "
                          "chunks and time the depth-first / breadth-first traversals of the "
@@ -228,6 +230,8 @@ def main():
         raise SystemExit("bench.py needs a GPU")
     B.lib()
     shape = pick_workload(args.workload)
+    if args.recompute:
+        shape = shape.with_(recompute=True)
     if args.dpp:
         return dpp_bench(args, shape)
     n_mb = shape.n_microbatches
@@ -275,7 +279,7 @@ def main():
     flops_dense = B.gpt_stage_model_flops(bufs.cfg, False) * n_mb
     tflops = flops / (ms * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if shape.dtype == "bf16" else PEAK_FP32_TFLOPS
-    ops_per_step = 22 * shape.n_layers * n_mb
+    ops_per_step = (25 if shape.recompute else 22) * shape.n_layers * n_mb
     roof, table = traced_pass(step, shape, ops_per_step, max(1, min(args.steps, 2)))
     out = {
         "metric": "model TFLOP/s for one stage fwd+bwd on 1 MI355X",
@@ -291,6 +295,8 @@ def main():
                    "schedule": "decoupled: all fwd on stream F, then all bwd on stream B" if decoupled
                                else "coupled fwd+bwd per micro-batch", "flop_count": "causal-aware",
                    "prepared_weights": "rebuilt every step (timed)" if prepare else "off",
+                   "stash": "recompute LayerNorm/GeLU outputs in backward" if shape.recompute else "full",
+                   "stash_GiB_per_microbatch": B.gpt_stage_stash_bytes(bufs.cfg) / 2**30,
                    "input_gen_seconds": gen_s},
         "roofline": roof,
         "kernels": table,

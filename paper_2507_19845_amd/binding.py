@@ -44,7 +44,7 @@ class gpt_stage_cfg(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("ffn", C.c_int32), ("seq", C.c_int32),
                 ("batch", C.c_int32), ("dtype", C.c_int32), ("gelu", C.c_int32),
-                ("ln_eps", C.c_float)]
+                ("ln_eps", C.c_float), ("recompute", C.c_int32)]
 
 
 class gpt_stage_params(C.Structure):
@@ -177,7 +177,7 @@ def make_cfg(s: synth.StageShape) -> gpt_stage_cfg:
                          ffn=s.ffn, seq=s.seq, batch=s.batch,
                          dtype=GPTS_BF16 if s.dtype == "bf16" else GPTS_FP32,
                          gelu=GPTS_GELU_ERF if s.gelu == "erf" else GPTS_GELU_TANH,
-                         ln_eps=s.ln_eps)
+                         ln_eps=s.ln_eps, recompute=1 if s.recompute else 0)
 
 
 # ---- host-side queries --------------------------------------------------------

@@ -299,6 +299,31 @@ hipError_t ln_bwd(int dtype, bool x_f32, int T_rows, int H, const void* dout, co
                               (const bf16*)gamma, (const bf16*)dres, (bf16*)dx, dgamma, dbeta, partial, st);
 }
 
+// g[i] = gelu(u[i]), 8 elements per thread (recomputation of the MLP activation)
+template <typename T, int KIND>
+__global__ __launch_bounds__(256) void gelu_kernel(const T* __restrict__ u, T* __restrict__ g, size_t n8) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n8) return;
+  float v[8];
+  load8(u + i * 8, v);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = gelu_f<KIND>(v[e]);
+  store8(g + i * 8, v);
+}
+
+hipError_t gelu_fwd(int dtype, int kind, const void* u, void* g, size_t n, hipStream_t st) {
+  const size_t n8 = n / 8;
+  dim3 grid((unsigned)((n8 + 255) / 256)), blk(256);
+  if (dtype == 0) {
+    if (kind == 0) hipLaunchKernelGGL((gelu_kernel<float, 0>), grid, blk, 0, st, (const float*)u, (float*)g, n8);
+    else hipLaunchKernelGGL((gelu_kernel<float, 1>), grid, blk, 0, st, (const float*)u, (float*)g, n8);
+  } else {
+    if (kind == 0) hipLaunchKernelGGL((gelu_kernel<bf16, 0>), grid, blk, 0, st, (const bf16*)u, (bf16*)g, n8);
+    else hipLaunchKernelGGL((gelu_kernel<bf16, 1>), grid, blk, 0, st, (const bf16*)u, (bf16*)g, n8);
+  }
+  return hipGetLastError();
+}
+
 hipError_t widen_to_f32(const void* in, float* out, size_t n, hipStream_t st) {
   const size_t n8 = n / 8;
   hipLaunchKernelGGL(widen_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, st, (const bf16*)in,

@@ -446,7 +446,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const MfmaArgs a) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             uq[e] = (bf16)v[e];
-            gq[e] = (bf16)gelu_f<EPI == EPI_GELU_TANH ? 0 : 1>(v[e]);
+            // g is the GeLU of u AS STORED, so that a backward pass that recomputes g from
+            // the stashed u gets the same bits
+            gq[e] = (bf16)gelu_f<EPI == EPI_GELU_TANH ? 0 : 1>((float)uq[e]);
           }
           *reinterpret_cast<bf16x4*>(static_cast<bf16*>(a.C) + o[u]) = uq;
           *reinterpret_cast<bf16x4*>(a.gelu_out + o[u]) = gq;

@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(
         if constexpr (GELU >= 0) {
           if (gelu_out) {
             C[o] = from_f32<T>(v);
-            gelu_out[o] = from_f32<T>(gelu_f<GELU < 0 ? 0 : GELU>(v));
+            gelu_out[o] = from_f32<T>(gelu_f<GELU < 0 ? 0 : GELU>(to_f32(C[o])));  // GeLU of u as stored
             continue;
           }
           if (dgelu_u) v *= gelu_grad_f<GELU < 0 ? 0 : GELU>(to_f32(dgelu_u[o]));

@@ -17,6 +17,8 @@ hipError_t ln_bwd(int dtype, bool x_f32, int T_rows, int H, const void* dout, co
                   float* dgamma, float* dbeta, float* partial, hipStream_t st);
 // out[i] = (float) in[i] for n bf16 elements (n a multiple of 8)
 hipError_t widen_to_f32(const void* in, float* out, size_t n, hipStream_t st);
+// g = gelu(u) elementwise (kind 0 tanh form, 1 erf form); n a multiple of 8
+hipError_t gelu_fwd(int dtype, int kind, const void* u, void* g, size_t n, hipStream_t st);
 size_t colsum_scratch_bytes(int M, int N);
 hipError_t colsum(int dtype, int M, int N, const void* A, float* out, float* partial,
                   hipStream_t st);

@@ -60,8 +60,9 @@ size_t tensor_off(const Dims& D, int layer, int id) {
 //   X [T,H]f32  mean1,rstd1 [T]f32  A [T,H]  QKV [T,3P]  C [T,P]  LSE [B,a,S]f32
 //   X1 [T,H]f32 mean2,rstd2 [T]f32  A2 [T,H] U [T,F]  G [T,F]
 // every region 256-byte aligned.
+constexpr size_t kAbsent = ~(size_t)0;
 struct StashLayer {
-  size_t X, stat1, A, QKV, C, LSE, X1, stat2, A2, U, G, end;
+  size_t X, stat1, A, QKV, C, LSE, X1, stat2, A2, U, G, end;   // kAbsent: not stashed
 };
 StashLayer stash_layer(const gpt_stage_cfg& c) {
   Dims D(c);
@@ -69,17 +70,18 @@ StashLayer stash_layer(const gpt_stage_cfg& c) {
   StashLayer s;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
+  const bool full = c.recompute == 0;   // with recomputation A, A2 and G are not stashed
   s.X = take((size_t)D.T * D.H * kResBytes);
   s.stat1 = take((size_t)2 * D.T * 4);
-  s.A = take((size_t)D.T * D.H * e);
+  s.A = full ? take((size_t)D.T * D.H * e) : kAbsent;
   s.QKV = take((size_t)D.T * 3 * D.P * e);
   s.C = take((size_t)D.T * D.P * e);
   s.LSE = take((size_t)D.B * D.a * D.S * 4);
   s.X1 = take((size_t)D.T * D.H * kResBytes);
   s.stat2 = take((size_t)2 * D.T * 4);
-  s.A2 = take((size_t)D.T * D.H * e);
+  s.A2 = full ? take((size_t)D.T * D.H * e) : kAbsent;
   s.U = take((size_t)D.T * D.F * e);
-  s.G = take((size_t)D.T * D.F * e);
+  s.G = full ? take((size_t)D.T * D.F * e) : kAbsent;
   s.end = o;
   return s;
 }
@@ -89,12 +91,24 @@ StashLayer stash_layer(const gpt_stage_cfg& c) {
 // may share one workspace, their regions are disjoint.  The forward region is the
 // attention kernels' scratch; offsets in BwdWs are relative to the whole workspace.
 size_t attention_scratch_bytes(int dtype, int B, int S, int a, int d, int phase);
-size_t fwd_ws_bytes(const gpt_stage_cfg& c) {
+struct FwdWs {
+  size_t attn, A, G, end;   // A (shared by both LayerNorm outputs) and G only with recomputation
+};
+FwdWs fwd_ws(const gpt_stage_cfg& c) {
   Dims D(c);
-  return align_up(attention_scratch_bytes(c.dtype, D.B, D.S, D.a, D.d, 0), 256);
+  const size_t e = esize(c);
+  FwdWs w;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
+  w.attn = take(attention_scratch_bytes(c.dtype, D.B, D.S, D.a, D.d, 0));
+  w.A = c.recompute ? take((size_t)D.T * D.H * e) : kAbsent;
+  w.G = c.recompute ? take((size_t)D.T * D.F * e) : kAbsent;
+  w.end = o;
+  return w;
 }
+size_t fwd_ws_bytes(const gpt_stage_cfg& c) { return fwd_ws(c).end; }
 struct BwdWs {
-  size_t dU, dA, dX1, dC, dQKV, attn, ping, pong, ln_part, cs_part, end;
+  size_t dU, dA, dX1, dC, dQKV, attn, ping, pong, ln_part, cs_part, rA, rG, rstat, end;
 };
 BwdWs bwd_ws(const gpt_stage_cfg& c) {
   Dims D(c);
@@ -115,6 +129,10 @@ BwdWs bwd_ws(const gpt_stage_cfg& c) {
   if (3 * D.P > maxn) maxn = 3 * D.P;
   if (D.F > maxn) maxn = D.F;
   w.cs_part = take(colsum_scratch_bytes(D.T, maxn));
+  // recomputed LayerNorm output (one buffer, used for A2 and then A), GeLU output, statistics
+  w.rA = c.recompute ? take((size_t)D.T * D.H * e) : kAbsent;
+  w.rG = c.recompute ? take((size_t)D.T * D.F * e) : kAbsent;
+  w.rstat = c.recompute ? take((size_t)2 * D.T * 4) : kAbsent;
   w.end = o;
   return w;
 }
@@ -266,41 +284,47 @@ int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, 
     GPTS_TRY(widen_to_f32(x, reinterpret_cast<float*>(stash + sl.X), (size_t)D.T * D.H, st), "widen x");
   else
     GPTS_TRY(hipMemcpyAsync(stash + sl.X, x, (size_t)D.T * D.H * e, hipMemcpyDeviceToDevice, st), "copy x");
+  const FwdWs fw = fwd_ws(c);
+  char* fwk = static_cast<char*>(p->workspace);
   for (int l = 0; l < D.L; ++l) {
     char* s = stash + (size_t)l * sl.end;
     void* X = s + sl.X;
     float* stat1 = reinterpret_cast<float*>(s + sl.stat1);
     float* stat2 = reinterpret_cast<float*>(s + sl.stat2);
     void* Yout = (l == D.L - 1) ? y : (void*)(s + sl.end + sl.X);
-    GPTS_OP(GPTS_TR_LN_FWD, 0, 0, 0.0, TH * (kResBytes + e), ln_fwd(dt, bf, D.T, D.H, c.ln_eps, X, w(l, GPTS_LN1_G), w(l, GPTS_LN1_B), s + sl.A, stat1,
+    // with recomputation the LayerNorm and GeLU outputs only live in the workspace
+    void* A = c.recompute ? fwk + fw.A : s + sl.A;
+    void* A2 = c.recompute ? fwk + fw.A : s + sl.A2;
+    void* G = c.recompute ? fwk + fw.G : s + sl.G;
+    GPTS_OP(GPTS_TR_LN_FWD, 0, 0, 0.0, TH * (kResBytes + e), ln_fwd(dt, bf, D.T, D.H, c.ln_eps, X, w(l, GPTS_LN1_G), w(l, GPTS_LN1_B), A, stat1,
                     stat1 + D.T, st), "ln1 fwd");
     GemmEpilogue ep;
     ep.bias = w(l, GPTS_B_QKV);
     ep.b_image = img(l, 0, 0);
-    GPTS_OP(GPTS_TR_GEMM_FWD, 0, 0, gf(D.T, 3 * D.P, D.H), gb(D.T, 3 * D.P, D.H, e), gemm(dt, 0, D.T, 3 * D.P, D.H, s + sl.A, w(l, GPTS_W_QKV), s + sl.QKV, ep, st), "qkv gemm");
+    GPTS_OP(GPTS_TR_GEMM_FWD, 0, 0, gf(D.T, 3 * D.P, D.H), gb(D.T, 3 * D.P, D.H, e), gemm(dt, 0, D.T, 3 * D.P, D.H, A, w(l, GPTS_W_QKV), s + sl.QKV, ep, st), "qkv gemm");
     GPTS_OP(GPTS_TR_ATTN_FWD, 0, 0, attn_fl, (double)D.T * 4 * D.P * e, attention_fwd(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
-                                  reinterpret_cast<float*>(s + sl.LSE), p->workspace, st), "attention fwd");
+                                  reinterpret_cast<float*>(s + sl.LSE), fwk + fw.attn, st), "attention fwd");
     ep = GemmEpilogue();
     ep.bias = w(l, GPTS_B_O);
     ep.residual = X;
     ep.residual_f32 = ep.out_f32 = bf;
     ep.b_image = img(l, 1, 0);
     GPTS_OP(GPTS_TR_GEMM_FWD, 1, 0, gf(D.T, D.H, D.P), gb(D.T, D.H, D.P, 2 * kResBytes), gemm(dt, 0, D.T, D.H, D.P, s + sl.C, w(l, GPTS_W_O), s + sl.X1, ep, st), "out-proj gemm");
-    GPTS_OP(GPTS_TR_LN_FWD, 1, 0, 0.0, TH * (kResBytes + e), ln_fwd(dt, bf, D.T, D.H, c.ln_eps, s + sl.X1, w(l, GPTS_LN2_G), w(l, GPTS_LN2_B), s + sl.A2,
+    GPTS_OP(GPTS_TR_LN_FWD, 1, 0, 0.0, TH * (kResBytes + e), ln_fwd(dt, bf, D.T, D.H, c.ln_eps, s + sl.X1, w(l, GPTS_LN2_G), w(l, GPTS_LN2_B), A2,
                     stat2, stat2 + D.T, st), "ln2 fwd");
     ep = GemmEpilogue();
     ep.bias = w(l, GPTS_B_FC1);
-    ep.gelu_out = s + sl.G;
+    ep.gelu_out = G;
     ep.gelu_kind = c.gelu;
     ep.b_image = img(l, 2, 0);
-    GPTS_OP(GPTS_TR_GEMM_FWD, 2, 0, gf(D.T, D.F, D.H), gb(D.T, D.F, D.H, 2 * e), gemm(dt, 0, D.T, D.F, D.H, s + sl.A2, w(l, GPTS_W_FC1), s + sl.U, ep, st), "fc1 gemm");
+    GPTS_OP(GPTS_TR_GEMM_FWD, 2, 0, gf(D.T, D.F, D.H), gb(D.T, D.F, D.H, 2 * e), gemm(dt, 0, D.T, D.F, D.H, A2, w(l, GPTS_W_FC1), s + sl.U, ep, st), "fc1 gemm");
     ep = GemmEpilogue();
     ep.bias = w(l, GPTS_B_FC2);
     ep.residual = s + sl.X1;
     ep.residual_f32 = bf;
     ep.out_f32 = bf && l != D.L - 1;   // the stage output y is bf16, the stream between layers fp32
     ep.b_image = img(l, 3, 0);
-    GPTS_OP(GPTS_TR_GEMM_FWD, 3, 0, gf(D.T, D.H, D.F), gb(D.T, D.H, D.F, 2 * kResBytes), gemm(dt, 0, D.T, D.H, D.F, s + sl.G, w(l, GPTS_W_FC2), Yout, ep, st), "fc2 gemm");
+    GPTS_OP(GPTS_TR_GEMM_FWD, 3, 0, gf(D.T, D.H, D.F), gb(D.T, D.H, D.F, 2 * kResBytes), gemm(dt, 0, D.T, D.H, D.F, G, w(l, GPTS_W_FC2), Yout, ep, st), "fc2 gemm");
   }
   return GPTS_OK;
 }
@@ -361,11 +385,23 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     ep.gelu_kind = c.gelu;
     ep.b_image = img(l, 3);
     GPTS_OP(GPTS_TR_GEMM_DGRAD, 3, 1, gf(D.T, D.F, D.H), gb(D.T, D.F, D.H, 2 * e), gemm(dt, 1, D.T, D.F, D.H, dY, w(l, GPTS_W_FC2), dU, ep, st), "fc2 dgrad");
-    GPTS_OP(GPTS_TR_GEMM_WGRAD, 3, 1, gf(D.H, D.F, D.T), gb(D.H, D.F, D.T, 8), gemm(dt, 2, D.H, D.F, D.T, dY, s + sl.G, g(l, GPTS_W_FC2), none, st), "fc2 wgrad");
+    const void* G = s + sl.G;
+    if (c.recompute) {
+      GPTS_OP(GPTS_TR_RECOMPUTE, 2, 1, 0.0, (double)D.T * D.F * 2 * e, gelu_fwd(dt, c.gelu, s + sl.U, wk + ws.rG, (size_t)D.T * D.F, st), "gelu recompute");
+      G = wk + ws.rG;
+    }
+    GPTS_OP(GPTS_TR_GEMM_WGRAD, 3, 1, gf(D.H, D.F, D.T), gb(D.H, D.F, D.T, 8), gemm(dt, 2, D.H, D.F, D.T, dY, G, g(l, GPTS_W_FC2), none, st), "fc2 wgrad");
     GPTS_OP(GPTS_TR_BIAS_GRAD, 3, 1, 0.0, TH * e, colsum(dt, D.T, D.H, dY, g(l, GPTS_B_FC2), cs_part, st), "fc2 bias grad");
     // u = a2 W1^T + b1
     GPTS_OP(GPTS_TR_GEMM_DGRAD, 2, 1, gf(D.T, D.H, D.F), gb(D.T, D.H, D.F, e), gemm(dt, 1, D.T, D.H, D.F, dU, w(l, GPTS_W_FC1), dA, d_fc1, st), "fc1 dgrad");
-    GPTS_OP(GPTS_TR_GEMM_WGRAD, 2, 1, gf(D.F, D.H, D.T), gb(D.F, D.H, D.T, 8), gemm(dt, 2, D.F, D.H, D.T, dU, s + sl.A2, g(l, GPTS_W_FC1), none, st), "fc1 wgrad");
+    const void* A2 = s + sl.A2;
+    if (c.recompute) {
+      float* rs = reinterpret_cast<float*>(wk + ws.rstat);
+      GPTS_OP(GPTS_TR_RECOMPUTE, 1, 1, 0.0, TH * (kResBytes + e), ln_fwd(dt, dt == GPTS_BF16, D.T, D.H, c.ln_eps, s + sl.X1, w(l, GPTS_LN2_G), w(l, GPTS_LN2_B),
+                      wk + ws.rA, rs, rs + D.T, st), "ln2 recompute");
+      A2 = wk + ws.rA;
+    }
+    GPTS_OP(GPTS_TR_GEMM_WGRAD, 2, 1, gf(D.F, D.H, D.T), gb(D.F, D.H, D.T, 8), gemm(dt, 2, D.F, D.H, D.T, dU, A2, g(l, GPTS_W_FC1), none, st), "fc1 wgrad");
     GPTS_OP(GPTS_TR_BIAS_GRAD, 2, 1, 0.0, (double)D.T * D.F * e, colsum(dt, D.T, D.F, dU, g(l, GPTS_B_FC1), cs_part, st), "fc1 bias grad");
     // a2 = LN2(x1), x1 also feeds the residual
     GPTS_OP(GPTS_TR_LN_BWD, 1, 1, 0.0, TH * (3 * e + kResBytes), ln_bwd(dt, dt == GPTS_BF16, D.T, D.H, dA, s + sl.X1, stat2, stat2 + D.T, w(l, GPTS_LN2_G), dY, dX1,
@@ -380,7 +416,14 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
              "attention bwd");
     // qkv = a Wqkv^T + bqkv
     GPTS_OP(GPTS_TR_GEMM_DGRAD, 0, 1, gf(D.T, D.H, 3 * D.P), gb(D.T, D.H, 3 * D.P, e), gemm(dt, 1, D.T, D.H, 3 * D.P, dQKV, w(l, GPTS_W_QKV), dA, d_qkv, st), "qkv dgrad");
-    GPTS_OP(GPTS_TR_GEMM_WGRAD, 0, 1, gf(3 * D.P, D.H, D.T), gb(3 * D.P, D.H, D.T, 8), gemm(dt, 2, 3 * D.P, D.H, D.T, dQKV, s + sl.A, g(l, GPTS_W_QKV), none, st), "qkv wgrad");
+    const void* A = s + sl.A;
+    if (c.recompute) {
+      float* rs = reinterpret_cast<float*>(wk + ws.rstat);
+      GPTS_OP(GPTS_TR_RECOMPUTE, 0, 1, 0.0, TH * (kResBytes + e), ln_fwd(dt, dt == GPTS_BF16, D.T, D.H, c.ln_eps, s + sl.X, w(l, GPTS_LN1_G), w(l, GPTS_LN1_B),
+                      wk + ws.rA, rs, rs + D.T, st), "ln1 recompute");
+      A = wk + ws.rA;
+    }
+    GPTS_OP(GPTS_TR_GEMM_WGRAD, 0, 1, gf(3 * D.P, D.H, D.T), gb(3 * D.P, D.H, D.T, 8), gemm(dt, 2, 3 * D.P, D.H, D.T, dQKV, A, g(l, GPTS_W_QKV), none, st), "qkv wgrad");
     GPTS_OP(GPTS_TR_BIAS_GRAD, 0, 1, 0.0, (double)D.T * 3 * D.P * e, colsum(dt, D.T, 3 * D.P, dQKV, g(l, GPTS_B_QKV), cs_part, st), "qkv bias grad");
     // a = LN1(x), x also feeds the residual
     GPTS_OP(GPTS_TR_LN_BWD, 0, 1, 0.0, TH * (3 * e + kResBytes), ln_bwd(dt, dt == GPTS_BF16, D.T, D.H, dA, s + sl.X, stat1, stat1 + D.T, w(l, GPTS_LN1_G), dX1, dXout,
@@ -403,6 +446,7 @@ int gpt_stage_validate(const gpt_stage_cfg* c) {
   if (c->dtype != GPTS_FP32 && c->dtype != GPTS_BF16) return fail(GPTS_EINVAL, "dtype must be GPTS_FP32 or GPTS_BF16");
   if (c->gelu != GPTS_GELU_TANH && c->gelu != GPTS_GELU_ERF) return fail(GPTS_EINVAL, "gelu must be GPTS_GELU_TANH or GPTS_GELU_ERF");
   if (!(c->ln_eps >= 0.f)) return fail(GPTS_EINVAL, "ln_eps must be >= 0");
+  if (c->recompute != 0 && c->recompute != 1) return fail(GPTS_EINVAL, "recompute must be 0 or 1");
   if (c->n_layers < 1 || c->batch < 1 || c->seq < 1 || c->n_heads < 1 || c->hidden < 1 || c->ffn < 1)
     return fail(GPTS_ESHAPE, "n_layers, batch, seq, n_heads, hidden, ffn must be >= 1");
   if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128)
@@ -577,6 +621,7 @@ const char* gpt_stage_trace_op_name(int op) {
     case GPTS_TR_BIAS_GRAD: return "bias_grad";
     case GPTS_TR_LN_BWD: return "layernorm_bwd";
     case GPTS_TR_ATTN_BWD: return "attention_bwd";
+    case GPTS_TR_RECOMPUTE: return "recompute";
   }
   return "unknown";
 }

@@ -51,6 +51,7 @@ class StageShape:
     out_std: float = 0.02   # std of w_o and w_fc2
     bias_std: float = 0.0
     ln_jitter: float = 0.0  # gamma = 1 + N(0, j), beta = N(0, j)
+    recompute: bool = False  # backward recomputes the LayerNorm and GeLU outputs (smaller stash)
 
     @property
     def attn_width(self) -> int:

@@ -451,3 +451,31 @@ def test_op_attention(dtype, Bn, S, a, d):
     got = B.to_host(dqkv)
     for i, nm in enumerate("qkv"):
         assert max_norm_err(got[..., i * P:(i + 1) * P], rd[..., i * P:(i + 1) * P]) <= tol, f"d{nm}"
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_recompute_variant_identical_results_smaller_stash(dtype):
+    """Activation recomputation (sections 4.1 / 5.2): the backward phase rebuilds the
+    LayerNorm and GeLU outputs instead of reading them from the stash.  Same bits, smaller
+    stash; checked against the oracle too."""
+    shape = synth.StageShape(name="rc", n_layers=2, hidden=256, n_heads=2, head_dim=64, ffn=512, seq=192,
+                             batch=2, dtype=dtype, n_microbatches=2, bias_std=0.02, ln_jitter=0.1)
+    print(f"[case] recompute {dtype}", flush=True)
+    params = [{k: synth.to_storage(v, dtype) for k, v in synth.make_layer_params(shape, l, 0).items()}
+              for l in range(shape.n_layers)]
+    xs = [synth.to_storage(synth.make_x(shape, 0, m), dtype) for m in range(2)]
+    dys = [synth.to_storage(synth.make_dy(shape, 0, m), dtype) for m in range(2)]
+    full = gpu_run(shape, params, xs, dys, decoupled=True)
+    rshape = shape.with_(recompute=True)
+    rec = gpu_run(rshape, params, xs, dys, decoupled=True)
+    for a, b in zip(full[0] + full[1], rec[0] + rec[1]):
+        assert np.array_equal(a, b)
+    for ga, gb_ in zip(full[2], rec[2]):
+        for k in ga:
+            assert np.array_equal(ga[k], gb_[k]), k
+    compare(shape, rec, oracle_run(shape, params, xs, dys))
+    e = 2 if dtype == "bf16" else 4
+    T, H, F = shape.tokens, shape.hidden, shape.ffn
+    saved = B.gpt_stage_stash_bytes(B.make_cfg(shape)) - B.gpt_stage_stash_bytes(B.make_cfg(rshape))
+    assert saved == shape.n_layers * (2 * T * H + T * F) * e
