@@ -335,6 +335,42 @@ size_t gpt_dpp_act_slot_bytes(const gpt_stage_cfg* cfg);                        
  * then.  report may be NULL.  Asynchronous like every other call. */
 int gpt_dpp_run(const gpt_dpp_job* job, void* stream, gpt_dpp_report* report);
 
+/* ---- communication coordinator, simulated on the host ------------------------------------
+ * Section 4.2 (MegaFBD, "communication coordinator"): training threads (virtual ranks) of one
+ * GPU share a control thread; a collective starts only after every rank of its group has
+ * posted the same request.  Per control thread a table holds one bit vector per communication
+ * group, one bit per virtual rank (flattened to one array).  Steps: registration (a rank sets
+ * its bit in the vector of the group it wants to communicate in), alignment (bitwise-OR
+ * all-reduce of the tables), readiness check (vector == the group's expected mask), ordered
+ * execution (ready groups in ascending group order; their vectors are cleared).
+ * Everything here runs on the host and moves no data: it models the protocol only.
+ *   group g has members group_members[group_start[g] .. group_start[g+1]-1]
+ *   control_of_rank[r] = control thread (GPU) that virtual rank r lives on */
+int gpt_fbd_coord_create(int n_ranks, int n_groups, const int32_t* group_start,
+                         const int32_t* group_members, int n_control,
+                         const int32_t* control_of_rank, void** coord);
+int gpt_fbd_coord_destroy(void* coord);
+/* bits: n_ranks + 1 chars; bits[r] = '1' if rank r is in the group (rank 0 leftmost, as in the
+ * paper's example: eight threads, group {0,1,2,3} -> "11110000") */
+int gpt_fbd_coord_expected(void* coord, int group, char* bits);
+int gpt_fbd_coord_register(void* coord, int rank, int group);            /* step 1 */
+int gpt_fbd_coord_align(void* coord);                                    /* step 2 */
+/* step 3, as seen by one control thread: ready groups in ascending order; returns the count */
+int gpt_fbd_coord_ready(void* coord, int control, int32_t* groups, int capacity);
+/* step 4: all control threads run the ready collectives in ascending group order (the tables
+ * must be aligned); their vectors are cleared; returns the count, groups[] the order */
+int gpt_fbd_coord_execute(void* coord, int32_t* groups, int capacity);
+/* Runs whole rank programs: rank r performs collectives in groups prog[prog_start[r] ..
+ * prog_start[r+1]-1], in that order, posting the next request only when the previous
+ * collective is done.  verify = 1: the coordinator protocol above, in rounds (every idle rank
+ * registers, align, execute).  verify = 0: no verification -- a control thread starts the
+ * oldest request it holds and is busy until that collective completes (the situation the
+ * section describes as deadlock-prone).  log receives the executed groups in order;
+ * *deadlocked = 1 when requests remain and nothing can proceed. */
+int gpt_fbd_coord_simulate(void* coord, const int32_t* prog_start, const int32_t* prog, int verify,
+                           int32_t* log, int log_capacity, int32_t* n_executed,
+                           int32_t* deadlocked);
+
 #ifdef __cplusplus
 }
 #endif

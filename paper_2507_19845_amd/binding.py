@@ -37,6 +37,8 @@ EXPORTS = (
     "gpt_stage_trace_create", "gpt_stage_trace_destroy", "gpt_stage_trace_reset",
     "gpt_stage_trace_collect", "gpt_stage_trace_op_name",
     "gpt_dpp_plan", "gpt_dpp_stash_slot_bytes", "gpt_dpp_act_slot_bytes", "gpt_dpp_run",
+    "gpt_fbd_coord_create", "gpt_fbd_coord_destroy", "gpt_fbd_coord_expected", "gpt_fbd_coord_register",
+    "gpt_fbd_coord_align", "gpt_fbd_coord_ready", "gpt_fbd_coord_execute", "gpt_fbd_coord_simulate",
 )
 
 
@@ -102,6 +104,7 @@ def lib() -> C.CDLL:
     L = C.CDLL(LIB_PATH)
     vp, i32, sz, f32 = C.c_void_p, C.c_int, C.c_size_t, C.c_float
     cfgp, parp = C.POINTER(gpt_stage_cfg), C.POINTER(gpt_stage_params)
+    i32p = C.POINTER(C.c_int32)
     sig = {
         "gpt_stage_validate": (i32, [cfgp]),
         "gpt_stage_param_count": (sz, [cfgp]),
@@ -138,6 +141,14 @@ def lib() -> C.CDLL:
         "gpt_dpp_stash_slot_bytes": (sz, [parp, i32]),
         "gpt_dpp_act_slot_bytes": (sz, [cfgp]),
         "gpt_dpp_run": (i32, [C.POINTER(gpt_dpp_job), vp, C.POINTER(gpt_dpp_report)]),
+        "gpt_fbd_coord_create": (i32, [i32, i32, i32p, i32p, i32, i32p, C.POINTER(vp)]),
+        "gpt_fbd_coord_destroy": (i32, [vp]),
+        "gpt_fbd_coord_expected": (i32, [vp, i32, C.c_char_p]),
+        "gpt_fbd_coord_register": (i32, [vp, i32, i32]),
+        "gpt_fbd_coord_align": (i32, [vp]),
+        "gpt_fbd_coord_ready": (i32, [vp, i32, i32p, i32]),
+        "gpt_fbd_coord_execute": (i32, [vp, i32p, i32]),
+        "gpt_fbd_coord_simulate": (i32, [vp, i32p, i32p, i32, i32p, i32, i32p, i32p]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -418,6 +429,73 @@ def gpt_dpp_run(policy: int, chunks, xs, dys, ys, dxs, dparams, stash_pool, act_
     rep = gpt_dpp_report()
     _check(lib().gpt_dpp_run(C.byref(job), _stream(stream), C.byref(rep)))
     return rep
+
+
+# ---- communication coordinator, simulated on the host ---------------------------------
+def _i32(values):
+    return (C.c_int32 * max(len(values), 1))(*values)
+
+
+def _ragged(lists):
+    start, flat = [0], []
+    for l in lists:
+        flat += list(l)
+        start.append(len(flat))
+    return _i32(start), _i32(flat)
+
+
+def gpt_fbd_coord_create(n_ranks: int, groups, control_of_rank) -> int:
+    """groups: list of member lists; control_of_rank: control thread of each virtual rank.
+    Returns the coordinator handle."""
+    gs, gm = _ragged(groups)
+    h = C.c_void_p()
+    _check(lib().gpt_fbd_coord_create(n_ranks, len(groups), gs, gm, max(control_of_rank) + 1 if control_of_rank else 0,
+                                      _i32(list(control_of_rank)), C.byref(h)))
+    return h.value
+
+
+def gpt_fbd_coord_destroy(coord) -> None:
+    _check(lib().gpt_fbd_coord_destroy(coord))
+
+
+def gpt_fbd_coord_expected(coord, group: int, n_ranks: int) -> str:
+    buf = C.create_string_buffer(n_ranks + 1)
+    _check(lib().gpt_fbd_coord_expected(coord, group, buf))
+    return buf.value.decode()
+
+
+def gpt_fbd_coord_register(coord, rank: int, group: int) -> None:
+    _check(lib().gpt_fbd_coord_register(coord, rank, group))
+
+
+def gpt_fbd_coord_align(coord) -> None:
+    _check(lib().gpt_fbd_coord_align(coord))
+
+
+def gpt_fbd_coord_ready(coord, control: int, n_groups: int):
+    out = (C.c_int32 * max(n_groups, 1))()
+    n = lib().gpt_fbd_coord_ready(coord, control, out, n_groups)
+    if n < 0:
+        _check(n)
+    return list(out[:n])
+
+
+def gpt_fbd_coord_execute(coord, n_groups: int):
+    out = (C.c_int32 * max(n_groups, 1))()
+    n = lib().gpt_fbd_coord_execute(coord, out, n_groups)
+    if n < 0:
+        _check(n)
+    return list(out[:n])
+
+
+def gpt_fbd_coord_simulate(coord, programs, verify: bool):
+    """-> (log, deadlocked)"""
+    ps, pf = _ragged(programs)
+    cap = max(sum(len(p) for p in programs), 1)
+    log = (C.c_int32 * cap)()
+    n, dead = C.c_int32(0), C.c_int32(0)
+    _check(lib().gpt_fbd_coord_simulate(coord, ps, pf, 1 if verify else 0, log, cap, C.byref(n), C.byref(dead)))
+    return list(log[:n.value]), bool(dead.value)
 
 
 # ---- device-memory plumbing (torch tensors as buffers; no arithmetic) --------------

@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared():
     text = open(os.path.join(ROOT, "include", "gpt_stage.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(gpt_(?:stage|dpp)_\w+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(gpt_(?:stage|dpp|fbd)_\w+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
