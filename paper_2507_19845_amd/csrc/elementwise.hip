@@ -101,8 +101,15 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(
     const T* __restrict__ dout, const TX* __restrict__ x, const float* __restrict__ mean,
     const float* __restrict__ rstd, const T* __restrict__ gamma, const T* __restrict__ dres,
     T* __restrict__ dx, float* __restrict__ partial, int T_rows, int H) {
-  __shared__ float red[2][kLnThreads / kWave];
+  // One barrier per row: the two row sums are reduced together and the LDS slots alternate
+  // between rows, so a row's writes cannot overtake the previous row's reads.  The loads of
+  // the next row (when the row fits few registers) and of the residual gradient are issued
+  // before the barrier, so that memory latency overlaps the reduction.
+  constexpr int NWV = kLnThreads / kWave;
+  constexpr bool PREFETCH = NCH <= 2;
+  __shared__ float red[2][2][NWV];
   const int nvec = H / 8;
+  const int wv = threadIdx.x / kWave;
   float dg[NCH][8], db[NCH][8], gam[NCH][8];
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
@@ -111,17 +118,31 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(
 #pragma unroll
     for (int e = 0; e < 8; ++e) dg[c][e] = db[c][e] = 0.f;
   }
-  for (int row = blockIdx.x; row < T_rows; row += gridDim.x) {
+  float dv[NCH][8], xh[NCH][8], dvn[PREFETCH ? NCH : 1][8], xn[PREFETCH ? NCH : 1][8];
+  auto load_row = [&](int row, float (&d)[NCH][8], float (&xx)[NCH][8]) {
+    const size_t base = (size_t)row * H;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int i = threadIdx.x + c * kLnThreads;
+      if (i < nvec) {
+        load8(dout + base + (size_t)i * 8, d[c]);
+        load8(x + base + (size_t)i * 8, xx[c]);
+      }
+    }
+  };
+  if constexpr (PREFETCH) {
+    if ((int)blockIdx.x < T_rows) load_row(blockIdx.x, dv, xh);
+  }
+  int buf = 0;
+  for (int row = blockIdx.x; row < T_rows; row += gridDim.x, buf ^= 1) {
+    if constexpr (!PREFETCH) load_row(row, dv, xh);
     const float mu = mean[row], r = rstd[row];
     const size_t base = (size_t)row * H;
-    float dv[NCH][8], xh[NCH][8];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
       const int i = threadIdx.x + c * kLnThreads;
       if (i < nvec) {
-        load8(dout + base + (size_t)i * 8, dv[c]);
-        load8(x + base + (size_t)i * 8, xh[c]);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const float d = dv[c][e];
@@ -134,22 +155,55 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(
         }
       }
     }
-    const float m1 = block_sum<kLnThreads / kWave>(s1, red[0]) / (float)H;
-    const float m2 = block_sum<kLnThreads / kWave>(s2, red[1]) / (float)H;
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+      red[buf][0][wv] = s1;
+      red[buf][1][wv] = s2;
+    }
+    float rs[NCH][8];
+    if (dres) {
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) {
+        const int i = threadIdx.x + c * kLnThreads;
+        if (i < nvec) load8(dres + base + (size_t)i * 8, rs[c]);
+      }
+    }
+    if constexpr (PREFETCH) {
+      const int nxt = row + gridDim.x;
+      if (nxt < T_rows) load_row(nxt, dvn, xn);
+    }
+    __syncthreads();
+    float m1 = 0.f, m2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NWV; ++i) {
+      m1 += red[buf][0][i];
+      m2 += red[buf][1][i];
+    }
+    m1 /= (float)H;
+    m2 /= (float)H;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
       const int i = threadIdx.x + c * kLnThreads;
       if (i < nvec) {
-        float o[8], rs[8];
-        if (dres) load8(dres + base + (size_t)i * 8, rs);
+        float o[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           float v = r * (dv[c][e] * gam[c][e] - m1 - xh[c][e] * m2);
-          if (dres) v += rs[e];
+          if (dres) v += rs[c][e];
           o[e] = v;
         }
         store8(dx + base + (size_t)i * 8, o);
       }
+    }
+    if constexpr (PREFETCH) {
+#pragma unroll
+      for (int c = 0; c < NCH; ++c)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          dv[c][e] = dvn[c][e];
+          xh[c][e] = xn[c][e];
+        }
     }
   }
   float* pg = partial + (size_t)blockIdx.x * 2 * H;
@@ -260,7 +314,7 @@ hipError_t ln_fwd(int dtype, bool x_f32, int T_rows, int H, float eps, const voi
                               (bf16*)out, mean, rstd, st);
 }
 
-int ln_bwd_blocks(int T_rows) { return T_rows < 256 ? T_rows : 256; }
+int ln_bwd_blocks(int T_rows) { return T_rows < 512 ? T_rows : 512; }
 
 template <typename TX, typename T>
 static hipError_t ln_bwd_t(int T_rows, int H, const T* dout, const TX* x, const float* mean,

@@ -25,12 +25,20 @@
 //    ids are first regrouped per XCD and then walked in bands of 4 tile rows to
 //    keep each XCD's L2 working set to a compact patch of the output.
 #include <type_traits>
+#include <utility>
 
+#include "agpr_ops.hpp"
 #include "kernels.hpp"
 
 namespace gpts {
 namespace {
 
+#ifndef GPTS_KC_STAGES
+// LDS stages of the 256x256 kernel for raw (not prepared) operands when A is K-contiguous:
+// 5 = ring with paired fetches (measured +3 % on the raw forward product), 4 = plain ring.
+// With a prepared B image the plain ring is as fast (the image is contiguous anyway).
+#define GPTS_KC_STAGES 5
+#endif
 #ifndef GPTS_BIG_WAVES
 #define GPTS_BIG_WAVES 4   // waves per workgroup of the 256x256 kernel
 #endif
@@ -191,12 +199,144 @@ template <int VM> __device__ __forceinline__ void wait_dma_and_barrier() {
   asm volatile("s_waitcnt vmcnt(%0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::"n"(VM) : "memory");
 }
 
+// ---- epilogue --------------------------------------------------------------------
+// Shared by the kernels below.  acc[i][j]: the wave's 32x32 blocks (block row i, block column j)
+// in the accumulator layout of the swapped MFMA (lane owns row lane&31 and four-column groups).
+// lds: LDS_BYTES of workgroup LDS that no wave reads any more and no DMA still writes.
+// write_pass(pass_constant, stg): stores rows [pass*RP, pass*RP + RP) of the wave's block
+// into the staging area, element (row, col) as fp32 at
+//   stg + row*WN + ((col/4) ^ (row & (WN/4 - 1)))*4 + col%4     (see stage_slot()).
+template <int WN> __device__ __forceinline__ int stage_slot(int row, int chunk) {
+  return row * WN + ((chunk ^ (row & (WN / 4 - 1))) * 4);
+}
+template <int... I, class F> __device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a constant expression
+template <int N, class F> __device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+template <int BM, int BN, int EPI, int NW, int LDS_BYTES, class StageWriter>
+__device__ __forceinline__ void gemm_epilogue(StageWriter&& write_pass, const MfmaArgs& a, char* lds,
+                                              int m0, int n0, int wm, int wn, int wave, int lane) {
+  constexpr int WGN = NW / 2, WM = BM / 2, WN = BN / WGN;
+  // The accumulators hold a lane-per-row layout (lane owns row lane&31 and four-column
+  // groups), which would store 16-byte pieces scattered over 32 rows.  Each wave instead
+  // transposes its block through the pipeline's LDS (free once every wave has left the
+  // main loop) in passes of RP rows, and reads it back row-major: CW lanes cover one row
+  // of the wave's WN columns, so every global load and store of the epilogue touches
+  // whole cache lines.  The 16-byte chunks of a staged row are XOR-swizzled with the row
+  // so that the column-wise writes spread over the banks.
+  __builtin_amdgcn_s_barrier();
+  constexpr int CW = WN / 4;                                 // 16-byte fp32 chunks per staged row
+  constexpr int RP_FIT = LDS_BYTES / NW / (WN * 4);         // rows of the wave's block that fit its LDS share
+  constexpr int RP = RP_FIT >= WM ? WM : RP_FIT / 32 * 32;   // rows per pass
+  static_assert(RP >= 32 && WM % RP == 0 && 64 % CW == 0, "epilogue staging does not fit");
+  constexpr int RPI = 64 / CW;                               // rows per read instruction
+  float* stg = reinterpret_cast<float*>(lds + wave * (RP * WN * 4));
+  const int rd_chunk = lane % CW, rd_row = lane / CW;
+  const int n = n0 + wn * WN + rd_chunk * 4;
+  const bool n_ok = n < a.N;
+  constexpr bool RES32 = EPI == EPI_BIAS_RES32_OUT32 || EPI == EPI_BIAS_RES32_OUT16;
+  constexpr bool GELU = EPI == EPI_GELU_TANH || EPI == EPI_GELU_ERF;
+  constexpr bool DGELU = EPI == EPI_DGELU_TANH || EPI == EPI_DGELU_ERF;
+  float bias_v[4] = {0.f, 0.f, 0.f, 0.f};
+  if constexpr (EPI == EPI_BIAS_RES || RES32 || GELU) {
+    if (a.bias && n_ok) {
+      const bf16x4 b = *reinterpret_cast<const bf16x4*>(a.bias + n);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) bias_v[e] = (float)b[e];
+    }
+  }
+  static_for<WM / RP>([&](auto pass_c) {
+    constexpr int pass = decltype(pass_c)::value;
+    write_pass(pass_c, std::integral_constant<int, RP>{}, stg);
+    // LDS operations of one wave complete in order: no wait is needed between the
+    // writes above and the reads below, only that the compiler keeps their order
+    asm volatile("" ::: "memory");
+    // UB rows at a time: all loads of a batch are issued before the first is used
+    constexpr int UB = 8;
+    static_assert((RP / RPI) % UB == 0, "row batches");
+    for (int it0 = 0; it0 < RP / RPI; it0 += UB) {
+      f32x4 sv[UB], in32[UB];
+      bf16x4 in16[UB];
+      bool ok[UB];
+      size_t o[UB];
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        const int row = (it0 + u) * RPI + rd_row;
+        const int m = m0 + wm * WM + pass * RP + row;
+        sv[u] = *reinterpret_cast<const f32x4*>(stg + row * WN + ((rd_chunk ^ (row & (CW - 1))) * 4));
+        ok[u] = m < a.M && n_ok;
+        o[u] = ok[u] ? (size_t)m * a.N + n : 0;  // element 0 is always a valid address
+        if constexpr (EPI == EPI_ACCUM) in32[u] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(a.C) + o[u]);
+        if constexpr (RES32) in32[u] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(a.residual) + o[u]);
+        if constexpr (DGELU) in16[u] = *reinterpret_cast<const bf16x4*>(a.dgelu_u + o[u]);
+        if constexpr (EPI == EPI_BIAS_RES) {
+          if (a.residual) in16[u] = *reinterpret_cast<const bf16x4*>(static_cast<const bf16*>(a.residual) + o[u]);
+          else
+#pragma unroll
+            for (int e = 0; e < 4; ++e) in16[u][e] = (bf16)0.f;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        if (!ok[u]) continue;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = sv[u][e] + bias_v[e];
+        if constexpr (EPI == EPI_ACCUM) {
+          f32x4 c;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) c[e] = in32[u][e] + v[e];
+          *reinterpret_cast<f32x4*>(static_cast<float*>(a.C) + o[u]) = c;
+        } else if constexpr (GELU) {
+          bf16x4 uq, gq;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            uq[e] = (bf16)v[e];
+            // g is the GeLU of u AS STORED, so that a backward pass that recomputes g from
+            // the stashed u gets the same bits
+            gq[e] = (bf16)gelu_f<EPI == EPI_GELU_TANH ? 0 : 1>((float)uq[e]);
+          }
+          *reinterpret_cast<bf16x4*>(static_cast<bf16*>(a.C) + o[u]) = uq;
+          *reinterpret_cast<bf16x4*>(a.gelu_out + o[u]) = gq;
+        } else {
+          if constexpr (DGELU) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f<EPI == EPI_DGELU_TANH ? 0 : 1>((float)in16[u][e]);
+          }
+          if constexpr (EPI == EPI_BIAS_RES) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += (float)in16[u][e];
+          }
+          if constexpr (RES32) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += in32[u][e];
+          }
+          if constexpr (EPI == EPI_BIAS_RES32_OUT32) {
+            f32x4 out;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) out[e] = v[e];
+            *reinterpret_cast<f32x4*>(static_cast<float*>(a.C) + o[u]) = out;
+          } else {
+            bf16x4 out;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) out[e] = (bf16)v[e];
+            *reinterpret_cast<bf16x4*>(static_cast<bf16*>(a.C) + o[u]) = out;
+          }
+        }
+      }
+    }
+  });
+}
+
 template <int BM, int BN, int BK, int NS, bool A_KMAJOR, bool B_KMAJOR, int EPI, bool B_IMG = false, int NW = 4>
 __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const MfmaArgs a) {
   // NW waves in a 2 x (NW/2) grid
   constexpr int WGN = NW / 2;
   constexpr int WM = BM / 2, WN = BN / WGN, TM = WM / 32, TN = WN / 32, KS = BK / 16;
-  static_assert((NS & (NS - 1)) == 0 && KS % 2 == 0, "stages: power of two; even MFMA steps per slice");
+  static_assert(((NS & (NS - 1)) == 0 || NS == 5) && KS % 2 == 0, "stages: power of two or 5; even MFMA steps per slice");
   // k order inside fragments: natural unless both operands are K-major
   constexpr bool NAT = !(A_KMAJOR && B_KMAJOR);
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
@@ -275,7 +415,79 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const MfmaArgs a) {
   };
 
   bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-  if constexpr (NS >= 4) {
+  if constexpr (NS == 5) {
+    // Ring of five stages with PAIRED fetches.  A K-contiguous operand row contributes
+    // only 64 bytes to a slice of 32, half a cache line; the other half belongs to the next
+    // slice.  Fetching the two slices at different times asks the L2 for every line twice.
+    // Here the DMA instructions of slices 2q and 2q+1 are issued back to back (same lane
+    // addresses, +64 bytes), so the second request finds the line in, or on its way to, the
+    // L1; each line is requested from the L2 once.  Slice t lives in stage t % 5; the pair
+    // (t+3, t+4) is issued during every ODD iteration t, into the stages that slices t-2
+    // and t-1 have left; even iterations issue nothing.  A slice is needed two or three
+    // iterations after its issue.
+    static_assert(KS == 2, "paired fetch is written for slices of two MFMA steps");
+    constexpr int RING = 5 * STAGE;
+    auto issue_pair_part = [&](int even_slice, uint32_t st_even, uint32_t st_odd, int j, bool second) {
+      // instruction j of the A operand (j < NIA) or of the B operand, for one slice of the pair
+      const int sl = min(even_slice + (second ? 1 : 0), nk - 1);
+      const uint32_t base = lds_base + (second ? st_odd : st_even);
+      if (j < NIA) opA.issue_one(a.A, lda, sl, base, wave, j);
+      else opB.issue_one(a.B, ldb, sl, base + A_BYTES, wave, j - NIA);
+    };
+    // one MFMA step; H = 0: no DMA, H = 1 / 2: first / second half of the pair's instructions
+    auto step5 = [&](const bf16x8(&fac)[TM], const bf16x8(&fbc)[TN], bf16x8(&fan)[TM], bf16x8(&fbn)[TN],
+                     const char* stage_nxt, int ks_nxt, auto half, int even_slice, uint32_t st_even, uint32_t st_odd) {
+      constexpr int H = decltype(half)::value;
+      load_frags(fan, fbn, stage_nxt, ks_nxt);
+      if constexpr (H == 0) {
+        mma(fac, fbc);
+        sched_pairs<N_PAIR, N_DS, N_MMA, 0>();
+      } else {
+        constexpr int ND = N_DMA;              // instructions of this step: N_DMA/2 per slice, two slices
+        constexpr int N1 = N_DS < N_MMA - ND ? N_DS : N_MMA - ND;
+        constexpr int Q = (N_MMA - N1) / ND;
+        static_assert(Q >= 1, "not enough MFMAs to spread the DMA instructions");
+        mma_range(fac, fbc, 0, N1);
+        sched_pairs<N1, N_DS, N1, 0>();
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int d = 0; d < ND; ++d) {
+          mma_range(fac, fbc, N1 + d * Q, N1 + (d + 1) * Q);
+          __builtin_amdgcn_sched_barrier(0);
+          issue_pair_part(even_slice, st_even, st_odd, (H - 1) * (N_DMA / 2) + d / 2, (d & 1) != 0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        mma_range(fac, fbc, N1 + ND * Q, N_MMA);
+      }
+    };
+    auto next_stage = [&](uint32_t st) { return st + STAGE == RING ? 0u : st + STAGE; };
+    std::integral_constant<int, 0> no_dma;
+    std::integral_constant<int, 1> first_half;
+    std::integral_constant<int, 2> second_half;
+    // prologue: pairs (0,1) and (2,3) into stages 0..3
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int j = 0; j < N_DMA; ++j) {
+        issue_pair_part(2 * q, (2 * q) * STAGE, (2 * q + 1) * STAGE, j, false);
+        issue_pair_part(2 * q, (2 * q) * STAGE, (2 * q + 1) * STAGE, j, true);
+      }
+    wait_dma_and_barrier<2 * N_DMA>();   // pair 0 has landed
+    load_frags(fa0, fb0, lds, 0);
+    uint32_t st = 0;                     // stage offset of slice kt
+    for (int kt = 0; kt < nk; kt += 2) {
+      // even slice kt: nothing to fetch
+      const uint32_t st1 = next_stage(st), st2 = next_stage(st1), st3 = next_stage(st2), st4 = next_stage(st3);
+      step5(fa0, fb0, fa1, fb1, lds + st, 1, no_dma, 0, 0, 0);
+      wait_dma_and_barrier<2 * N_DMA>();            // slice kt+1: every pair but the youngest has landed
+      step5(fa1, fb1, fa0, fb0, lds + st1, 0, no_dma, 0, 0, 0);
+      // odd slice kt+1: fetch the pair (kt+4, kt+5) into the stages of slices kt-1 and kt
+      step5(fa0, fb0, fa1, fb1, lds + st1, 1, first_half, kt + 4, st4, st);
+      wait_dma_and_barrier<N_DMA>();                // slice kt+2: only this iteration's first half may be in flight
+      step5(fa1, fb1, fa0, fb0, lds + st2, 0, second_half, kt + 4, st4, st);
+      st = st2;
+    }
+  } else if constexpr (NS >= 4) {
     // Deep pipeline: slice t lives in stage t % NS.  At the top of iteration kt slice
     // kt is complete, slices kt+1 .. kt+NS-2 are in flight and the stage of slice
     // kt-1 is free: slice kt+NS-1 is fetched into it during this iteration, its DMA
@@ -358,128 +570,146 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const MfmaArgs a) {
   // no DMA may still be writing LDS when the workgroup retires
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-  // ---- epilogue --------------------------------------------------------------------
-  // The accumulators hold a lane-per-row layout (lane owns row lane&31 and four-column
-  // groups), which would store 16-byte pieces scattered over 32 rows.  Each wave instead
-  // transposes its block through the pipeline's LDS (free once every wave has left the
-  // main loop) in passes of RP rows, and reads it back row-major: CW lanes cover one row
-  // of the wave's WN columns, so every global load and store of the epilogue touches
-  // whole cache lines.  The 16-byte chunks of a staged row are XOR-swizzled with the row
-  // so that the column-wise writes spread over the banks.
-  __builtin_amdgcn_s_barrier();
-  constexpr int CW = WN / 4;                                 // 16-byte fp32 chunks per staged row
-  constexpr int RP_FIT = NS * STAGE / NW / (WN * 4);         // rows of the wave's block that fit its LDS share
-  constexpr int RP = RP_FIT >= WM ? WM : RP_FIT / 32 * 32;   // rows per pass
-  static_assert(RP >= 32 && WM % RP == 0 && 64 % CW == 0, "epilogue staging does not fit");
-  constexpr int TI = RP / 32, RPI = 64 / CW;                 // 32-row blocks per pass; rows per read instruction
-  float* stg = reinterpret_cast<float*>(lds + wave * (RP * WN * 4));
-  const int wr_row = lane & 31, wr_half = lane >> 5;
-  const int rd_chunk = lane % CW, rd_row = lane / CW;
-  const int n = n0 + wn * WN + rd_chunk * 4;
-  const bool n_ok = n < a.N;
-  constexpr bool RES32 = EPI == EPI_BIAS_RES32_OUT32 || EPI == EPI_BIAS_RES32_OUT16;
-  constexpr bool GELU = EPI == EPI_GELU_TANH || EPI == EPI_GELU_ERF;
-  constexpr bool DGELU = EPI == EPI_DGELU_TANH || EPI == EPI_DGELU_ERF;
-  float bias_v[4] = {0.f, 0.f, 0.f, 0.f};
-  if constexpr (EPI == EPI_BIAS_RES || RES32 || GELU) {
-    if (a.bias && n_ok) {
-      const bf16x4 b = *reinterpret_cast<const bf16x4*>(a.bias + n);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) bias_v[e] = (float)b[e];
-    }
-  }
-#pragma unroll
-  for (int pass = 0; pass < WM / RP; ++pass) {
+  // lane owns row lane&31 of each 32x32 block and, per group g, columns 8g + 4*(lane>>5) .. +3
+  auto write_pass = [&](auto pass_c, auto rp_c, float* stg) {
+    constexpr int pass = decltype(pass_c)::value, TI = decltype(rp_c)::value / 32;
 #pragma unroll
     for (int ii = 0; ii < TI; ++ii)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int row = ii * 32 + wr_row, chunk = j * 8 + g * 2 + wr_half;
           f32x4 v;
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = acc[pass * TI + ii][j][g * 4 + e];
-          *reinterpret_cast<f32x4*>(stg + row * WN + ((chunk ^ (row & (CW - 1))) * 4)) = v;
+          *reinterpret_cast<f32x4*>(stg + stage_slot<WN>(ii * 32 + (lane & 31), j * 8 + g * 2 + (lane >> 5))) = v;
         }
-    // LDS operations of one wave complete in order: no wait is needed between the
-    // writes above and the reads below, only that the compiler keeps their order
-    asm volatile("" ::: "memory");
-    // UB rows at a time: all loads of a batch are issued before the first is used
-    constexpr int UB = 8;
-    static_assert((RP / RPI) % UB == 0, "row batches");
-    for (int it0 = 0; it0 < RP / RPI; it0 += UB) {
-      f32x4 sv[UB], in32[UB];
-      bf16x4 in16[UB];
-      bool ok[UB];
-      size_t o[UB];
+  };
+  gemm_epilogue<BM, BN, EPI, NW, NS * STAGE>(write_pass, a, lds, m0, n0, wm, wn, wave, lane);
+}
+
+// ---- 16x16x32 products with hand-placed accumulators -------------------------------------
+// The chip sustains a clearly higher clock on a stream of v_mfma_f32_16x16x32_bf16 than on the
+// same flops issued as 32x32x16 (2.05 against 1.80 GHz on matrix instructions alone), so the
+// K-contiguous products (forward; dgrad through the weight image) use the smaller shape.  The
+// compiler, however, shuffles sixty-four 4-register accumulators between register files in
+// every iteration, so here the accumulators are placed by hand: block (ib, jb) of the wave's
+// 8 x 8 grid of 16x16 blocks lives in AGPRs a[4*(8*ib+jb) .. +3] for the whole kernel, the
+// matrix instructions are inline assembly naming those registers, and the epilogue reads them
+// back with v_accvgpr_read.  The compiler never allocates AGPRs in this kernel on its own (it
+// has no matrix builtin and needs well under 256 ordinary registers); the clearing block below
+// names all 256 as clobbered, which is what makes the kernel's register allocation include them.
+// Operands are swapped as in the 32x32 kernel: D'[n][m] = B-fragment x A-fragment, so lane l
+// holds, for output row m = l%16 of the block, the four columns n = 4*(l/16) .. +3.
+// One workgroup: 256 x 256 tile, 4 waves (2 x 2, 128 x 128 each), K slices of 32 through the
+// same four-stage DMA ring and LDS layout as gemm_mfma_kernel; a slice is ONE matrix step
+// (k = 32): 8 A and 8 B fragments of 16 rows, 64 matrix instructions.  Fragments are double
+// buffered in registers: while slice t is multiplied, the 16 fragments of slice t+1 are read
+// from LDS and the 8 DMA instructions of slice t+3 are issued, one LDS read after every 4 and
+// one DMA after every 8 matrix instructions.  One barrier per slice, at its start.
+template <int EPI, bool B_IMG>
+__global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
+  constexpr int BM = 256, BN = 256, BK = 32, NS = 4, NW = 4, WGN = 2;
+  constexpr int WM = BM / 2, WN = BN / WGN, NB = WM / 16;   // 8 x 8 blocks of 16 x 16 per wave
+  constexpr int A_BYTES = BM * BK * 2, STAGE = A_BYTES + BN * BK * 2, RB = BK * 2;
+  __shared__ __attribute__((aligned(1024))) char lds[NS * STAGE];
+  const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) char*)lds;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+  const int nb = tiles_m * tiles_n;
+  int id = blockIdx.x;
+  if ((nb & 7) == 0) id = (id & 7) * (nb >> 3) + (id >> 3);  // contiguous range per XCD
+  constexpr int GROUP = 4;
+  const int per_group = GROUP * tiles_n;
+  const int grp = id / per_group, first_m = grp * GROUP;
+  const int gsz = min(tiles_m - first_m, GROUP);
+  const int tm_i = first_m + (id % per_group) % gsz, tn_i = (id % per_group) / gsz;
+  const int m0 = tm_i * BM, n0 = tn_i * BN;
+  const int nk = a.K / BK;                      // a multiple of 4 (checked by the dispatcher)
+
+  Operand<BM, WM, BK, false, true, false, NW> opA;
+  Operand<BN, WN, BK, false, true, B_IMG, NW> opB;
+  opA.init(m0, a.M, (size_t)a.K, wave, lane, wm * WM);
+  opB.init(n0, a.N, (size_t)a.K, wave, lane, wn * WN);
+  constexpr int NIA = BM * BK * 2 / 1024 / NW, NIB = BN * BK * 2 / 1024 / NW, N_DMA = NIA + NIB;
+  static_assert(N_DMA == 8 && NB == 8, "the slice schedule below is written for 8 DMA instructions and 8 x 8 blocks");
+
+  // fragment of 16 rows x 32 k: lane reads chunk lane>>4 of row lane&15 (the swizzle has period 16 rows)
+  const int frag_off = (lane & 15) * RB + (((lane >> 4) ^ swz_kc<BK / 8>(lane & 15)) << 4);
+  const char* fragA = lds + wm * WM * RB + frag_off;
+  const char* fragB = lds + A_BYTES + wn * WN * RB + frag_off;
+  bf16x8 fa[2][NB], fb[2][NB];
+
+  agpr_clear_all();
+
+  auto dma = [&](int slice, int stage, int i) {   // DMA instruction i of a slice: A first, then B
+    const int sl = min(slice, nk - 1);
+    if (i < NIA) opA.issue_one(a.A, (size_t)a.K, sl, lds_base + stage * STAGE, wave, i);
+    else opB.issue_one(a.B, (size_t)a.K, sl, lds_base + stage * STAGE + A_BYTES, wave, i - NIA);
+  };
 #pragma unroll
-      for (int u = 0; u < UB; ++u) {
-        const int row = (it0 + u) * RPI + rd_row;
-        const int m = m0 + wm * WM + pass * RP + row;
-        sv[u] = *reinterpret_cast<const f32x4*>(stg + row * WN + ((rd_chunk ^ (row & (CW - 1))) * 4));
-        ok[u] = m < a.M && n_ok;
-        o[u] = ok[u] ? (size_t)m * a.N + n : 0;  // element 0 is always a valid address
-        if constexpr (EPI == EPI_ACCUM) in32[u] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(a.C) + o[u]);
-        if constexpr (RES32) in32[u] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(a.residual) + o[u]);
-        if constexpr (DGELU) in16[u] = *reinterpret_cast<const bf16x4*>(a.dgelu_u + o[u]);
-        if constexpr (EPI == EPI_BIAS_RES) {
-          if (a.residual) in16[u] = *reinterpret_cast<const bf16x4*>(static_cast<const bf16*>(a.residual) + o[u]);
-          else
+  for (int s0 = 0; s0 < NS - 1; ++s0)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) in16[u][e] = (bf16)0.f;
-        }
-      }
+    for (int i = 0; i < N_DMA; ++i) dma(s0, s0, i);
+  wait_dma_and_barrier<(NS - 2) * N_DMA>();   // slice 0 has landed
 #pragma unroll
-      for (int u = 0; u < UB; ++u) {
-        if (!ok[u]) continue;
-        float v[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = sv[u][e] + bias_v[e];
-        if constexpr (EPI == EPI_ACCUM) {
-          f32x4 c;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) c[e] = in32[u][e] + v[e];
-          *reinterpret_cast<f32x4*>(static_cast<float*>(a.C) + o[u]) = c;
-        } else if constexpr (GELU) {
-          bf16x4 uq, gq;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            uq[e] = (bf16)v[e];
-            // g is the GeLU of u AS STORED, so that a backward pass that recomputes g from
-            // the stashed u gets the same bits
-            gq[e] = (bf16)gelu_f<EPI == EPI_GELU_TANH ? 0 : 1>((float)uq[e]);
-          }
-          *reinterpret_cast<bf16x4*>(static_cast<bf16*>(a.C) + o[u]) = uq;
-          *reinterpret_cast<bf16x4*>(a.gelu_out + o[u]) = gq;
-        } else {
-          if constexpr (DGELU) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f<EPI == EPI_DGELU_TANH ? 0 : 1>((float)in16[u][e]);
-          }
-          if constexpr (EPI == EPI_BIAS_RES) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += (float)in16[u][e];
-          }
-          if constexpr (RES32) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += in32[u][e];
-          }
-          if constexpr (EPI == EPI_BIAS_RES32_OUT32) {
-            f32x4 out;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) out[e] = v[e];
-            *reinterpret_cast<f32x4*>(static_cast<float*>(a.C) + o[u]) = out;
-          } else {
-            bf16x4 out;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) out[e] = (bf16)v[e];
-            *reinterpret_cast<bf16x4*>(static_cast<bf16*>(a.C) + o[u]) = out;
-          }
-        }
-      }
-    }
+  for (int u = 0; u < NB; ++u) {
+    fa[0][u] = *reinterpret_cast<const bf16x8*>(fragA + u * 16 * RB);
+    fb[0][u] = *reinterpret_cast<const bf16x8*>(fragB + u * 16 * RB);
   }
+
+  for (int kt = 0; kt < nk; kt += NS) {
+    static_for<NS>([&](auto r_c) {
+      constexpr int r = decltype(r_c)::value, cur = r & 1, nxt = cur ^ 1;
+      constexpr int st_next = (r + 1) % NS, st_fill = (r + NS - 1) % NS;
+      const int t = kt + r;
+      // slice t+1 has landed (only the copies of slice t+2 may still be in flight); every wave
+      // has finished reading slices <= t from LDS
+      wait_dma_and_barrier<N_DMA>();
+      static_for<16>([&](auto g_c) {
+        constexpr int g = decltype(g_c)::value;
+        // four matrix instructions: block row g/2, block columns 4*(g%2) .. +3
+        static_for<4>([&](auto q_c) {
+          constexpr int ib = g / 2, jb = 4 * (g % 2) + decltype(q_c)::value;
+          mfma16_at<4 * (NB * ib + jb)>(fb[cur][jb], fa[cur][ib]);
+        });
+        __builtin_amdgcn_sched_barrier(0);
+        // one fragment of the next slice
+        if constexpr (g < NB) fa[nxt][g] = *reinterpret_cast<const bf16x8*>(fragA + st_next * STAGE + g * 16 * RB);
+        else fb[nxt][g - NB] = *reinterpret_cast<const bf16x8*>(fragB + st_next * STAGE + (g - NB) * 16 * RB);
+        // and after every second group one DMA instruction of slice t+3
+        if constexpr (g % 2 == 1) dma(t + NS - 1, st_fill, g / 2);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    });
+  }
+  // no DMA may still be writing LDS when the staging starts; the matrix pipeline must have
+  // drained before the accumulators are read (the compiler does not know they were written)
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+
+  auto write_pass = [&](auto pass_c, auto rp_c, float* stg) {
+    constexpr int pass = decltype(pass_c)::value, BI = decltype(rp_c)::value / 16;   // block rows per pass
+    static_for<BI * NB>([&](auto b_c) {
+      constexpr int ii = decltype(b_c)::value / NB, jb = decltype(b_c)::value % NB;
+      constexpr int R = 4 * (NB * (pass * BI + ii) + jb);
+      f32x4 v;
+      v[0] = agpr_read<R>();
+      v[1] = agpr_read<R + 1>();
+      v[2] = agpr_read<R + 2>();
+      v[3] = agpr_read<R + 3>();
+      *reinterpret_cast<f32x4*>(stg + stage_slot<WN>(ii * 16 + (lane & 15), jb * 4 + (lane >> 4))) = v;
+    });
+  };
+  gemm_epilogue<BM, BN, EPI, NW, NS * STAGE>(write_pass, a, lds, m0, n0, wm, wn, wave, lane);
+}
+
+template <int EPI, bool B_IMG> hipError_t launch_mi16(const MfmaArgs& a, hipStream_t st) {
+  const int tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
+  hipLaunchKernelGGL((gemm_mi16_kernel<EPI, B_IMG>), dim3(tiles), dim3(256), 0, st, a);
+  return hipGetLastError();
 }
 
 template <int BM, int BN, int BK, int NS, bool AK, bool BKM, int EPI, bool B_IMG = false, int NW = 4>
@@ -496,7 +726,14 @@ hipError_t launch(const MfmaArgs& a, hipStream_t st) {
 bool use_big_tiles(int M, int N) { return (long)((M + 255) / 256) * ((N + 255) / 256) >= 200; }
 
 template <bool AK, bool BKM, int EPI> hipError_t pick_tile(const MfmaArgs& a, hipStream_t st) {
-  if (use_big_tiles(a.M, a.N)) return launch<256, 256, 32, 4, AK, BKM, EPI, false, GPTS_BIG_WAVES>(a, st);
+  if (use_big_tiles(a.M, a.N)) {
+    // both operands K-contiguous (forward on raw weights): the 16x16x32 kernel
+    if constexpr (!AK && !BKM) {
+      if (a.K % 128 == 0) return launch_mi16<EPI, false>(a, st);
+    }
+    // otherwise a K-contiguous A operand (dgrad) takes the five-stage ring with paired fetches
+    return launch<256, 256, 32, AK ? 4 : GPTS_KC_STAGES, AK, BKM, EPI, false, GPTS_BIG_WAVES>(a, st);
+  }
   return launch<128, 128, 64, 2, AK, BKM, EPI>(a, st);
 }
 
@@ -570,7 +807,8 @@ hipError_t gemm_mfma(int form, int M, int N, int K, const void* A, const void* B
     // B comes as the image of its [N rows, K] K-contiguous view: forward and dgrad are
     // then the same product with different epilogues.
     a.B = (const bf16*)ep.b_image;
-#define GPTS_IMG(EPI) launch<256, 256, 32, 4, false, false, EPI, true, GPTS_BIG_WAVES>(a, st)
+    const bool mi16 = K % 128 == 0;
+#define GPTS_IMG(EPI) (mi16 ? launch_mi16<EPI, true>(a, st) : launch<256, 256, 32, 4, false, false, EPI, true, GPTS_BIG_WAVES>(a, st))
     if (form == 0) {
       if (ep.gelu_out) return ep.gelu_kind == 0 ? GPTS_IMG(EPI_GELU_TANH) : GPTS_IMG(EPI_GELU_ERF);
       if (ep.residual && ep.residual_f32) return ep.out_f32 ? GPTS_IMG(EPI_BIAS_RES32_OUT32) : GPTS_IMG(EPI_BIAS_RES32_OUT16);
