@@ -50,7 +50,7 @@ typedef __attribute__((address_space(1))) const void* glb_ptr;
 // epilogue kinds
 // (RES32: the residual is fp32; OUT32: C is written as fp32 -- the residual stream of a bf16 stage)
 enum { EPI_BIAS_RES = 0, EPI_GELU_TANH, EPI_GELU_ERF, EPI_PLAIN, EPI_DGELU_TANH, EPI_DGELU_ERF, EPI_ACCUM,
-       EPI_BIAS_RES32_OUT32, EPI_BIAS_RES32_OUT16 };
+       EPI_BIAS_RES32_OUT32, EPI_BIAS_RES32_OUT16, EPI_BIAS /* bias only: no residual operand */ };
 
 struct MfmaArgs {
   const bf16* A;
@@ -241,7 +241,7 @@ __device__ __forceinline__ void gemm_epilogue(StageWriter&& write_pass, const Mf
   constexpr bool GELU = EPI == EPI_GELU_TANH || EPI == EPI_GELU_ERF;
   constexpr bool DGELU = EPI == EPI_DGELU_TANH || EPI == EPI_DGELU_ERF;
   float bias_v[4] = {0.f, 0.f, 0.f, 0.f};
-  if constexpr (EPI == EPI_BIAS_RES || RES32 || GELU) {
+  if constexpr (EPI == EPI_BIAS_RES || EPI == EPI_BIAS || RES32 || GELU) {
     if (a.bias && n_ok) {
       const bf16x4 b = *reinterpret_cast<const bf16x4*>(a.bias + n);
 #pragma unroll
@@ -272,12 +272,7 @@ __device__ __forceinline__ void gemm_epilogue(StageWriter&& write_pass, const Mf
         if constexpr (EPI == EPI_ACCUM) in32[u] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(a.C) + o[u]);
         if constexpr (RES32) in32[u] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(a.residual) + o[u]);
         if constexpr (DGELU) in16[u] = *reinterpret_cast<const bf16x4*>(a.dgelu_u + o[u]);
-        if constexpr (EPI == EPI_BIAS_RES) {
-          if (a.residual) in16[u] = *reinterpret_cast<const bf16x4*>(static_cast<const bf16*>(a.residual) + o[u]);
-          else
-#pragma unroll
-            for (int e = 0; e < 4; ++e) in16[u][e] = (bf16)0.f;
-        }
+        if constexpr (EPI == EPI_BIAS_RES) in16[u] = *reinterpret_cast<const bf16x4*>(static_cast<const bf16*>(a.residual) + o[u]);
       }
 #pragma unroll
       for (int u = 0; u < UB; ++u) {
@@ -607,6 +602,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const MfmaArgs a) {
 // buffered in registers: while slice t is multiplied, the 16 fragments of slice t+1 are read
 // from LDS and the 8 DMA instructions of slice t+3 are issued, one LDS read after every 4 and
 // one DMA after every 8 matrix instructions.  One barrier per slice, at its start.
+// (Staging the slices through registers -- plain loads two slices ahead, ds_write into a
+// two-stage ring -- was measured 3-6 % slower than the DMA ring in this kernel.)
 template <int EPI, bool B_IMG>
 __global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
   constexpr int BM = 256, BN = 256, BK = 32, NS = 4, NW = 4, WGN = 2;
@@ -812,7 +809,7 @@ hipError_t gemm_mfma(int form, int M, int N, int K, const void* A, const void* B
     if (form == 0) {
       if (ep.gelu_out) return ep.gelu_kind == 0 ? GPTS_IMG(EPI_GELU_TANH) : GPTS_IMG(EPI_GELU_ERF);
       if (ep.residual && ep.residual_f32) return ep.out_f32 ? GPTS_IMG(EPI_BIAS_RES32_OUT32) : GPTS_IMG(EPI_BIAS_RES32_OUT16);
-      return GPTS_IMG(EPI_BIAS_RES);
+      return ep.residual ? GPTS_IMG(EPI_BIAS_RES) : GPTS_IMG(EPI_BIAS);
     }
     if (ep.dgelu_u) return ep.gelu_kind == 0 ? GPTS_IMG(EPI_DGELU_TANH) : GPTS_IMG(EPI_DGELU_ERF);
     return GPTS_IMG(EPI_PLAIN);
@@ -825,7 +822,7 @@ hipError_t gemm_mfma(int form, int M, int N, int K, const void* A, const void* B
     if (ep.residual && ep.residual_f32)
       return ep.out_f32 ? pick_tile<false, false, EPI_BIAS_RES32_OUT32>(a, st)
                         : pick_tile<false, false, EPI_BIAS_RES32_OUT16>(a, st);
-    return pick_tile<false, false, EPI_BIAS_RES>(a, st);
+    return ep.residual ? pick_tile<false, false, EPI_BIAS_RES>(a, st) : pick_tile<false, false, EPI_BIAS>(a, st);
   }
   if (form == 1) {
     if (ep.dgelu_u)
