@@ -175,6 +175,14 @@ template <int R, int WR, int BK, bool KMAJOR, bool NAT, bool IMG = false, int NW
   }
 };
 
+// eight bf16 from two transposing LDS reads (each delivers 4 consecutive k of the lane's column)
+__device__ __forceinline__ bf16x8 tr_pair(const char* p0, const char* p1) {
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p0);
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p1);
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
 // Scheduling hint for one MFMA step: spread the LDS reads that fetch the next
 // step's fragments (and, with N_DMA > 0, the DMA instructions of a later slice)
 // between the MFMAs of the current step, one read after each of the first MFMAs.
@@ -604,8 +612,12 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const MfmaArgs a) {
 // one DMA after every 8 matrix instructions.  One barrier per slice, at its start.
 // (Staging the slices through registers -- plain loads two slices ahead, ds_write into a
 // two-stage ring -- was measured 3-6 % slower than the DMA ring in this kernel.)
-template <int EPI, bool B_IMG>
+// KM: both operands K-major (wgrad: A is [K, M], B is [K, N]); their slices sit in LDS as they
+// sit in memory (32 k-rows of 512 bytes, 32-byte units swizzled with the k-row) and a fragment
+// is two transposing reads: lane group lane>>4 is the k-octet, lane&15 the column.
+template <int EPI, bool B_IMG, bool KM = false>
 __global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
+  static_assert(!(KM && B_IMG), "images are K-contiguous");
   constexpr int BM = 256, BN = 256, BK = 32, NS = 4, NW = 4, WGN = 2;
   constexpr int WM = BM / 2, WN = BN / WGN, NB = WM / 16;   // 8 x 8 blocks of 16 x 16 per wave
   constexpr int A_BYTES = BM * BK * 2, STAGE = A_BYTES + BN * BK * 2, RB = BK * 2;
@@ -627,25 +639,50 @@ __global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
   const int m0 = tm_i * BM, n0 = tn_i * BN;
   const int nk = a.K / BK;                      // a multiple of 4 (checked by the dispatcher)
 
-  Operand<BM, WM, BK, false, true, false, NW> opA;
-  Operand<BN, WN, BK, false, true, B_IMG, NW> opB;
-  opA.init(m0, a.M, (size_t)a.K, wave, lane, wm * WM);
-  opB.init(n0, a.N, (size_t)a.K, wave, lane, wn * WN);
+  const size_t lda = KM ? (size_t)a.M : (size_t)a.K, ldb = KM ? (size_t)a.N : (size_t)a.K;
+  Operand<BM, WM, BK, KM, true, false, NW> opA;
+  Operand<BN, WN, BK, KM, true, B_IMG, NW> opB;
+  opA.init(m0, a.M, lda, wave, lane, wm * WM);
+  opB.init(n0, a.N, ldb, wave, lane, wn * WN);
   constexpr int NIA = BM * BK * 2 / 1024 / NW, NIB = BN * BK * 2 / 1024 / NW, N_DMA = NIA + NIB;
   static_assert(N_DMA == 8 && NB == 8, "the slice schedule below is written for 8 DMA instructions and 8 x 8 blocks");
 
-  // fragment of 16 rows x 32 k: lane reads chunk lane>>4 of row lane&15 (the swizzle has period 16 rows)
+  // K-contiguous: fragment of 16 rows x 32 k: lane reads chunk lane>>4 of row lane&15 (the
+  // swizzle has period 16 rows)
   const int frag_off = (lane & 15) * RB + (((lane >> 4) ^ swz_kc<BK / 8>(lane & 15)) << 4);
-  const char* fragA = lds + wm * WM * RB + frag_off;
-  const char* fragB = lds + A_BYTES + wn * WN * RB + frag_off;
+  const char* fragA = lds + (KM ? 0 : wm * WM * RB + frag_off);
+  const char* fragB = lds + A_BYTES + (KM ? 0 : wn * WN * RB + frag_off);
+  // K-major: transposing read t (0, 1) of block rb fetches k-rows 8*(lane>>4) + 4t + 0..3 of the
+  // block's 16 columns; the lane supplies the address of k-row +(lane&15)>>2, 8-byte piece lane&3
+  int rdA[KM ? 2 : 1][KM ? NB : 1], rdB[KM ? 2 : 1][KM ? NB : 1];
+  if constexpr (KM) {
+    constexpr int ROWB = BM * 2;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int k = 8 * (lane >> 4) + 4 * t + ((lane & 15) >> 2), sw = swz_km<true>(k);
+#pragma unroll
+      for (int rb = 0; rb < NB; ++rb) {
+        rdA[t][rb] = k * ROWB + (((((wm * WM) >> 4) + rb) ^ sw) << 5) + (lane & 3) * 8;
+        rdB[t][rb] = k * ROWB + (((((wn * WN) >> 4) + rb) ^ sw) << 5) + (lane & 3) * 8;
+      }
+    }
+  }
+  auto frag_a = [&](int stage, int rb) -> bf16x8 {
+    if constexpr (!KM) return *reinterpret_cast<const bf16x8*>(fragA + stage * STAGE + rb * 16 * RB);
+    else return tr_pair(fragA + stage * STAGE + rdA[0][rb], fragA + stage * STAGE + rdA[1][rb]);
+  };
+  auto frag_b = [&](int stage, int rb) -> bf16x8 {
+    if constexpr (!KM) return *reinterpret_cast<const bf16x8*>(fragB + stage * STAGE + rb * 16 * RB);
+    else return tr_pair(fragB + stage * STAGE + rdB[0][rb], fragB + stage * STAGE + rdB[1][rb]);
+  };
   bf16x8 fa[2][NB], fb[2][NB];
 
   agpr_clear_all();
 
   auto dma = [&](int slice, int stage, int i) {   // DMA instruction i of a slice: A first, then B
     const int sl = min(slice, nk - 1);
-    if (i < NIA) opA.issue_one(a.A, (size_t)a.K, sl, lds_base + stage * STAGE, wave, i);
-    else opB.issue_one(a.B, (size_t)a.K, sl, lds_base + stage * STAGE + A_BYTES, wave, i - NIA);
+    if (i < NIA) opA.issue_one(a.A, lda, sl, lds_base + stage * STAGE, wave, i);
+    else opB.issue_one(a.B, ldb, sl, lds_base + stage * STAGE + A_BYTES, wave, i - NIA);
   };
 #pragma unroll
   for (int s0 = 0; s0 < NS - 1; ++s0)
@@ -654,8 +691,8 @@ __global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
   wait_dma_and_barrier<(NS - 2) * N_DMA>();   // slice 0 has landed
 #pragma unroll
   for (int u = 0; u < NB; ++u) {
-    fa[0][u] = *reinterpret_cast<const bf16x8*>(fragA + u * 16 * RB);
-    fb[0][u] = *reinterpret_cast<const bf16x8*>(fragB + u * 16 * RB);
+    fa[0][u] = frag_a(0, u);
+    fb[0][u] = frag_b(0, u);
   }
 
   for (int kt = 0; kt < nk; kt += NS) {
@@ -675,8 +712,8 @@ __global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
         });
         __builtin_amdgcn_sched_barrier(0);
         // one fragment of the next slice
-        if constexpr (g < NB) fa[nxt][g] = *reinterpret_cast<const bf16x8*>(fragA + st_next * STAGE + g * 16 * RB);
-        else fb[nxt][g - NB] = *reinterpret_cast<const bf16x8*>(fragB + st_next * STAGE + (g - NB) * 16 * RB);
+        if constexpr (g < NB) fa[nxt][g] = frag_a(st_next, g);
+        else fb[nxt][g - NB] = frag_b(st_next, g - NB);
         // and after every second group one DMA instruction of slice t+3
         if constexpr (g % 2 == 1) dma(t + NS - 1, st_fill, g / 2);
         __builtin_amdgcn_sched_barrier(0);
@@ -703,9 +740,9 @@ __global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
   gemm_epilogue<BM, BN, EPI, NW, NS * STAGE>(write_pass, a, lds, m0, n0, wm, wn, wave, lane);
 }
 
-template <int EPI, bool B_IMG> hipError_t launch_mi16(const MfmaArgs& a, hipStream_t st) {
+template <int EPI, bool B_IMG, bool KM = false> hipError_t launch_mi16(const MfmaArgs& a, hipStream_t st) {
   const int tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
-  hipLaunchKernelGGL((gemm_mi16_kernel<EPI, B_IMG>), dim3(tiles), dim3(256), 0, st, a);
+  hipLaunchKernelGGL((gemm_mi16_kernel<EPI, B_IMG, KM>), dim3(tiles), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
@@ -724,9 +761,10 @@ bool use_big_tiles(int M, int N) { return (long)((M + 255) / 256) * ((N + 255) /
 
 template <bool AK, bool BKM, int EPI> hipError_t pick_tile(const MfmaArgs& a, hipStream_t st) {
   if (use_big_tiles(a.M, a.N)) {
-    // both operands K-contiguous (forward on raw weights): the 16x16x32 kernel
-    if constexpr (!AK && !BKM) {
-      if (a.K % 128 == 0) return launch_mi16<EPI, false>(a, st);
+    // both operands K-contiguous (forward on raw weights) or both K-major (wgrad): the
+    // 16x16x32 kernel
+    if constexpr (AK == BKM) {
+      if (a.K % 128 == 0) return launch_mi16<EPI, false, AK>(a, st);
     }
     // otherwise a K-contiguous A operand (dgrad) takes the five-stage ring with paired fetches
     return launch<256, 256, 32, AK ? 4 : GPTS_KC_STAGES, AK, BKM, EPI, false, GPTS_BIG_WAVES>(a, st);

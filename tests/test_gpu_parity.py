@@ -358,7 +358,8 @@ def test_op_layernorm(dtype, T, H, x_f32):
 
 GEMM_SHAPES = [(64, 64, 64), (200, 136, 72), (256, 256, 256), (320, 448, 192), (512, 1024, 320),
                (1024, 768, 2048),
-               (3904, 3392, 192)]   # large enough for the 256x256 tiles, ragged last tile in M and N
+               (3904, 3392, 192),   # large enough for the 256x256 tiles, ragged last tile in M and N
+               (3904, 3392, 384)]   # same with K a multiple of 128: the 16x16x32 kernels (NT and TN)
 
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
