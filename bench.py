@@ -279,7 +279,7 @@ def main():
     flops_dense = B.gpt_stage_model_flops(bufs.cfg, False) * n_mb
     tflops = flops / (ms * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if shape.dtype == "bf16" else PEAK_FP32_TFLOPS
-    ops_per_step = (25 if shape.recompute else 22) * shape.n_layers * n_mb
+    ops_per_step = (25 if shape.recompute else 22) * shape.n_layers * n_mb   # trace capacity (upper bound)
     roof, table = traced_pass(step, shape, ops_per_step, max(1, min(args.steps, 2)))
     out = {
         "metric": "model TFLOP/s for one stage fwd+bwd on 1 MI355X",

@@ -223,13 +223,16 @@ int gpt_stage_op_layernorm_fwd(int dtype, int x_f32, int T, int H, float eps, co
                                float* mean, float* rstd, void* stream);
 
 /* dx = dres + LN-backward(dout) ; dgamma += sum_t dout*xhat ; dbeta += sum_t dout.
- * dres may be NULL (treated as 0).  partial: fp32 scratch of
+ * dres may be NULL (treated as 0).  dxsum may be NULL; otherwise fp32 [H] and
+ * dxsum += sum_t dx[t,:] (dx as stored in `dtype`): dx is the gradient of the output of
+ * the linear layer that feeds the residual stream, so this is that layer's bias gradient,
+ * obtained without another pass over dx.  partial: fp32 scratch of
  * gpt_stage_op_layernorm_bwd_scratch_bytes(T,H). */
 size_t gpt_stage_op_layernorm_bwd_scratch_bytes(int T, int H);
 int gpt_stage_op_layernorm_bwd(int dtype, int x_f32, int T, int H, const void* dout, const void* x,
                                const float* mean, const float* rstd, const void* gamma,
                                const void* dres, void* dx, float* dgamma, float* dbeta,
-                               float* partial, void* stream);
+                               float* dxsum, float* partial, void* stream);
 
 /* Matrix products of the three forms the stage uses; fp32 accumulation.
  *   form 0 (NT, forward):  C[M,N]  = A[M,K] B[N,K]^T (+ bias[N]) (+ residual[M,N])

@@ -124,7 +124,7 @@ def lib() -> C.CDLL:
         "gpt_stage_fwd_bwd": (i32, [parp, vp, vp, vp, vp, vp, vp, vp]),
         "gpt_stage_op_layernorm_fwd": (i32, [i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp]),
         "gpt_stage_op_layernorm_bwd_scratch_bytes": (sz, [i32, i32]),
-        "gpt_stage_op_layernorm_bwd": (i32, [i32, i32, i32, i32] + [vp] * 11),
+        "gpt_stage_op_layernorm_bwd": (i32, [i32, i32, i32, i32] + [vp] * 12),
         "gpt_stage_op_gemm": (i32, [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp]),
         "gpt_stage_op_colsum_scratch_bytes": (sz, [i32, i32]),
         "gpt_stage_op_colsum": (i32, [i32, i32, i32, vp, vp, vp, vp]),
@@ -340,10 +340,10 @@ def gpt_stage_op_layernorm_bwd_scratch_bytes(T, H) -> int:
 
 
 def gpt_stage_op_layernorm_bwd(dtype, T, H, dout, x, mean, rstd, gamma, dres, dx, dgamma, dbeta,
-                               partial, stream=None, x_f32=False):
+                               partial, stream=None, x_f32=False, dxsum=None):
     _check(lib().gpt_stage_op_layernorm_bwd(dtype, int(x_f32), T, H, _ptr(dout), _ptr(x), _ptr(mean), _ptr(rstd),
                                             _ptr(gamma), _ptr(dres), _ptr(dx), _ptr(dgamma),
-                                            _ptr(dbeta), _ptr(partial), _stream(stream)))
+                                            _ptr(dbeta), _ptr(dxsum), _ptr(partial), _stream(stream)))
 
 
 def gpt_stage_op_gemm(dtype, form, M, N, K, A, B, Cout, bias=None, residual=None, C2=None,

@@ -1,7 +1,8 @@
 // HBM-bound kernels of the stage: LayerNorm forward/backward (with the residual
-// gradient folded in), column sums for bias gradients, and the fixed-order
-// reduction of per-workgroup partial sums.  One 256-thread workgroup (4 waves)
-// per token row, 16-byte loads, the row cached in registers, fp32 statistics.
+// gradient and the bias gradient of the preceding linear layer folded in), column sums
+// for the other bias gradients, and the fixed-order reduction of per-workgroup partial
+// sums.  One workgroup per token row at a time (256 threads forward, 512 backward),
+// 16-byte loads, the row cached in registers, fp32 statistics.
 #include "kernels.hpp"
 
 namespace gpts {
@@ -95,9 +96,15 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(
 //   dx = dres + r (g - mean(g) - xhat mean(g xhat)).
 // Each workgroup walks rows blockIdx.x, +gridDim.x, ... and keeps its share of
 // sum_t dout*xhat and sum_t dout in registers; it writes them once to
-// partial[blockIdx.x][0][H] / [1][H] for the fixed-order reduction below.
-template <typename TX, typename T, int NCH>
-__global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(
+// partial[blockIdx.x][0][H] / [1][H] for the fixed-order reduction below.  With DXSUM it
+// also keeps the column sums of dx as stored (partial[blockIdx.x][2][H]): dx is the
+// gradient of the output of the linear layer in front of the residual branch, so these
+// are that layer's bias gradient, which then needs no pass of its own over dx.
+constexpr int kLnBwdThreads = 512;
+constexpr int kLnBwdMaxBlocks = 512;
+
+template <typename TX, typename T, int NCH, bool DXSUM>
+__global__ __launch_bounds__(kLnBwdThreads) void ln_bwd_kernel(
     const T* __restrict__ dout, const TX* __restrict__ x, const float* __restrict__ mean,
     const float* __restrict__ rstd, const T* __restrict__ gamma, const T* __restrict__ dres,
     T* __restrict__ dx, float* __restrict__ partial, int T_rows, int H) {
@@ -105,25 +112,28 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(
   // between rows, so a row's writes cannot overtake the previous row's reads.  The loads of
   // the next row (when the row fits few registers) and of the residual gradient are issued
   // before the barrier, so that memory latency overlaps the reduction.
-  constexpr int NWV = kLnThreads / kWave;
+  constexpr int NT = kLnBwdThreads, NWV = NT / kWave, NPART = DXSUM ? 3 : 2;
   constexpr bool PREFETCH = NCH <= 2;
   __shared__ float red[2][2][NWV];
   const int nvec = H / 8;
   const int wv = threadIdx.x / kWave;
-  float dg[NCH][8], db[NCH][8], gam[NCH][8];
+  float dg[NCH][8], db[NCH][8], dc[DXSUM ? NCH : 1][8], gam[NCH][8];
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
-    const int i = threadIdx.x + c * kLnThreads;
+    const int i = threadIdx.x + c * NT;
     if (i < nvec) load8(gamma + (size_t)i * 8, gam[c]);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) dg[c][e] = db[c][e] = 0.f;
+    for (int e = 0; e < 8; ++e) {
+      dg[c][e] = db[c][e] = 0.f;
+      if constexpr (DXSUM) dc[c][e] = 0.f;
+    }
   }
   float dv[NCH][8], xh[NCH][8], dvn[PREFETCH ? NCH : 1][8], xn[PREFETCH ? NCH : 1][8];
   auto load_row = [&](int row, float (&d)[NCH][8], float (&xx)[NCH][8]) {
     const size_t base = (size_t)row * H;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-      const int i = threadIdx.x + c * kLnThreads;
+      const int i = threadIdx.x + c * NT;
       if (i < nvec) {
         load8(dout + base + (size_t)i * 8, d[c]);
         load8(x + base + (size_t)i * 8, xx[c]);
@@ -141,7 +151,7 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-      const int i = threadIdx.x + c * kLnThreads;
+      const int i = threadIdx.x + c * NT;
       if (i < nvec) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -165,7 +175,7 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(
     if (dres) {
 #pragma unroll
       for (int c = 0; c < NCH; ++c) {
-        const int i = threadIdx.x + c * kLnThreads;
+        const int i = threadIdx.x + c * NT;
         if (i < nvec) load8(dres + base + (size_t)i * 8, rs[c]);
       }
     }
@@ -184,7 +194,7 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(
     m2 /= (float)H;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-      const int i = threadIdx.x + c * kLnThreads;
+      const int i = threadIdx.x + c * NT;
       if (i < nvec) {
         float o[8];
 #pragma unroll
@@ -192,6 +202,7 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(
           float v = r * (dv[c][e] * gam[c][e] - m1 - xh[c][e] * m2);
           if (dres) v += rs[c][e];
           o[e] = v;
+          if constexpr (DXSUM) dc[c][e] += (float)(T)v;
         }
         store8(dx + base + (size_t)i * 8, o);
       }
@@ -206,13 +217,14 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(
         }
     }
   }
-  float* pg = partial + (size_t)blockIdx.x * 2 * H;
+  float* pg = partial + (size_t)blockIdx.x * NPART * H;
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
-    const int i = threadIdx.x + c * kLnThreads;
+    const int i = threadIdx.x + c * NT;
     if (i < nvec) {
       store8(pg + (size_t)i * 8, dg[c]);
       store8(pg + (size_t)H + (size_t)i * 8, db[c]);
+      if constexpr (DXSUM) store8(pg + (size_t)2 * H + (size_t)i * 8, dc[c]);
     }
   }
 }
@@ -227,27 +239,29 @@ __global__ __launch_bounds__(256) void widen_kernel(const bf16* __restrict__ in,
   store8(out + i * 8, v);
 }
 
-// out[c] += sum_{g<G} partial[g*stride + c] for c < N0 (into out0) and N0 <= c < N
-// (into out1[c-N0]).  32 columns x 8 row groups per workgroup; the row groups are
-// combined through LDS in fixed order, so the result is deterministic.
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial,
-                                                              float* __restrict__ out0,
-                                                              float* __restrict__ out1, int G,
-                                                              size_t stride, int N0, int N) {
-  __shared__ float sm[8][32];
+// out[c] += sum_{g<G} partial[g*stride + c], the columns c < N being split at N0 and N1
+// over out0 (c < N0), out1 (N0 <= c < N1) and out2 (N1 <= c).  32 columns x 32 row groups per
+// workgroup; the row groups are combined through LDS in fixed order, so the result is
+// deterministic.
+__global__ __launch_bounds__(1024) void reduce_partials_kernel(const float* __restrict__ partial, int G,
+                                                               size_t stride, int N, float* __restrict__ out0,
+                                                               int N0, float* __restrict__ out1, int N1,
+                                                               float* __restrict__ out2) {
+  __shared__ float sm[32][33];
   const int cx = threadIdx.x & 31, ry = threadIdx.x >> 5;
   const int c = blockIdx.x * 32 + cx;
   float s = 0.f;
   if (c < N)
-    for (int g = ry; g < G; g += 8) s += partial[(size_t)g * stride + c];
+    for (int g = ry; g < G; g += 32) s += partial[(size_t)g * stride + c];
   sm[ry][cx] = s;
   __syncthreads();
   if (ry == 0 && c < N) {
     float t = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) t += sm[i][cx];
+    for (int i = 0; i < 32; ++i) t += sm[i][cx];
     if (c < N0) out0[c] += t;
-    else out1[c - N0] += t;
+    else if (c < N1) out1[c - N0] += t;
+    else out2[c - N1] += t;
   }
 }
 
@@ -314,18 +328,24 @@ hipError_t ln_fwd(int dtype, bool x_f32, int T_rows, int H, float eps, const voi
                               (bf16*)out, mean, rstd, st);
 }
 
-int ln_bwd_blocks(int T_rows) { return T_rows < 512 ? T_rows : 512; }
+int ln_bwd_blocks(int T_rows) { return T_rows < kLnBwdMaxBlocks ? T_rows : kLnBwdMaxBlocks; }
 
 template <typename TX, typename T>
 static hipError_t ln_bwd_t(int T_rows, int H, const T* dout, const TX* x, const float* mean,
                            const float* rstd, const T* gamma, const T* dres, T* dx, float* dgamma,
-                           float* dbeta, float* partial, hipStream_t st) {
-  const int nch = (H / 8 + kLnThreads - 1) / kLnThreads;
+                           float* dbeta, float* dxsum, float* partial, hipStream_t st) {
+  const int nch = (H / 8 + kLnBwdThreads - 1) / kLnBwdThreads;
   const int G = ln_bwd_blocks(T_rows);
-  dim3 g(G), b(kLnThreads);
-#define GPTS_LN_BWD(N)                                                                              \
-  hipLaunchKernelGGL((ln_bwd_kernel<TX, T, N>), g, b, 0, st, dout, x, mean, rstd, gamma, dres, dx, \
-                     partial, T_rows, H)
+  dim3 g(G), b(kLnBwdThreads);
+#define GPTS_LN_BWD(N)                                                                                  \
+  do {                                                                                                  \
+    if (dxsum)                                                                                          \
+      hipLaunchKernelGGL((ln_bwd_kernel<TX, T, N, true>), g, b, 0, st, dout, x, mean, rstd, gamma, dres, \
+                         dx, partial, T_rows, H);                                                       \
+    else                                                                                                \
+      hipLaunchKernelGGL((ln_bwd_kernel<TX, T, N, false>), g, b, 0, st, dout, x, mean, rstd, gamma,     \
+                         dres, dx, partial, T_rows, H);                                                 \
+  } while (0)
   if (nch <= 1) GPTS_LN_BWD(1);
   else if (nch <= 2) GPTS_LN_BWD(2);
   else if (nch <= 4) GPTS_LN_BWD(4);
@@ -333,24 +353,27 @@ static hipError_t ln_bwd_t(int T_rows, int H, const T* dout, const TX* x, const 
 #undef GPTS_LN_BWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * H + 31) / 32), dim3(256), 0, st, partial, dgamma,
-                     dbeta, G, (size_t)2 * H, H, 2 * H);
+  const int np = dxsum ? 3 : 2;
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((np * H + 31) / 32), dim3(1024), 0, st, partial, G,
+                     (size_t)np * H, np * H, dgamma, H, dbeta, 2 * H, dxsum);
   return hipGetLastError();
 }
 
 hipError_t ln_bwd(int dtype, bool x_f32, int T_rows, int H, const void* dout, const void* x,
                   const float* mean, const float* rstd, const void* gamma, const void* dres, void* dx,
-                  float* dgamma, float* dbeta, float* partial, hipStream_t st) {
+                  float* dgamma, float* dbeta, float* dxsum, float* partial, hipStream_t st) {
+  if (H > 8 * 8 * kLnBwdThreads) return hipErrorInvalidValue;
   if (dtype == 0)
     return ln_bwd_t<float, float>(T_rows, H, (const float*)dout, (const float*)x, mean, rstd,
                                   (const float*)gamma, (const float*)dres, (float*)dx, dgamma, dbeta,
-                                  partial, st);
+                                  dxsum, partial, st);
   if (x_f32)
     return ln_bwd_t<float, bf16>(T_rows, H, (const bf16*)dout, (const float*)x, mean, rstd,
                                  (const bf16*)gamma, (const bf16*)dres, (bf16*)dx, dgamma, dbeta,
-                                 partial, st);
+                                 dxsum, partial, st);
   return ln_bwd_t<bf16, bf16>(T_rows, H, (const bf16*)dout, (const bf16*)x, mean, rstd,
-                              (const bf16*)gamma, (const bf16*)dres, (bf16*)dx, dgamma, dbeta, partial, st);
+                              (const bf16*)gamma, (const bf16*)dres, (bf16*)dx, dgamma, dbeta, dxsum,
+                              partial, st);
 }
 
 // g[i] = gelu(u[i]), 8 elements per thread (recomputation of the MLP activation)
@@ -386,7 +409,7 @@ hipError_t widen_to_f32(const void* in, float* out, size_t n, hipStream_t st) {
 }
 
 size_t ln_bwd_scratch_bytes(int T_rows, int H) {
-  return (size_t)ln_bwd_blocks(T_rows) * 2 * H * sizeof(float);
+  return (size_t)ln_bwd_blocks(T_rows) * 3 * H * sizeof(float);
 }
 
 int colsum_splits(int M) { return M < 4 * 64 ? (M + 3) / 4 : 64; }
@@ -403,8 +426,8 @@ hipError_t colsum(int dtype, int M, int N, const void* A, float* out, float* par
     hipLaunchKernelGGL(colsum_partial_kernel<bf16>, g, b, 0, st, (const bf16*)A, partial, M, N);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((N + 31) / 32), dim3(256), 0, st, partial, out,
-                     (float*)nullptr, G, (size_t)N, N, N);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((N + 31) / 32), dim3(1024), 0, st, partial, G, (size_t)N, N,
+                     out, N, (float*)nullptr, N, (float*)nullptr);
   return hipGetLastError();
 }
 

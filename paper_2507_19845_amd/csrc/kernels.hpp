@@ -12,9 +12,10 @@ hipError_t ln_fwd(int dtype, bool x_f32, int T_rows, int H, float eps, const voi
                   const void* gamma, const void* beta, void* out, float* mean, float* rstd,
                   hipStream_t st);
 size_t ln_bwd_scratch_bytes(int T_rows, int H);
+// dxsum (may be null): += column sums of dx as stored
 hipError_t ln_bwd(int dtype, bool x_f32, int T_rows, int H, const void* dout, const void* x,
                   const float* mean, const float* rstd, const void* gamma, const void* dres, void* dx,
-                  float* dgamma, float* dbeta, float* partial, hipStream_t st);
+                  float* dgamma, float* dbeta, float* dxsum, float* partial, hipStream_t st);
 // out[i] = (float) in[i] for n bf16 elements (n a multiple of 8)
 hipError_t widen_to_f32(const void* in, float* out, size_t n, hipStream_t st);
 // g = gelu(u) elementwise (kind 0 tanh form, 1 erf form); n a multiple of 8

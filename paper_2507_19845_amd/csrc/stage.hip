@@ -391,7 +391,10 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
       G = wk + ws.rG;
     }
     GPTS_OP(GPTS_TR_GEMM_WGRAD, 3, 1, gf(D.H, D.F, D.T), gb(D.H, D.F, D.T, 8), gemm(dt, 2, D.H, D.F, D.T, dY, G, g(l, GPTS_W_FC2), none, st), "fc2 wgrad");
-    GPTS_OP(GPTS_TR_BIAS_GRAD, 3, 1, 0.0, TH * e, colsum(dt, D.T, D.H, dY, g(l, GPTS_B_FC2), cs_part, st), "fc2 bias grad");
+    // the bias gradient of fc2 is the column sum of the layer's incoming gradient: below the
+    // top layer the LayerNorm backward that produced that gradient has summed it already
+    if (l == c.n_layers - 1)
+      GPTS_OP(GPTS_TR_BIAS_GRAD, 3, 1, 0.0, TH * e, colsum(dt, D.T, D.H, dY, g(l, GPTS_B_FC2), cs_part, st), "fc2 bias grad");
     // u = a2 W1^T + b1
     GPTS_OP(GPTS_TR_GEMM_DGRAD, 2, 1, gf(D.T, D.H, D.F), gb(D.T, D.H, D.F, e), gemm(dt, 1, D.T, D.H, D.F, dU, w(l, GPTS_W_FC1), dA, d_fc1, st), "fc1 dgrad");
     const void* A2 = s + sl.A2;
@@ -405,11 +408,10 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     GPTS_OP(GPTS_TR_BIAS_GRAD, 2, 1, 0.0, (double)D.T * D.F * e, colsum(dt, D.T, D.F, dU, g(l, GPTS_B_FC1), cs_part, st), "fc1 bias grad");
     // a2 = LN2(x1), x1 also feeds the residual
     GPTS_OP(GPTS_TR_LN_BWD, 1, 1, 0.0, TH * (3 * e + kResBytes), ln_bwd(dt, dt == GPTS_BF16, D.T, D.H, dA, s + sl.X1, stat2, stat2 + D.T, w(l, GPTS_LN2_G), dY, dX1,
-                    g(l, GPTS_LN2_G), g(l, GPTS_LN2_B), ln_part, st), "ln2 bwd");
+                    g(l, GPTS_LN2_G), g(l, GPTS_LN2_B), g(l, GPTS_B_O), ln_part, st), "ln2 bwd (+ out-proj bias grad)");
     // x1 = x + c Wo^T + bo
     GPTS_OP(GPTS_TR_GEMM_DGRAD, 1, 1, gf(D.T, D.P, D.H), gb(D.T, D.P, D.H, e), gemm(dt, 1, D.T, D.P, D.H, dX1, w(l, GPTS_W_O), dC, d_o, st), "out-proj dgrad");
     GPTS_OP(GPTS_TR_GEMM_WGRAD, 1, 1, gf(D.H, D.P, D.T), gb(D.H, D.P, D.T, 8), gemm(dt, 2, D.H, D.P, D.T, dX1, s + sl.C, g(l, GPTS_W_O), none, st), "out-proj wgrad");
-    GPTS_OP(GPTS_TR_BIAS_GRAD, 1, 1, 0.0, TH * e, colsum(dt, D.T, D.H, dX1, g(l, GPTS_B_O), cs_part, st), "out-proj bias grad");
     // c = attention(qkv)
     GPTS_OP(GPTS_TR_ATTN_BWD, 0, 1, 2.0 * attn_fl, (double)D.T * 9 * D.P * e, attention_bwd(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
                                   reinterpret_cast<const float*>(s + sl.LSE), dC, dQKV, attn_scratch, st),
@@ -427,7 +429,8 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     GPTS_OP(GPTS_TR_BIAS_GRAD, 0, 1, 0.0, (double)D.T * 3 * D.P * e, colsum(dt, D.T, 3 * D.P, dQKV, g(l, GPTS_B_QKV), cs_part, st), "qkv bias grad");
     // a = LN1(x), x also feeds the residual
     GPTS_OP(GPTS_TR_LN_BWD, 0, 1, 0.0, TH * (3 * e + kResBytes), ln_bwd(dt, dt == GPTS_BF16, D.T, D.H, dA, s + sl.X, stat1, stat1 + D.T, w(l, GPTS_LN1_G), dX1, dXout,
-                    g(l, GPTS_LN1_G), g(l, GPTS_LN1_B), ln_part, st), "ln1 bwd");
+                    g(l, GPTS_LN1_G), g(l, GPTS_LN1_B), l > 0 ? g(l - 1, GPTS_B_FC2) : nullptr, ln_part, st),
+            "ln1 bwd (+ fc2 bias grad of the layer below)");
     dY = dXout;
   }
   return GPTS_OK;
@@ -640,11 +643,11 @@ size_t gpt_stage_op_layernorm_bwd_scratch_bytes(int T, int H) { return ln_bwd_sc
 int gpt_stage_op_layernorm_bwd(int dtype, int x_f32, int T, int H, const void* dout, const void* x,
                                const float* mean, const float* rstd, const void* gamma,
                                const void* dres, void* dx, float* dgamma, float* dbeta,
-                               float* partial, void* stream) {
+                               float* dxsum, float* partial, void* stream) {
   if (!op_dtype_ok(dtype) || !dout || !x || !mean || !rstd || !gamma || !dx || !dgamma || !dbeta || !partial)
     return fail(GPTS_EINVAL, "layernorm_bwd: bad argument");
   if (T < 1 || H < 8 || H % 8 || H > 16384) return fail(GPTS_ESHAPE, "layernorm_bwd: H must be a multiple of 8, <= 16384");
-  GPTS_TRY(ln_bwd(dtype, x_f32 != 0, T, H, dout, x, mean, rstd, gamma, dres, dx, dgamma, dbeta, partial,
+  GPTS_TRY(ln_bwd(dtype, x_f32 != 0, T, H, dout, x, mean, rstd, gamma, dres, dx, dgamma, dbeta, dxsum, partial,
                   static_cast<hipStream_t>(stream)), "layernorm_bwd");
   return GPTS_OK;
 }

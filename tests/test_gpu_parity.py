@@ -145,11 +145,14 @@ def test_operator_tracer_records_every_operator():
         recs, dropped = B.gpt_stage_trace_collect(tr, 64)
     finally:
         B.set_trace(None)
-    assert dropped == 0 and len(recs) == 22 * shape.n_layers
+    # per layer 7 forward and 13 backward operators (the out-proj and fc2 bias gradients ride on
+    # the LayerNorm backward kernels), plus the top layer's fc2 bias gradient
+    n_ops = 20 * shape.n_layers + 1
+    assert dropped == 0 and len(recs) == n_ops
     assert [r["op"] for r in recs[:7]] == ["layernorm_fwd", "gemm_fwd", "attention_fwd", "gemm_fwd",
                                           "layernorm_fwd", "gemm_fwd", "gemm_fwd"]
-    assert [r["phase"] for r in recs] == [0] * 14 + [1] * 30
-    assert [r["layer"] for r in recs[14:]] == [1] * 15 + [0] * 15          # backward walks layers in reverse
+    assert [r["phase"] for r in recs] == [0] * 14 + [1] * 27
+    assert [r["layer"] for r in recs[14:]] == [1] * 14 + [0] * 13          # backward walks layers in reverse
     assert all(r["dur_ms"] > 0 for r in recs)
     assert all(b["start_ms"] >= a["start_ms"] for a, b in zip(recs, recs[1:]))
     T, H, F = shape.tokens, shape.hidden, shape.ffn
@@ -168,7 +171,7 @@ def test_operator_tracer_records_every_operator():
         B.set_trace(None)
         B.gpt_stage_trace_destroy(small)
         B.gpt_stage_trace_destroy(tr)
-    assert len(recs2) == 5 and dropped2 == 22 * shape.n_layers - 5
+    assert len(recs2) == 5 and dropped2 == n_ops - 5
 
 
 def test_run_to_run_bitwise_determinism():
@@ -354,6 +357,16 @@ def test_op_layernorm(dtype, T, H, x_f32):
     assert max_norm_err(B.to_host(dxo), rdx + dres) <= tol
     assert max_norm_err(B.to_host(dgam), rdg + 1.0) <= max(tol * 0.1, 1e-5)
     assert max_norm_err(B.to_host(dbet), rdb - 2.0) <= max(tol * 0.1, 1e-5)
+    # same call with the column sums of dx requested (the fused bias gradient): dx, dgamma and
+    # dbeta bit-identical to the call without, the sums += into a pre-filled vector
+    dgam2 = torch.full((H,), 1.0, dtype=torch.float32, device="cuda")
+    dbet2 = torch.full((H,), -2.0, dtype=torch.float32, device="cuda")
+    dxs = torch.full((H,), 0.5, dtype=torch.float32, device="cuda")
+    dxo2 = torch.empty_like(out)
+    B.gpt_stage_op_layernorm_bwd(dt, T, H, B.to_device(dout, dtype), dx_, mean, rstd, dg_,
+                                 B.to_device(dres, dtype), dxo2, dgam2, dbet2, part, x_f32=x_f32, dxsum=dxs)
+    assert torch.equal(dxo2, dxo) and torch.equal(dgam2, dgam) and torch.equal(dbet2, dbet)
+    assert max_norm_err(B.to_host(dxs), (rdx + dres).sum(0) + 0.5) <= max(tol * 0.1, 1e-5)
 
 
 GEMM_SHAPES = [(64, 64, 64), (200, 136, 72), (256, 256, 256), (320, 448, 192), (512, 1024, 320),
