@@ -26,7 +26,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # summary under profiles/ has the commands and the per-kernel figures).  Only reported while
 # the kernel source is the one the counters were taken on.
 GEMM_TRAFFIC = {"workload": "decoupled_bf16", "bytes_per_launch": 784.0 * 2**20,
-                "source_sha256_16": "4af74c334479f771"}
+                "source_sha256_16": "529df1122ac23b76"}
 PEAK_FP32_TFLOPS = 157.3    # MI355X fp32 vector
 DEFAULT_WORKLOAD = "decoupled_bf16"
 
@@ -136,7 +136,7 @@ def traced_pass(step, shape, n_ops, steps):
     achieved = fl / ms / 1e9
     roof = {"bound": "mfma" if shape.dtype == "bf16" else "alu", "achieved": achieved, "peak": peak,
             "unit": "TFLOP/s", "frac": achieved / peak, "traffic": gemm_traffic(shape),
-            "kernel": "gemm_mi16_kernel (forward, dgrad) + gemm_mfma_kernel (wgrad): the 12 matrix products of a layer",
+            "kernel": "gemm_mi16_kernel: the 12 matrix products of a layer (forward, dgrad, wgrad)",
             "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
             "algorithmic_bytes_per_launch": sum(c["bytes"] for c in gemm) / n,
             "launches": n, "avg_launch_ms": ms / n, "flops_per_launch": fl / n,
