@@ -62,13 +62,13 @@ def pick_workload(arg):
 
 def cpu_baseline(shape):
     """Time the oracle, as it stands, on a bounded sample of the workload:
-    one layer, one micro-batch, the first min(S, 2048) tokens of each sequence."""
+    one layer, one micro-batch, the first min(S, 4096) tokens of each sequence."""
     import numpy as np
     from threadpoolctl import threadpool_info
     from oracle import gpt_stage_oracle as orc
     from paper_2507_19845_amd import binding as B
     from paper_2507_19845_amd import synth
-    s = shape.with_(n_layers=1, seq=min(shape.seq, 2048), n_microbatches=1)
+    s = shape.with_(n_layers=1, seq=min(shape.seq, 4096), n_microbatches=1)
     params = [{k: v.astype(np.float64) for k, v in synth.make_layer_params(s, 0, 0).items()}]
     x, dy = synth.make_x(s, 0).astype(np.float64), synth.make_dy(s, 0).astype(np.float64)
     t0 = time.perf_counter()
