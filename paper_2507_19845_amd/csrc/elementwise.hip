@@ -415,6 +415,12 @@ size_t ln_bwd_scratch_bytes(int T_rows, int H) {
 int colsum_splits(int M) { return M < 4 * 64 ? (M + 3) / 4 : 64; }
 size_t colsum_scratch_bytes(int M, int N) { return (size_t)colsum_splits(M) * N * sizeof(float); }
 
+hipError_t reduce_colsum_partials(const float* partial, int G, int N, float* out, hipStream_t st) {
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((N + 31) / 32), dim3(1024), 0, st, partial, G, (size_t)N, N,
+                     out, N, (float*)nullptr, N, (float*)nullptr);
+  return hipGetLastError();
+}
+
 hipError_t colsum(int dtype, int M, int N, const void* A, float* out, float* partial,
                   hipStream_t st) {
   const int G = colsum_splits(M);

@@ -61,6 +61,7 @@ struct MfmaArgs {
   const void* residual;
   bf16* gelu_out;
   const bf16* dgelu_u;
+  float* colsum;   // GeLU' epilogue only, may be null: per-wave-row column sums of C
 };
 
 // 16-byte chunk swizzle of a K-contiguous tile row with CPR chunks per row.  Chosen
@@ -249,6 +250,9 @@ __device__ __forceinline__ void gemm_epilogue(StageWriter&& write_pass, const Mf
   constexpr bool GELU = EPI == EPI_GELU_TANH || EPI == EPI_GELU_ERF;
   constexpr bool DGELU = EPI == EPI_DGELU_TANH || EPI == EPI_DGELU_ERF;
   float bias_v[4] = {0.f, 0.f, 0.f, 0.f};
+  // GeLU' epilogue: the lane's share of the column sums of C, before rounding to bf16 (the bias
+  // gradient of the linear layer whose output gradient this product forms)
+  float cs[4] = {0.f, 0.f, 0.f, 0.f};
   if constexpr (EPI == EPI_BIAS_RES || EPI == EPI_BIAS || RES32 || GELU) {
     if (a.bias && n_ok) {
       const bf16x4 b = *reinterpret_cast<const bf16x4*>(a.bias + n);
@@ -327,11 +331,30 @@ __device__ __forceinline__ void gemm_epilogue(StageWriter&& write_pass, const Mf
 #pragma unroll
             for (int e = 0; e < 4; ++e) out[e] = (bf16)v[e];
             *reinterpret_cast<bf16x4*>(static_cast<bf16*>(a.C) + o[u]) = out;
+            if constexpr (DGELU) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) cs[e] += v[e];
+            }
           }
         }
       }
     }
   });
+  if constexpr (DGELU) {
+    if (a.colsum) {
+      // lanes CW apart hold the same columns of different rows
+#pragma unroll
+      for (int off = CW; off < 64; off <<= 1)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cs[e] += __shfl_xor(cs[e], off);
+      if (lane < CW && n_ok) {
+        f32x4 out;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[e] = cs[e];
+        *reinterpret_cast<f32x4*>(a.colsum + (size_t)((m0 / BM) * 2 + wm) * a.N + n) = out;
+      }
+    }
+  }
 }
 
 template <int BM, int BN, int BK, int NS, bool A_KMAJOR, bool B_KMAJOR, int EPI, bool B_IMG = false, int NW = 4>
@@ -821,6 +844,11 @@ bool gemm_mfma_supported(int form, int M, int N, int K) {
          (size_t)M * K < (1ull << 31) && (size_t)N * K < (1ull << 31);
 }
 
+int gemm_mfma_colsum_rows(int M, int N) {
+  const int bm = use_big_tiles(M, N) ? 256 : 128;
+  return 2 * ((M + bm - 1) / bm);
+}
+
 size_t gemm_image_elems(int N, int K) { return (size_t)((N + 255) / 256) * 256 * K; }
 
 hipError_t gemm_prepare_image(const void* src, void* img, int N, int K, bool transposed, hipStream_t st) {
@@ -838,6 +866,7 @@ hipError_t gemm_mfma(int form, int M, int N, int K, const void* A, const void* B
   a.M = M; a.N = N; a.K = K;
   a.bias = (const bf16*)ep.bias; a.residual = ep.residual;
   a.gelu_out = (bf16*)ep.gelu_out; a.dgelu_u = (const bf16*)ep.dgelu_u;
+  a.colsum = ep.dgelu_u ? ep.colsum_partial : nullptr;
   if (ep.b_image && form != 2 && use_big_tiles(M, N)) {
     // B comes as the image of its [N rows, K] K-contiguous view: forward and dgrad are
     // then the same product with different epilogues.

@@ -21,8 +21,11 @@ hipError_t widen_to_f32(const void* in, float* out, size_t n, hipStream_t st);
 // g = gelu(u) elementwise (kind 0 tanh form, 1 erf form); n a multiple of 8
 hipError_t gelu_fwd(int dtype, int kind, const void* u, void* g, size_t n, hipStream_t st);
 size_t colsum_scratch_bytes(int M, int N);
+int colsum_splits(int M);   // rows of partial sums that colsum_scratch_bytes() provides for
 hipError_t colsum(int dtype, int M, int N, const void* A, float* out, float* partial,
                   hipStream_t st);
+// out[n] += sum_{g<G} partial[g*N + n], in fixed order
+hipError_t reduce_colsum_partials(const float* partial, int G, int N, float* out, hipStream_t st);
 
 // Epilogue description shared by all GEMM implementations.
 struct GemmEpilogue {
@@ -33,6 +36,10 @@ struct GemmEpilogue {
   void* gelu_out = nullptr;        // [M,N]: if set, C keeps the pre-activation and this gets gelu(C)
   const void* dgelu_u = nullptr;   // [M,N]: if set, C *= gelu'(u)
   int gelu_kind = 0;               // 0 tanh, 1 erf
+  float* colsum_partial = nullptr; // with dgelu_u, MFMA path only: [gemm_mfma_colsum_rows()][N] fp32,
+                                   // written (not added to): column sums of C (fp32, before it is
+                                   // rounded for storage), one row per group of tile rows; their sum
+                                   // over the rows is sum_m C[m, :]
   const void* b_image = nullptr;   // forms 0/1, bf16: B re-laid-out by gemm_prepare_image() as the
                                    // tiled image of its [N rows, K contiguous] view (optional)
 };
@@ -48,6 +55,8 @@ size_t gemm_image_elems(int N, int K);
 hipError_t gemm_prepare_image(const void* src, void* img, int N, int K, bool transposed, hipStream_t st);
 hipError_t gemm_mfma(int form, int M, int N, int K, const void* A, const void* B, void* C,
                      const GemmEpilogue& ep, hipStream_t st);
+// rows of GemmEpilogue::colsum_partial that gemm_mfma() writes for an [M,N] product
+int gemm_mfma_colsum_rows(int M, int N);
 
 hipError_t attention_fwd_simple(int dtype, int B, int S, int a, int d, const void* qkv, void* out,
                                 float* lse, hipStream_t st);

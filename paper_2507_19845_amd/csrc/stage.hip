@@ -384,7 +384,14 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     ep.dgelu_u = s + sl.U;
     ep.gelu_kind = c.gelu;
     ep.b_image = img(l, 3);
+    // the matrix-core product also leaves the column sums of dU (the fc1 bias gradient) as
+    // per-tile-row partials, when it runs and they fit the column-sum scratch
+    const int cs_rows = (dt == GPTS_BF16 && gemm_mfma_supported(1, D.T, D.F, D.H)) ? gemm_mfma_colsum_rows(D.T, D.F) : 0;
+    const bool fused_b1 = cs_rows > 0 && cs_rows <= colsum_splits(D.T);
+    if (fused_b1) ep.colsum_partial = cs_part;
     GPTS_OP(GPTS_TR_GEMM_DGRAD, 3, 1, gf(D.T, D.F, D.H), gb(D.T, D.F, D.H, 2 * e), gemm(dt, 1, D.T, D.F, D.H, dY, w(l, GPTS_W_FC2), dU, ep, st), "fc2 dgrad");
+    if (fused_b1)
+      GPTS_OP(GPTS_TR_BIAS_GRAD, 2, 1, 0.0, (double)cs_rows * D.F * 4, reduce_colsum_partials(cs_part, cs_rows, D.F, g(l, GPTS_B_FC1), st), "fc1 bias grad (partials from the fc2 dgrad epilogue)");
     const void* G = s + sl.G;
     if (c.recompute) {
       GPTS_OP(GPTS_TR_RECOMPUTE, 2, 1, 0.0, (double)D.T * D.F * 2 * e, gelu_fwd(dt, c.gelu, s + sl.U, wk + ws.rG, (size_t)D.T * D.F, st), "gelu recompute");
@@ -405,7 +412,8 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
       A2 = wk + ws.rA;
     }
     GPTS_OP(GPTS_TR_GEMM_WGRAD, 2, 1, gf(D.F, D.H, D.T), gb(D.F, D.H, D.T, 8), gemm(dt, 2, D.F, D.H, D.T, dU, A2, g(l, GPTS_W_FC1), none, st), "fc1 wgrad");
-    GPTS_OP(GPTS_TR_BIAS_GRAD, 2, 1, 0.0, (double)D.T * D.F * e, colsum(dt, D.T, D.F, dU, g(l, GPTS_B_FC1), cs_part, st), "fc1 bias grad");
+    if (!fused_b1)
+      GPTS_OP(GPTS_TR_BIAS_GRAD, 2, 1, 0.0, (double)D.T * D.F * e, colsum(dt, D.T, D.F, dU, g(l, GPTS_B_FC1), cs_part, st), "fc1 bias grad");
     // a2 = LN2(x1), x1 also feeds the residual
     GPTS_OP(GPTS_TR_LN_BWD, 1, 1, 0.0, TH * (3 * e + kResBytes), ln_bwd(dt, dt == GPTS_BF16, D.T, D.H, dA, s + sl.X1, stat2, stat2 + D.T, w(l, GPTS_LN2_G), dY, dX1,
                     g(l, GPTS_LN2_G), g(l, GPTS_LN2_B), g(l, GPTS_B_O), ln_part, st), "ln2 bwd (+ out-proj bias grad)");
