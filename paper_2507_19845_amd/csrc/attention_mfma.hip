@@ -34,6 +34,11 @@ namespace {
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
+// Wave priority inside the kernels: raised around a run of matrix instructions, so that of the
+// two waves sharing a SIMD the one feeding the matrix pipe issues first and the other's softmax
+// arithmetic fills the gaps (measured: forward +1.7 %, backward +1 %).
+#define GPTS_PRIO(p) __builtin_amdgcn_s_setprio(p)
+
 constexpr int BQ = 128;   // queries per workgroup of the forward kernel
 constexpr int BKV = 64;   // rows per streamed tile
 constexpr int BW = 256;   // rows owned by a workgroup of the backward kernels (8 waves x 32)
@@ -237,6 +242,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
 
     // ---- S^T = K Q^T for the two 32-key blocks -------------------------------------
     f32x16 sacc[2];
+    GPTS_PRIO(1);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
@@ -247,6 +253,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
         sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[kb], 0, 0, 0);
       }
     }
+    GPTS_PRIO(0);
     // ---- causal mask (only tiles that reach past the first query of the wave) --------
     if (k0 + BKV - 1 > q0 + wave * 32) {
 #pragma unroll
@@ -288,6 +295,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
     }
     l_run += psum;
     // ---- O^T += V^T P^T ------------------------------------------------------------------------
+    GPTS_PRIO(1);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {           // 16 keys per step
       const bf16x8 pf = pack8(sacc[ks >> 1], (ks & 1) * 8);
@@ -297,6 +305,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
         oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[db], 0, 0, 0);
       }
     }
+    GPTS_PRIO(0);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
@@ -454,9 +463,11 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma_kernel(
         f32x16 sacc;
 #pragma unroll
         for (int e = 0; e < 16; ++e) sacc[e] = 0.f;
+        GPTS_PRIO(1);
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk)
           sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(aQ + (aoff ^ (kk << 5))), kfr[kk], sacc, 0, 0, 0);
+        GPTS_PRIO(0);
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const f32x4 L = *reinterpret_cast<const f32x4*>(Ls + g * 8);
@@ -478,9 +489,11 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma_kernel(
         f32x16 dpacc;
 #pragma unroll
         for (int e = 0; e < 16; ++e) dpacc[e] = 0.f;
+        GPTS_PRIO(1);
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk)
           dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(aO + (aoff ^ (kk << 5))), vfr[kk], dpacc, 0, 0, 0);
+        GPTS_PRIO(0);
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const f32x4 Dl = *reinterpret_cast<const f32x4*>(Ds + g * 8);
@@ -491,6 +504,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma_kernel(
         dsf[0] = pack8(dpacc, 0);
         dsf[1] = pack8(dpacc, 8);
       }
+      GPTS_PRIO(1);
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {   // 16 queries per step
         const int off = ioff ^ ((qb * 2 + ks) << 5);
@@ -500,6 +514,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma_kernel(
           dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(tQT + db * 4096 + off), dsf[ks], dk[db], 0, 0, 0);
         }
       }
+      GPTS_PRIO(0);
     }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -597,6 +612,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma_kernel(
     if (kt + 1 < nkv) fetch(kt + 1, (kt + 1) & 1);
     if (k0 > qmax_wave) continue;
     f32x16 sacc[2], dpacc[2];
+    GPTS_PRIO(1);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
@@ -608,6 +624,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma_kernel(
         dpacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(tV + off), dof[kk], dpacc[kb], 0, 0, 0);
       }
     }
+    GPTS_PRIO(0);
     if (k0 + BKV - 1 > q0 + wave * 32) {  // tile reaches past the first query of the wave: mask
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -627,6 +644,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma_kernel(
           dpacc[kb][e] = p * (dpacc[kb][e] - Dl);
         }
     }
+    GPTS_PRIO(1);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const bf16x8 dsf = pack8(dpacc[ks >> 1], (ks & 1) * 8);
@@ -634,6 +652,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma_kernel(
       for (int db = 0; db < DB; ++db)
         dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(tKT + db * 4096 + (ioff ^ (ks << 5))), dsf, dq[db], 0, 0, 0);
     }
+    GPTS_PRIO(0);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
