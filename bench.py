@@ -25,8 +25,8 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # passes (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, averaged over the 768 launches of a step; the
 # summary under profiles/ has the commands and the per-kernel figures).  Only reported while
 # the kernel source is the one the counters were taken on.
-GEMM_TRAFFIC = {"workload": "decoupled_bf16", "bytes_per_launch": 784.0 * 2**20,
-                "source_sha256_16": "529df1122ac23b76"}
+GEMM_TRAFFIC = {"workload": "decoupled_bf16", "bytes_per_launch": 784.2 * 2**20,
+                "source_sha256_16": "11be058bc68e9db4"}
 PEAK_FP32_TFLOPS = 157.3    # MI355X fp32 vector
 DEFAULT_WORKLOAD = "decoupled_bf16"
 
