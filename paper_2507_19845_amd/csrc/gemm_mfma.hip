@@ -260,85 +260,112 @@ __device__ __forceinline__ void gemm_epilogue(StageWriter&& write_pass, const Mf
       for (int e = 0; e < 4; ++e) bias_v[e] = (float)b[e];
     }
   }
-  static_for<WM / RP>([&](auto pass_c) {
-    constexpr int pass = decltype(pass_c)::value;
-    write_pass(pass_c, std::integral_constant<int, RP>{}, stg);
-    // LDS operations of one wave complete in order: no wait is needed between the
-    // writes above and the reads below, only that the compiler keeps their order
-    asm volatile("" ::: "memory");
-    // UB rows at a time: all loads of a batch are issued before the first is used
-    constexpr int UB = 8;
-    static_assert((RP / RPI) % UB == 0, "row batches");
-    for (int it0 = 0; it0 < RP / RPI; it0 += UB) {
-      f32x4 sv[UB], in32[UB];
-      bf16x4 in16[UB];
-      bool ok[UB];
-      size_t o[UB];
+  // The readback goes in batches of UB row instructions.  The global loads of a batch (the
+  // fp32 tile an accumulating product adds to, a residual, u for GeLU') depend on addresses
+  // only, so they are issued one batch ahead -- the first before the tile is even staged --
+  // and a batch's memory latency overlaps the staging and the arithmetic and stores of the
+  // batch before it.
+  constexpr int UB = 8, NPASS = WM / RP, BPP = RP / RPI / UB, NBATCH = NPASS * BPP;
+  static_assert((RP / RPI) % UB == 0, "row batches");
+  constexpr bool HAS_LOADS = EPI == EPI_ACCUM || RES32 || DGELU || EPI == EPI_BIAS_RES;
+  struct Batch {
+    f32x4 in32[UB];
+    bf16x4 in16[UB];
+    bool ok[UB];
+    size_t o[UB];
+  } bt[2];
+  auto issue = [&](auto idx_c) {
+    constexpr int idx = decltype(idx_c)::value, pass = idx / BPP, it0 = (idx % BPP) * UB;
+    Batch& t = bt[idx & 1];
 #pragma unroll
-      for (int u = 0; u < UB; ++u) {
-        const int row = (it0 + u) * RPI + rd_row;
-        const int m = m0 + wm * WM + pass * RP + row;
-        sv[u] = *reinterpret_cast<const f32x4*>(stg + row * WN + ((rd_chunk ^ (row & (CW - 1))) * 4));
-        ok[u] = m < a.M && n_ok;
-        o[u] = ok[u] ? (size_t)m * a.N + n : 0;  // element 0 is always a valid address
-        if constexpr (EPI == EPI_ACCUM) in32[u] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(a.C) + o[u]);
-        if constexpr (RES32) in32[u] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(a.residual) + o[u]);
-        if constexpr (DGELU) in16[u] = *reinterpret_cast<const bf16x4*>(a.dgelu_u + o[u]);
-        if constexpr (EPI == EPI_BIAS_RES) in16[u] = *reinterpret_cast<const bf16x4*>(static_cast<const bf16*>(a.residual) + o[u]);
-      }
+    for (int u = 0; u < UB; ++u) {
+      const int row = (it0 + u) * RPI + rd_row;
+      const int m = m0 + wm * WM + pass * RP + row;
+      t.ok[u] = m < a.M && n_ok;
+      t.o[u] = t.ok[u] ? (size_t)m * a.N + n : 0;  // element 0 is always a valid address
+      if constexpr (EPI == EPI_ACCUM) t.in32[u] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(a.C) + t.o[u]);
+      if constexpr (RES32) t.in32[u] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(a.residual) + t.o[u]);
+      if constexpr (DGELU) t.in16[u] = *reinterpret_cast<const bf16x4*>(a.dgelu_u + t.o[u]);
+      if constexpr (EPI == EPI_BIAS_RES) t.in16[u] = *reinterpret_cast<const bf16x4*>(static_cast<const bf16*>(a.residual) + t.o[u]);
+    }
+  };
+  auto finish = [&](auto idx_c) {
+    constexpr int idx = decltype(idx_c)::value, it0 = (idx % BPP) * UB;
+    Batch& t = bt[idx & 1];
+    f32x4 sv[UB];
 #pragma unroll
-      for (int u = 0; u < UB; ++u) {
-        if (!ok[u]) continue;
-        float v[4];
+    for (int u = 0; u < UB; ++u) {
+      const int row = (it0 + u) * RPI + rd_row;
+      sv[u] = *reinterpret_cast<const f32x4*>(stg + row * WN + ((rd_chunk ^ (row & (CW - 1))) * 4));
+    }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = sv[u][e] + bias_v[e];
-        if constexpr (EPI == EPI_ACCUM) {
-          f32x4 c;
+    for (int u = 0; u < UB; ++u) {
+      if (!t.ok[u]) continue;
+      float v[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) c[e] = in32[u][e] + v[e];
-          *reinterpret_cast<f32x4*>(static_cast<float*>(a.C) + o[u]) = c;
-        } else if constexpr (GELU) {
-          bf16x4 uq, gq;
+      for (int e = 0; e < 4; ++e) v[e] = sv[u][e] + bias_v[e];
+      if constexpr (EPI == EPI_ACCUM) {
+        f32x4 c;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            uq[e] = (bf16)v[e];
-            // g is the GeLU of u AS STORED, so that a backward pass that recomputes g from
-            // the stashed u gets the same bits
-            gq[e] = (bf16)gelu_f<EPI == EPI_GELU_TANH ? 0 : 1>((float)uq[e]);
-          }
-          *reinterpret_cast<bf16x4*>(static_cast<bf16*>(a.C) + o[u]) = uq;
-          *reinterpret_cast<bf16x4*>(a.gelu_out + o[u]) = gq;
+        for (int e = 0; e < 4; ++e) c[e] = t.in32[u][e] + v[e];
+        *reinterpret_cast<f32x4*>(static_cast<float*>(a.C) + t.o[u]) = c;
+      } else if constexpr (GELU) {
+        bf16x4 uq, gq;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          uq[e] = (bf16)v[e];
+          // g is the GeLU of u AS STORED, so that a backward pass that recomputes g from
+          // the stashed u gets the same bits
+          gq[e] = (bf16)gelu_f<EPI == EPI_GELU_TANH ? 0 : 1>((float)uq[e]);
+        }
+        *reinterpret_cast<bf16x4*>(static_cast<bf16*>(a.C) + t.o[u]) = uq;
+        *reinterpret_cast<bf16x4*>(a.gelu_out + t.o[u]) = gq;
+      } else {
+        if constexpr (DGELU) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f<EPI == EPI_DGELU_TANH ? 0 : 1>((float)t.in16[u][e]);
+        }
+        if constexpr (EPI == EPI_BIAS_RES) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += (float)t.in16[u][e];
+        }
+        if constexpr (RES32) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += t.in32[u][e];
+        }
+        if constexpr (EPI == EPI_BIAS_RES32_OUT32) {
+          f32x4 out;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) out[e] = v[e];
+          *reinterpret_cast<f32x4*>(static_cast<float*>(a.C) + t.o[u]) = out;
         } else {
+          bf16x4 out;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) out[e] = (bf16)v[e];
+          *reinterpret_cast<bf16x4*>(static_cast<bf16*>(a.C) + t.o[u]) = out;
           if constexpr (DGELU) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f<EPI == EPI_DGELU_TANH ? 0 : 1>((float)in16[u][e]);
-          }
-          if constexpr (EPI == EPI_BIAS_RES) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += (float)in16[u][e];
-          }
-          if constexpr (RES32) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += in32[u][e];
-          }
-          if constexpr (EPI == EPI_BIAS_RES32_OUT32) {
-            f32x4 out;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) out[e] = v[e];
-            *reinterpret_cast<f32x4*>(static_cast<float*>(a.C) + o[u]) = out;
-          } else {
-            bf16x4 out;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) out[e] = (bf16)v[e];
-            *reinterpret_cast<bf16x4*>(static_cast<bf16*>(a.C) + o[u]) = out;
-            if constexpr (DGELU) {
-#pragma unroll
-              for (int e = 0; e < 4; ++e) cs[e] += v[e];
-            }
+            for (int e = 0; e < 4; ++e) cs[e] += v[e];
           }
         }
       }
     }
+  };
+  if constexpr (HAS_LOADS) issue(std::integral_constant<int, 0>{});
+  static_for<NBATCH>([&](auto idx_c) {
+    constexpr int idx = decltype(idx_c)::value;
+    if constexpr (idx % BPP == 0) {
+      write_pass(std::integral_constant<int, idx / BPP>{}, std::integral_constant<int, RP>{}, stg);
+      // LDS operations of one wave complete in order: no wait is needed between the
+      // writes above and the reads below, only that the compiler keeps their order
+      asm volatile("" ::: "memory");
+    }
+    if constexpr (HAS_LOADS) {
+      if constexpr (idx + 1 < NBATCH) issue(std::integral_constant<int, idx + 1>{});
+    } else {
+      issue(idx_c);
+    }
+    finish(idx_c);
   });
   if constexpr (DGELU) {
     if (a.colsum) {
