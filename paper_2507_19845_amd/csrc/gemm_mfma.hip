@@ -756,8 +756,10 @@ __global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
       static_for<16>([&](auto g_c) {
         constexpr int g = decltype(g_c)::value;
         // four matrix instructions: block row g/2, block columns 4*(g%2) .. +3
+        // (block columns run forwards in even block rows and backwards in odd ones, so that
+        // exactly one operand changes from one instruction to the next)
         static_for<4>([&](auto q_c) {
-          constexpr int ib = g / 2, jb = 4 * (g % 2) + decltype(q_c)::value;
+          constexpr int ib = g / 2, j0 = 4 * (g % 2) + decltype(q_c)::value, jb = (ib & 1) ? NB - 1 - j0 : j0;
           mfma16_at<4 * (NB * ib + jb)>(fb[cur][jb], fa[cur][ib]);
         });
         __builtin_amdgcn_sched_barrier(0);
