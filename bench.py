@@ -26,7 +26,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # summary under profiles/ has the commands and the per-kernel figures).  Only reported while
 # the kernel source is the one the counters were taken on.
 GEMM_TRAFFIC = {"workload": "decoupled_bf16", "bytes_per_launch": 784.2 * 2**20,
-                "source_sha256_16": "370223dd7a06f7d5"}
+                "source_sha256_16": "becfdd5c80417f46"}
 PEAK_FP32_TFLOPS = 157.3    # MI355X fp32 vector
 DEFAULT_WORKLOAD = "decoupled_bf16"
 
