@@ -83,6 +83,22 @@ typedef struct {
                         backward phase recomputes them from the stashed x, x1
                         (with the stashed statistics' inputs) and u.  One third less
                         stash, about 3 % more backward time, identical results.  */
+  int32_t fwd_fp16;  /* bf16 stages only.  0: forward activations are bf16.  1: the forward
+                        phase keeps the activations that branch off the residual stream
+                        (both LayerNorm outputs, qkv, the attention probabilities and
+                        output, u, g) in fp16 -- 11 significand bits instead of 8 at the
+                        same size -- and runs its products on the matrix cores' f16
+                        instructions against fp16 images of the weights, still with fp32
+                        accumulation; x, y, weights, gradients and every backward product
+                        stay bf16 (gradients need bf16's range), the backward phase reading
+                        bf16 copies of the stashed fp16 tensors and rebuilding the
+                        LayerNorm and GeLU outputs as with `recompute`.  For stages whose
+                        attention logits are large enough that bf16 rounding of the forward
+                        activations, amplified by the softmax, shows in the gradients.
+                        Needs p->prepared (built by gpt_stage_prepare() with the SAME cfg: the
+                        forward images then hold fp16) and hidden, attention width and ffn
+                        multiples of 128, head_dim 64 or 128.  Forward activations are bounded
+                        by LayerNorm and the softmax; values beyond fp16's range saturate. */
 } gpt_stage_cfg;
 
 typedef struct {
@@ -107,7 +123,7 @@ typedef struct {
 
 /* GPTS_OK if the kernels support cfg: L,B,S >= 1; head_dim in {32,64,128};
  * H, P, F multiples of 8; H <= 16384; dtype/gelu valid.  bf16 additionally
- * needs T = B*S, H, P, F multiples of 64 (MFMA tile granularity). */
+ * needs T = B*S, H, P, F multiples of 64 (MFMA tile granularity); fwd_fp16 see cfg. */
 int gpt_stage_validate(const gpt_stage_cfg* cfg);
 
 size_t gpt_stage_param_count(const gpt_stage_cfg* cfg);  /* elements, all layers */
@@ -190,7 +206,7 @@ int gpt_stage_fwd_bwd(const gpt_stage_params* p, const void* x, const void* dy,
  * run concurrently on the host.  Records beyond capacity are dropped and counted. */
 enum {
   GPTS_TR_LN_FWD = 0, GPTS_TR_GEMM_FWD, GPTS_TR_ATTN_FWD, GPTS_TR_GEMM_DGRAD, GPTS_TR_GEMM_WGRAD,
-  GPTS_TR_BIAS_GRAD, GPTS_TR_LN_BWD, GPTS_TR_ATTN_BWD, GPTS_TR_RECOMPUTE, GPTS_TR_N_OPS
+  GPTS_TR_BIAS_GRAD, GPTS_TR_LN_BWD, GPTS_TR_ATTN_BWD, GPTS_TR_RECOMPUTE, GPTS_TR_CONVERT, GPTS_TR_N_OPS
 };
 typedef struct {
   int32_t op;       /* GPTS_TR_*                                                     */

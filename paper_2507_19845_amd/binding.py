@@ -46,7 +46,7 @@ class gpt_stage_cfg(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("ffn", C.c_int32), ("seq", C.c_int32),
                 ("batch", C.c_int32), ("dtype", C.c_int32), ("gelu", C.c_int32),
-                ("ln_eps", C.c_float), ("recompute", C.c_int32)]
+                ("ln_eps", C.c_float), ("recompute", C.c_int32), ("fwd_fp16", C.c_int32)]
 
 
 class gpt_stage_params(C.Structure):
@@ -188,7 +188,8 @@ def make_cfg(s: synth.StageShape) -> gpt_stage_cfg:
                          ffn=s.ffn, seq=s.seq, batch=s.batch,
                          dtype=GPTS_BF16 if s.dtype == "bf16" else GPTS_FP32,
                          gelu=GPTS_GELU_ERF if s.gelu == "erf" else GPTS_GELU_TANH,
-                         ln_eps=s.ln_eps, recompute=1 if s.recompute else 0)
+                         ln_eps=s.ln_eps, recompute=1 if s.recompute else 0,
+                         fwd_fp16=1 if s.fwd_fp16 else 0)
 
 
 # ---- host-side queries --------------------------------------------------------
@@ -231,70 +232,44 @@ def gpt_stage_strerror(code: int) -> str:
 
 
 # ---- the stage calls -----------------------------------------------------------
-_active_trace: Optional[int] = None   # tracer handle attached to every stage call made below
-
-
-def set_trace(trace: Optional[int]) -> None:
-    """Attach a tracer handle (or None) to all subsequent stage calls of this module."""
-    global _active_trace
-    _active_trace = trace
-
-
-_prepared: Dict[int, torch.Tensor] = {}   # weights data_ptr -> prepared buffer to pass along
-
-
-def use_prepared(weights: torch.Tensor, prepared: Optional[torch.Tensor]) -> None:
-    """Pass `prepared` (filled by gpt_stage_prepare for these weights) with every later
-    stage call on `weights`; None stops doing so."""
-    if prepared is None:
-        _prepared.pop(weights.data_ptr(), None)
-    else:
-        _prepared[weights.data_ptr()] = prepared
-
-
-def _params(cfg, weights, workspace) -> gpt_stage_params:
-    prep = _prepared.get(weights.data_ptr()) if weights is not None else None
+def make_params(cfg, weights, workspace, prepared=None, trace: Optional[int] = None) -> gpt_stage_params:
+    """The C struct gpt_stage_params from tensors (pointers only: the caller keeps the
+    tensors alive for as long as the struct is used)."""
     return gpt_stage_params(cfg=cfg, weights=_ptr(weights), workspace=_ptr(workspace),
-                            prepared=_ptr(prep), trace=_active_trace)
+                            prepared=_ptr(prepared), trace=trace)
 
 
 def gpt_stage_prepared_bytes(cfg) -> int:
     return lib().gpt_stage_prepared_bytes(C.byref(cfg))
 
 
-def gpt_stage_prepare(cfg, weights, prepared, stream=None) -> None:
-    p = gpt_stage_params(cfg=cfg, weights=_ptr(weights), workspace=None, prepared=None, trace=None)
+def gpt_stage_prepare(p: gpt_stage_params, prepared, stream=None) -> None:
     _check(lib().gpt_stage_prepare(C.byref(p), _ptr(prepared), _stream(stream)))
 
 
-def gpt_stage_fwd(cfg, weights, workspace, x, act_stash, y, stream=None) -> None:
-    p = _params(cfg, weights, workspace)
+def gpt_stage_fwd(p: gpt_stage_params, x, act_stash, y, stream=None) -> None:
     _check(lib().gpt_stage_fwd(C.byref(p), _ptr(x), _ptr(act_stash), _ptr(y), _stream(stream)))
 
 
-def gpt_stage_bwd(cfg, weights, workspace, act_stash, dy, dx, dparams, stream=None) -> None:
-    p = _params(cfg, weights, workspace)
+def gpt_stage_bwd(p: gpt_stage_params, act_stash, dy, dx, dparams, stream=None) -> None:
     _check(lib().gpt_stage_bwd(C.byref(p), _ptr(act_stash), _ptr(dy), _ptr(dx), _ptr(dparams),
                                _stream(stream)))
 
 
-def gpt_stage_fwd_only(cfg, weights, workspace, x, act_stash, y, stream=None,
+def gpt_stage_fwd_only(p: gpt_stage_params, x, act_stash, y, stream=None,
                        done_event: Optional[torch.cuda.Event] = None) -> None:
-    p = _params(cfg, weights, workspace)
     ev = _event(done_event)
     _check(lib().gpt_stage_fwd_only(C.byref(p), _ptr(x), _ptr(act_stash), _ptr(y), _stream(stream), ev))
 
 
-def gpt_stage_bwd_only(cfg, weights, workspace, act_stash, dy, dx, dparams, stream=None,
+def gpt_stage_bwd_only(p: gpt_stage_params, act_stash, dy, dx, dparams, stream=None,
                        wait_event: Optional[torch.cuda.Event] = None) -> None:
-    p = _params(cfg, weights, workspace)
     ev = _event(wait_event)
     _check(lib().gpt_stage_bwd_only(C.byref(p), _ptr(act_stash), _ptr(dy), _ptr(dx), _ptr(dparams),
                                     _stream(stream), ev))
 
 
-def gpt_stage_fwd_bwd(cfg, weights, workspace, x, dy, act_stash, y, dx, dparams, stream=None) -> None:
-    p = _params(cfg, weights, workspace)
+def gpt_stage_fwd_bwd(p: gpt_stage_params, x, dy, act_stash, y, dx, dparams, stream=None) -> None:
     _check(lib().gpt_stage_fwd_bwd(C.byref(p), _ptr(x), _ptr(dy), _ptr(act_stash), _ptr(y), _ptr(dx),
                                    _ptr(dparams), _stream(stream)))
 
@@ -536,20 +511,28 @@ class StageBuffers:
                       for _ in range(n_stash)]
         wb = max(gpt_stage_workspace_bytes(self.cfg, 0), gpt_stage_workspace_bytes(self.cfg, 1), 256)
         self.workspace = torch.empty(wb, dtype=torch.uint8, device=device)
+        self.prepared: Optional[torch.Tensor] = None    # passed as params.prepared when set
+        self._prepared_buf: Optional[torch.Tensor] = None
+        self.trace: Optional[int] = None                # tracer handle passed as params.trace
+
+    def params(self) -> gpt_stage_params:
+        """gpt_stage_params for the stage calls: this object's weights and workspace, the
+        prepared weights if prepare() was called, and the tracer in self.trace (if any)."""
+        return make_params(self.cfg, self.weights, self.workspace, self.prepared, self.trace)
 
     def prepare(self, stream=None) -> None:
-        """(Re)build the prepared-weights buffer from the current weights and pass it
-        with every later stage call on these weights (bf16 stages only)."""
+        """(Re)build the prepared-weights buffer from the current weights; it is passed
+        with every later params() (bf16 stages only)."""
         nbytes = gpt_stage_prepared_bytes(self.cfg)
         if nbytes == 0:
             return
-        if getattr(self, "prepared", None) is None:
-            self.prepared = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
-        gpt_stage_prepare(self.cfg, self.weights, self.prepared, stream)
-        use_prepared(self.weights, self.prepared)
+        if self._prepared_buf is None:
+            self._prepared_buf = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        gpt_stage_prepare(make_params(self.cfg, self.weights, None), self._prepared_buf, stream)
+        self.prepared = self._prepared_buf
 
     def unprepare(self) -> None:
-        use_prepared(self.weights, None)
+        self.prepared = None
 
     def act(self) -> torch.Tensor:
         s = self.shape
@@ -561,6 +544,8 @@ class StageBuffers:
                 off, n = gpt_stage_param_offset(self.cfg, l, tid)
                 assert p[name].size == n, (name, p[name].shape, n)
                 self.weights[off:off + n].copy_(to_device(p[name].reshape(-1), self.shape.dtype, self.device))
+        if self.shape.fwd_fp16:
+            self.prepare()   # the fp16 forward products read the weights through their images
 
     def read_grads(self) -> List[Dict[str, np.ndarray]]:
         shapes = synth.param_shapes(self.shape)

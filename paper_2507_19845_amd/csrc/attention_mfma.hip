@@ -45,11 +45,28 @@ constexpr int BW = 256;   // rows owned by a workgroup of the backward kernels (
 
 __device__ __forceinline__ int swz16(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
-__device__ __forceinline__ bf16x8 pack8(const f32x16& v, int base) {
-  bf16x8 r;
+// Eight accumulator values rounded to 16 bits as the next product's operand.  All operand
+// registers are typed bf16x8; with F16 they hold fp16 bits (forward activations kept in fp16).
+template <bool F16 = false> __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int base) {
+  if constexpr (F16) {
+    f16x8 r;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) r[e] = (bf16)v[base + e];
-  return r;
+    for (int e = 0; e < 8; ++e) r[e] = (f16)v[base + e];
+    return __builtin_bit_cast(bf16x8, r);
+  } else {
+    bf16x8 r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = (bf16)v[base + e];
+    return r;
+  }
+}
+// acc += A (32 x 16) * B (16 x 32); F16: the operand registers hold fp16 values
+template <bool F16 = false>
+__device__ __forceinline__ f32x16 mma32(const bf16x8& a, const bf16x8& b, const f32x16& acc) {
+  if constexpr (F16)
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), acc, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
 }
 
 // Marks a register value as used.  The tiles travel by DMA instructions the compiler
@@ -177,7 +194,8 @@ __device__ __forceinline__ bf16x8 lds_frag(const char* p) { return *reinterpret_
 
 // ---- forward -----------------------------------------------------------------------------
 // grid (heads, batch, query tiles): the heaviest query tiles of all heads start first.
-template <int D>
+// F16: qkv, the V image, the probabilities and out are fp16 (same layouts, f16 instructions).
+template <int D, bool F16 = false>
 __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv,
                                                                const bf16* __restrict__ vt_img,
                                                                bf16* __restrict__ out,
@@ -250,7 +268,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
 #pragma unroll
       for (int kk = 0; kk < KSTEPS; ++kk) {
         const bf16x8 kf = lds_frag(tK + kb * 32 * ROWB + (koff ^ (kk << 5)));
-        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[kb], 0, 0, 0);
+        sacc[kb] = mma32<F16>(kf, qf[kk], sacc[kb]);
       }
     }
     GPTS_PRIO(0);
@@ -298,11 +316,11 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
     GPTS_PRIO(1);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {           // 16 keys per step
-      const bf16x8 pf = pack8(sacc[ks >> 1], (ks & 1) * 8);
+      const bf16x8 pf = pack8<F16>(sacc[ks >> 1], (ks & 1) * 8);
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
         const bf16x8 vf = lds_frag(tV + db * 4096 + (voff ^ (ks << 5)));
-        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[db], 0, 0, 0);
+        oacc[db] = mma32<F16>(vf, pf, oacc[db]);
       }
     }
     GPTS_PRIO(0);
@@ -318,10 +336,17 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        bf16x4 o;
+        if constexpr (F16) {
+          f16x4 o;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = (bf16)(oacc[db][g * 4 + e] * inv);
-        *reinterpret_cast<bf16x4*>(orow + db * 32 + g * 8 + h * 4) = o;
+          for (int e = 0; e < 4; ++e) o[e] = sat_f16(oacc[db][g * 4 + e] * inv);
+          *reinterpret_cast<f16x4*>(orow + db * 32 + g * 8 + h * 4) = o;
+        } else {
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = (bf16)(oacc[db][g * 4 + e] * inv);
+          *reinterpret_cast<bf16x4*>(orow + db * 32 + g * 8 + h * 4) = o;
+        }
       }
     if (h == 0) lse[((size_t)b * a + n) * S + qrow] = (m_run * c + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
   }
@@ -329,7 +354,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
 
 
 // delta[b,n,i] = sum_d dO[b,i,n*D+d] * O[b,i,n*D+d]; one 16-lane group per (row, head).
-template <int D>
+// O16: out holds fp16 values.
+template <int D, bool O16 = false>
 __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16* __restrict__ out,
                                                          const bf16* __restrict__ dout,
                                                          float* __restrict__ delta, int S, int a,
@@ -346,7 +372,8 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16* __restrict_
       const bf16x4 o = *reinterpret_cast<const bf16x4*>(out + off + e);
       const bf16x4 g = *reinterpret_cast<const bf16x4*>(dout + off + e);
 #pragma unroll
-      for (int k = 0; k < 4; ++k) acc = fmaf((float)o[k], (float)g[k], acc);
+      for (int k = 0; k < 4; ++k)
+        acc = fmaf(O16 ? (float)__builtin_bit_cast(f16x4, o)[k] : (float)o[k], (float)g[k], acc);
     }
   }
 #pragma unroll
@@ -369,9 +396,12 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16* __restrict_
 //   dK^T[d][k] += Q^T dS   (A = fragment of the Q image,  B = dS)
 // so a lane owns one key column and nothing moves between lanes.
 // grid (heads, batch, key blocks): the key blocks with the most queries start first.
-template <int D>
+// F16S: the logits are recomputed from fp16 copies of Q and K (qk16, laid out like qkv) with
+// the f16 instruction -- the operands the forward pass formed them from; everything else
+// (V, the images, dO) is bf16.  Without F16S qk16 == qkv.
+template <int D, bool F16S = false>
 __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma_kernel(
-    const bf16* __restrict__ qkv, const bf16* __restrict__ dout, const bf16* __restrict__ qt_img,
+    const bf16* __restrict__ qkv, const bf16* __restrict__ qk16, const bf16* __restrict__ dout, const bf16* __restrict__ qt_img,
     const bf16* __restrict__ dot_img, const float* __restrict__ lse, const float* __restrict__ delta,
     bf16* __restrict__ dqkv, int S, int a) {
   constexpr int KSTEPS = D / 16, DB = D / 32, ROWB = D * 2, TILE = BKV * ROWB;
@@ -385,6 +415,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma_kernel(
   const int P = a * D;
   const size_t ld = 3 * (size_t)P;
   const bf16* base = qkv + (size_t)b * S * ld + (size_t)n * D;
+  const bf16* base16 = qk16 + (size_t)b * S * ld + (size_t)n * D;
   const bf16* dobase = dout + (size_t)b * S * P + (size_t)n * D;
   const int ntile = (S + BKV - 1) / BKV;
   const size_t img_off = ((size_t)b * a + n) * ntile * (size_t)(D * BKV);
@@ -402,7 +433,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma_kernel(
   bf16x8 kfr[KSTEPS], vfr[KSTEPS];
 #pragma unroll
   for (int kk = 0; kk < KSTEPS; ++kk) {
-    kfr[kk] = *reinterpret_cast<const bf16x8*>(base + (size_t)kclamp * ld + P + kk * 16 + h * 8);
+    kfr[kk] = *reinterpret_cast<const bf16x8*>(base16 + (size_t)kclamp * ld + P + kk * 16 + h * 8);
     vfr[kk] = *reinterpret_cast<const bf16x8*>(base + (size_t)kclamp * ld + 2 * P + kk * 16 + h * 8);
   }
 #pragma unroll
@@ -427,7 +458,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma_kernel(
     int lane = lane_id;
     asm volatile("" : "+v"(lane));
     char* t = lds + stage * 4 * TILE;
-    dma_tile<D, 8>(base, ld, qt * BKV, S, t, wave, lane);
+    dma_tile<D, 8>(base16, ld, qt * BKV, S, t, wave, lane);
     dma_tile<D, 8>(dobase, (size_t)P, qt * BKV, S, t + TILE, wave, lane);
     dma_image<D, 8>(qimg + (size_t)qt * (D * BKV), t + 2 * TILE, wave, lane);
     dma_image<D, 8>(doimg + (size_t)qt * (D * BKV), t + 3 * TILE, wave, lane);
@@ -466,7 +497,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma_kernel(
         GPTS_PRIO(1);
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk)
-          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(aQ + (aoff ^ (kk << 5))), kfr[kk], sacc, 0, 0, 0);
+          sacc = mma32<F16S>(lds_frag(aQ + (aoff ^ (kk << 5))), kfr[kk], sacc);
         GPTS_PRIO(0);
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
@@ -543,9 +574,9 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma_kernel(
 //   S^T = K Q^T,  dP^T = V dO^T  (A = K / V fragments from LDS, B = Q / dO in registers)
 //   dS^T = P^T (dP^T - delta_q),  dQ^T[d][q] += K^T dS^T (A = fragment of the K image).
 // grid (heads, batch, query blocks), heaviest first.
-template <int D>
+template <int D, bool F16S = false>
 __global__ __launch_bounds__(512) void attn_bwd_dq_mfma_kernel(
-    const bf16* __restrict__ qkv, const bf16* __restrict__ dout, const bf16* __restrict__ kt_img,
+    const bf16* __restrict__ qkv, const bf16* __restrict__ qk16, const bf16* __restrict__ dout, const bf16* __restrict__ kt_img,
     const float* __restrict__ lse, const float* __restrict__ delta, bf16* __restrict__ dqkv, int S, int a) {
   constexpr int KSTEPS = D / 16, DB = D / 32, ROWB = D * 2, TILE = BKV * ROWB;
   __shared__ __attribute__((aligned(1024))) char lds[6 * TILE];  // [stage][K | V | K image]
@@ -558,6 +589,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma_kernel(
   const int P = a * D;
   const size_t ld = 3 * (size_t)P;
   const bf16* base = qkv + (size_t)b * S * ld + (size_t)n * D;
+  const bf16* base16 = qk16 + (size_t)b * S * ld + (size_t)n * D;
   const int ntile = (S + BKV - 1) / BKV;
   const bf16* kimg = kt_img + ((size_t)b * a + n) * ntile * (size_t)(D * BKV);
   const int q0 = qt * BW;
@@ -570,7 +602,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma_kernel(
   bf16x8 qf[KSTEPS], dof[KSTEPS];
 #pragma unroll
   for (int kk = 0; kk < KSTEPS; ++kk) {
-    qf[kk] = *reinterpret_cast<const bf16x8*>(base + (size_t)qclamp * ld + kk * 16 + h * 8);
+    qf[kk] = *reinterpret_cast<const bf16x8*>(base16 + (size_t)qclamp * ld + kk * 16 + h * 8);
     dof[kk] = *reinterpret_cast<const bf16x8*>(dout + ((size_t)b * S + qclamp) * P + (size_t)n * D + kk * 16 + h * 8);
   }
   const float L2 = lse[((size_t)b * a + n) * S + qclamp] * 1.4426950408889634f;
@@ -597,7 +629,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma_kernel(
     int lane = lane_id;  // opaque: recompute the DMA offsets per tile rather than keep them
     asm volatile("" : "+v"(lane));
     char* t = lds + stage * 3 * TILE;
-    dma_tile<D, 8>(base + P, ld, kt * BKV, S, t, wave, lane);
+    dma_tile<D, 8>(base16 + P, ld, kt * BKV, S, t, wave, lane);
     dma_tile<D, 8>(base + 2 * P, ld, kt * BKV, S, t + TILE, wave, lane);
     dma_image<D, 8>(kimg + (size_t)kt * (D * BKV), t + 2 * TILE, wave, lane);
   };
@@ -620,7 +652,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma_kernel(
 #pragma unroll
       for (int kk = 0; kk < KSTEPS; ++kk) {
         const int off = kb * 32 * ROWB + (koff ^ (kk << 5));
-        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(tK + off), qf[kk], sacc[kb], 0, 0, 0);
+        sacc[kb] = mma32<F16S>(lds_frag(tK + off), qf[kk], sacc[kb]);
         dpacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(tV + off), dof[kk], dpacc[kb], 0, 0, 0);
       }
     }
@@ -684,6 +716,13 @@ void launch_timage(const TImageArgs& t, int B, int S, int a, hipStream_t st) {
 
 }  // namespace
 
+// The kernels address a tile row with a 32-bit byte offset from the (batch, head) base and
+// count (batch, row, head) triples in an int.
+bool attention_mfma_supported(int B, int S, int a, int d) {
+  return (d == 64 || d == 128) && B >= 1 && S >= 1 && a >= 1 && (size_t)S * 3 * a * d < (1ull << 31) &&
+         (size_t)B * S * a < (1ull << 27);
+}
+
 size_t attention_mfma_scratch_bytes(int B, int S, int a, int d, int phase) {
   const size_t img = align256(image_bytes(B, S, a, d));
   if (phase == 0) return img;                                     // V image
@@ -691,8 +730,8 @@ size_t attention_mfma_scratch_bytes(int B, int S, int a, int d, int phase) {
 }
 
 hipError_t attention_fwd_mfma(int B, int S, int a, int d, const void* qkv, void* out, float* lse,
-                              void* scratch, hipStream_t st) {
-  if (d != 64 && d != 128) return hipErrorInvalidValue;
+                              void* scratch, hipStream_t st, bool f16) {
+  if (!attention_mfma_supported(B, S, a, d)) return hipErrorInvalidValue;
   const int P = a * d;
   const bf16* q = (const bf16*)qkv;
   bf16* vimg = (bf16*)scratch;
@@ -702,20 +741,33 @@ hipError_t attention_fwd_mfma(int B, int S, int a, int d, const void* qkv, void*
   t.ld[0] = 3 * (size_t)P;
   t.dst[0] = vimg;
   dim3 g(a, B, (S + BQ - 1) / BQ), blk(256);
+  // the image kernel only moves 16-bit values, so it serves fp16 as it serves bf16
   if (d == 128) {
     launch_timage<128>(t, B, S, a, st);
-    hipLaunchKernelGGL(attn_fwd_mfma_kernel<128>, g, blk, 0, st, q, vimg, (bf16*)out, lse, S, a);
+    if (f16) hipLaunchKernelGGL((attn_fwd_mfma_kernel<128, true>), g, blk, 0, st, q, vimg, (bf16*)out, lse, S, a);
+    else hipLaunchKernelGGL((attn_fwd_mfma_kernel<128, false>), g, blk, 0, st, q, vimg, (bf16*)out, lse, S, a);
   } else {
     launch_timage<64>(t, B, S, a, st);
-    hipLaunchKernelGGL(attn_fwd_mfma_kernel<64>, g, blk, 0, st, q, vimg, (bf16*)out, lse, S, a);
+    if (f16) hipLaunchKernelGGL((attn_fwd_mfma_kernel<64, true>), g, blk, 0, st, q, vimg, (bf16*)out, lse, S, a);
+    else hipLaunchKernelGGL((attn_fwd_mfma_kernel<64, false>), g, blk, 0, st, q, vimg, (bf16*)out, lse, S, a);
   }
   return hipGetLastError();
 }
 
+template <int D, bool F16>
+static void launch_bwd(dim3 gd, dim3 gw, const TImageArgs& t, int B, int S, int a, int total, const bf16* q,
+                const bf16* q16, const bf16* o, const bf16* g, bf16* qimg, bf16* kimg, bf16* doimg,
+                const float* lse, float* delta, bf16* dq, hipStream_t st) {
+  hipLaunchKernelGGL((attn_delta_kernel<D, F16>), gd, dim3(256), 0, st, o, g, delta, S, a, total);
+  launch_timage<D>(t, B, S, a, st);
+  hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<D, F16>), gw, dim3(512), 0, st, q, q16, g, qimg, doimg, lse, delta, dq, S, a);
+  hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, F16>), gw, dim3(512), 0, st, q, q16, g, kimg, lse, delta, dq, S, a);
+}
+
 hipError_t attention_bwd_mfma(int B, int S, int a, int d, const void* qkv, const void* out,
                               const float* lse, const void* dout, void* dqkv, void* scratch,
-                              hipStream_t st) {
-  if (d != 64 && d != 128) return hipErrorInvalidValue;
+                              hipStream_t st, const void* qkv_f16) {
+  if (!attention_mfma_supported(B, S, a, d)) return hipErrorInvalidValue;
   const int total = B * S * a, P = a * d;
   const size_t img = align256(image_bytes(B, S, a, d));
   char* sc = static_cast<char*>(scratch);
@@ -732,17 +784,14 @@ hipError_t attention_bwd_mfma(int B, int S, int a, int d, const void* qkv, const
   t.src[0] = q;         t.ld[0] = 3 * (size_t)P; t.dst[0] = qimg;
   t.src[1] = q + P;     t.ld[1] = 3 * (size_t)P; t.dst[1] = kimg;
   t.src[2] = g;         t.ld[2] = (size_t)P;     t.dst[2] = doimg;
-  dim3 gd((total * 16 + 255) / 256), gw(a, B, (S + BW - 1) / BW);
+  dim3 gd((unsigned)(((size_t)total * 16 + 255) / 256)), gw(a, B, (S + BW - 1) / BW);
+  const bf16* q16 = (const bf16*)qkv_f16;
   if (d == 128) {
-    hipLaunchKernelGGL(attn_delta_kernel<128>, gd, dim3(256), 0, st, o, g, delta, S, a, total);
-    launch_timage<128>(t, B, S, a, st);
-    hipLaunchKernelGGL(attn_bwd_dkv_mfma_kernel<128>, gw, dim3(512), 0, st, q, g, qimg, doimg, lse, delta, dq, S, a);
-    hipLaunchKernelGGL(attn_bwd_dq_mfma_kernel<128>, gw, dim3(512), 0, st, q, g, kimg, lse, delta, dq, S, a);
+    if (q16) launch_bwd<128, true>(gd, gw, t, B, S, a, total, q, q16, o, g, qimg, kimg, doimg, lse, delta, dq, st);
+    else launch_bwd<128, false>(gd, gw, t, B, S, a, total, q, q, o, g, qimg, kimg, doimg, lse, delta, dq, st);
   } else {
-    hipLaunchKernelGGL(attn_delta_kernel<64>, gd, dim3(256), 0, st, o, g, delta, S, a, total);
-    launch_timage<64>(t, B, S, a, st);
-    hipLaunchKernelGGL(attn_bwd_dkv_mfma_kernel<64>, gw, dim3(512), 0, st, q, g, qimg, doimg, lse, delta, dq, S, a);
-    hipLaunchKernelGGL(attn_bwd_dq_mfma_kernel<64>, gw, dim3(512), 0, st, q, g, kimg, lse, delta, dq, S, a);
+    if (q16) launch_bwd<64, true>(gd, gw, t, B, S, a, total, q, q16, o, g, qimg, kimg, doimg, lse, delta, dq, st);
+    else launch_bwd<64, false>(gd, gw, t, B, S, a, total, q, q, o, g, qimg, kimg, doimg, lse, delta, dq, st);
   }
   return hipGetLastError();
 }

@@ -9,6 +9,11 @@ using bf16 = __bf16;  // hardware round-to-nearest-even conversions (v_cvt_pk_bf
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+// fp16: the storage type of the forward activations when cfg.fwd_fp16 is set (3 more
+// significand bits than bf16 at the same size and the same matrix-core rate)
+using f16 = _Float16;
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -21,6 +26,13 @@ __device__ __forceinline__ float to_f32(bf16 v) { return static_cast<float>(v); 
 template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return static_cast<bf16>(v); }
+__device__ __forceinline__ float to_f32(f16 v) { return static_cast<float>(v); }
+// fp32 -> fp16, round to nearest even, saturating at the largest finite fp16 value
+// instead of overflowing to infinity
+__device__ __forceinline__ f16 sat_f16(float v) {
+  return static_cast<f16>(__builtin_fminf(__builtin_fmaxf(v, -65504.f), 65504.f));
+}
+template <> __device__ __forceinline__ f16 from_f32<f16>(float v) { return sat_f16(v); }
 
 // A 16-byte vector of storage elements: 4 x fp32 or 8 x bf16.
 template <typename T> struct Vec16;

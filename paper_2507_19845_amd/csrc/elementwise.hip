@@ -20,6 +20,17 @@ __device__ __forceinline__ void load8(const bf16* p, float (&v)[8]) {
 #pragma unroll
   for (int e = 0; e < 8; ++e) v[e] = (float)a[e];
 }
+__device__ __forceinline__ void load8(const f16* p, float (&v)[8]) {
+  const f16x8 a = *reinterpret_cast<const f16x8*>(p);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = (float)a[e];
+}
+__device__ __forceinline__ void store8(f16* p, const float (&v)[8]) {
+  f16x8 a;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) a[e] = sat_f16(v[e]);
+  *reinterpret_cast<f16x8*>(p) = a;
+}
 __device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
   f32x4 a, b;
 #pragma unroll
@@ -37,11 +48,12 @@ __device__ __forceinline__ void store8(bf16* p, const float (&v)[8]) {
 // ----------------------------------------------------------------- LN fwd ----
 // Per token: mu = mean(x), var = mean((x-mu)^2), r = 1/sqrt(var+eps),
 // out = (x-mu) r gamma + beta.  TX = type of x (the residual stream, fp32 inside
-// bf16 stages), T = type of gamma/beta/out.  NCH = 8-element chunks per thread.
-template <typename TX, typename T, int NCH>
+// bf16 stages), T = type of gamma/beta, TO = type of out (T, or fp16 when the forward
+// activations of a bf16 stage are kept in fp16).  NCH = 8-element chunks per thread.
+template <typename TX, typename T, typename TO, int NCH>
 __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(
     const TX* __restrict__ x, const T* __restrict__ gamma, const T* __restrict__ beta,
-    T* __restrict__ out, float* __restrict__ mean, float* __restrict__ rstd, int H, float eps) {
+    TO* __restrict__ out, float* __restrict__ mean, float* __restrict__ rstd, int H, float eps) {
   __shared__ float red[2][kLnThreads / kWave];
   const int row = blockIdx.x;
   const int nvec = H / 8;
@@ -72,7 +84,7 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(
   }
   const float var = block_sum<kLnThreads / kWave>(q, red[1]) / (float)H;
   const float r = 1.f / sqrtf(var + eps);
-  T* orow = out + (size_t)row * H;
+  TO* orow = out + (size_t)row * H;
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
     const int i = threadIdx.x + c * kLnThreads;
@@ -300,13 +312,13 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict
 }
 
 // --------------------------------------------------------------- launchers ----
-template <typename TX, typename T>
+template <typename TX, typename T, typename TO>
 static hipError_t ln_fwd_t(int T_rows, int H, float eps, const TX* x, const T* gamma, const T* beta,
-                           T* out, float* mean, float* rstd, hipStream_t st) {
+                           TO* out, float* mean, float* rstd, hipStream_t st) {
   const int nch = (H / 8 + kLnThreads - 1) / kLnThreads;
   dim3 g(T_rows), b(kLnThreads);
 #define GPTS_LN_FWD(N)                                                                           \
-  hipLaunchKernelGGL((ln_fwd_kernel<TX, T, N>), g, b, 0, st, x, gamma, beta, out, mean, rstd, H, eps)
+  hipLaunchKernelGGL((ln_fwd_kernel<TX, T, TO, N>), g, b, 0, st, x, gamma, beta, out, mean, rstd, H, eps)
   if (nch <= 1) GPTS_LN_FWD(1);
   else if (nch <= 2) GPTS_LN_FWD(2);
   else if (nch <= 4) GPTS_LN_FWD(4);
@@ -317,15 +329,22 @@ static hipError_t ln_fwd_t(int T_rows, int H, float eps, const TX* x, const T* g
 
 hipError_t ln_fwd(int dtype, bool x_f32, int T_rows, int H, float eps, const void* x,
                   const void* gamma, const void* beta, void* out, float* mean, float* rstd,
-                  hipStream_t st) {
-  if (dtype == 0)
-    return ln_fwd_t<float, float>(T_rows, H, eps, (const float*)x, (const float*)gamma,
-                                  (const float*)beta, (float*)out, mean, rstd, st);
-  if (x_f32)
-    return ln_fwd_t<float, bf16>(T_rows, H, eps, (const float*)x, (const bf16*)gamma,
-                                 (const bf16*)beta, (bf16*)out, mean, rstd, st);
-  return ln_fwd_t<bf16, bf16>(T_rows, H, eps, (const bf16*)x, (const bf16*)gamma, (const bf16*)beta,
-                              (bf16*)out, mean, rstd, st);
+                  hipStream_t st, bool out_f16) {
+  if (dtype == 0) {
+    if (out_f16) return hipErrorInvalidValue;
+    return ln_fwd_t<float, float, float>(T_rows, H, eps, (const float*)x, (const float*)gamma,
+                                         (const float*)beta, (float*)out, mean, rstd, st);
+  }
+  if (x_f32) {
+    if (out_f16)
+      return ln_fwd_t<float, bf16, f16>(T_rows, H, eps, (const float*)x, (const bf16*)gamma,
+                                        (const bf16*)beta, (f16*)out, mean, rstd, st);
+    return ln_fwd_t<float, bf16, bf16>(T_rows, H, eps, (const float*)x, (const bf16*)gamma,
+                                       (const bf16*)beta, (bf16*)out, mean, rstd, st);
+  }
+  if (out_f16) return hipErrorInvalidValue;
+  return ln_fwd_t<bf16, bf16, bf16>(T_rows, H, eps, (const bf16*)x, (const bf16*)gamma, (const bf16*)beta,
+                                    (bf16*)out, mean, rstd, st);
 }
 
 int ln_bwd_blocks(int T_rows) { return T_rows < kLnBwdMaxBlocks ? T_rows : kLnBwdMaxBlocks; }
@@ -377,8 +396,8 @@ hipError_t ln_bwd(int dtype, bool x_f32, int T_rows, int H, const void* dout, co
 }
 
 // g[i] = gelu(u[i]), 8 elements per thread (recomputation of the MLP activation)
-template <typename T, int KIND>
-__global__ __launch_bounds__(256) void gelu_kernel(const T* __restrict__ u, T* __restrict__ g, size_t n8) {
+template <typename TU, typename T, int KIND>
+__global__ __launch_bounds__(256) void gelu_kernel(const TU* __restrict__ u, T* __restrict__ g, size_t n8) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n8) return;
   float v[8];
@@ -388,16 +407,37 @@ __global__ __launch_bounds__(256) void gelu_kernel(const T* __restrict__ u, T* _
   store8(g + i * 8, v);
 }
 
-hipError_t gelu_fwd(int dtype, int kind, const void* u, void* g, size_t n, hipStream_t st) {
+hipError_t gelu_fwd(int dtype, int kind, const void* u, void* g, size_t n, hipStream_t st, bool u_f16) {
   const size_t n8 = n / 8;
   dim3 grid((unsigned)((n8 + 255) / 256)), blk(256);
   if (dtype == 0) {
-    if (kind == 0) hipLaunchKernelGGL((gelu_kernel<float, 0>), grid, blk, 0, st, (const float*)u, (float*)g, n8);
-    else hipLaunchKernelGGL((gelu_kernel<float, 1>), grid, blk, 0, st, (const float*)u, (float*)g, n8);
+    if (u_f16) return hipErrorInvalidValue;
+    if (kind == 0) hipLaunchKernelGGL((gelu_kernel<float, float, 0>), grid, blk, 0, st, (const float*)u, (float*)g, n8);
+    else hipLaunchKernelGGL((gelu_kernel<float, float, 1>), grid, blk, 0, st, (const float*)u, (float*)g, n8);
+  } else if (u_f16) {
+    if (kind == 0) hipLaunchKernelGGL((gelu_kernel<f16, bf16, 0>), grid, blk, 0, st, (const f16*)u, (bf16*)g, n8);
+    else hipLaunchKernelGGL((gelu_kernel<f16, bf16, 1>), grid, blk, 0, st, (const f16*)u, (bf16*)g, n8);
   } else {
-    if (kind == 0) hipLaunchKernelGGL((gelu_kernel<bf16, 0>), grid, blk, 0, st, (const bf16*)u, (bf16*)g, n8);
-    else hipLaunchKernelGGL((gelu_kernel<bf16, 1>), grid, blk, 0, st, (const bf16*)u, (bf16*)g, n8);
+    if (kind == 0) hipLaunchKernelGGL((gelu_kernel<bf16, bf16, 0>), grid, blk, 0, st, (const bf16*)u, (bf16*)g, n8);
+    else hipLaunchKernelGGL((gelu_kernel<bf16, bf16, 1>), grid, blk, 0, st, (const bf16*)u, (bf16*)g, n8);
   }
+  return hipGetLastError();
+}
+
+// out[i] = bf16(in[i]) for fp16 in: the backward phase's bf16 copies of forward activations
+// that were stored in fp16
+__global__ __launch_bounds__(256) void f16_to_bf16_kernel(const f16* __restrict__ in, bf16* __restrict__ out,
+                                                          size_t n8) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n8) return;
+  float v[8];
+  load8(in + i * 8, v);
+  store8(out + i * 8, v);
+}
+hipError_t f16_to_bf16(const void* in, void* out, size_t n, hipStream_t st) {
+  const size_t n8 = n / 8;
+  hipLaunchKernelGGL(f16_to_bf16_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, st, (const f16*)in,
+                     (bf16*)out, n8);
   return hipGetLastError();
 }
 

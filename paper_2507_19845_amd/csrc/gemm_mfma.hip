@@ -225,9 +225,14 @@ template <int... I, class F> __device__ __forceinline__ void static_for_impl(std
 template <int N, class F> __device__ __forceinline__ void static_for(F&& f) {
   static_for_impl(std::make_integer_sequence<int, N>{}, f);
 }
-template <int BM, int BN, int EPI, int NW, int LDS_BYTES, class StageWriter>
+// OUT16: the 16-bit outputs (C of the bias-only epilogue; C and the GeLU output of the GeLU
+// epilogues) are written as fp16 instead of bf16 (forward activations kept in fp16).
+template <int BM, int BN, int EPI, int NW, int LDS_BYTES, bool OUT16 = false, class StageWriter>
 __device__ __forceinline__ void gemm_epilogue(StageWriter&& write_pass, const MfmaArgs& a, char* lds,
                                               int m0, int n0, int wm, int wn, int wave, int lane) {
+  static_assert(!OUT16 || EPI == EPI_BIAS || EPI == EPI_GELU_TANH || EPI == EPI_GELU_ERF ||
+                    EPI == EPI_BIAS_RES32_OUT32 || EPI == EPI_BIAS_RES32_OUT16,
+                "fp16 outputs exist for the forward epilogues only");
   constexpr int WGN = NW / 2, WM = BM / 2, WN = BN / WGN;
   // The accumulators hold a lane-per-row layout (lane owns row lane&31 and four-column
   // groups), which would store 16-byte pieces scattered over 32 rows.  Each wave instead
@@ -310,16 +315,18 @@ __device__ __forceinline__ void gemm_epilogue(StageWriter&& write_pass, const Mf
         for (int e = 0; e < 4; ++e) c[e] = t.in32[u][e] + v[e];
         *reinterpret_cast<f32x4*>(static_cast<float*>(a.C) + t.o[u]) = c;
       } else if constexpr (GELU) {
-        bf16x4 uq, gq;
+        using T16 = std::conditional_t<OUT16, f16, bf16>;
+        typedef T16 t16x4 __attribute__((ext_vector_type(4)));
+        t16x4 uq, gq;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          uq[e] = (bf16)v[e];
+          uq[e] = from_f32<T16>(v[e]);
           // g is the GeLU of u AS STORED, so that a backward pass that recomputes g from
           // the stashed u gets the same bits
-          gq[e] = (bf16)gelu_f<EPI == EPI_GELU_TANH ? 0 : 1>((float)uq[e]);
+          gq[e] = from_f32<T16>(gelu_f<EPI == EPI_GELU_TANH ? 0 : 1>((float)uq[e]));
         }
-        *reinterpret_cast<bf16x4*>(static_cast<bf16*>(a.C) + t.o[u]) = uq;
-        *reinterpret_cast<bf16x4*>(a.gelu_out + t.o[u]) = gq;
+        *reinterpret_cast<t16x4*>(static_cast<T16*>(a.C) + t.o[u]) = uq;
+        *reinterpret_cast<t16x4*>(reinterpret_cast<T16*>(a.gelu_out) + t.o[u]) = gq;
       } else {
         if constexpr (DGELU) {
 #pragma unroll
@@ -338,6 +345,11 @@ __device__ __forceinline__ void gemm_epilogue(StageWriter&& write_pass, const Mf
 #pragma unroll
           for (int e = 0; e < 4; ++e) out[e] = v[e];
           *reinterpret_cast<f32x4*>(static_cast<float*>(a.C) + t.o[u]) = out;
+        } else if constexpr (OUT16 && EPI == EPI_BIAS) {
+          f16x4 out;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) out[e] = sat_f16(v[e]);
+          *reinterpret_cast<f16x4*>(static_cast<f16*>(a.C) + t.o[u]) = out;
         } else {
           bf16x4 out;
 #pragma unroll
@@ -665,9 +677,12 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const MfmaArgs a) {
 // KM: both operands K-major (wgrad: A is [K, M], B is [K, N]); their slices sit in LDS as they
 // sit in memory (32 k-rows of 512 bytes, 32-byte units swizzled with the k-row) and a fragment
 // is two transposing reads: lane group lane>>4 is the k-octet, lane&15 the column.
-template <int EPI, bool B_IMG, bool KM = false>
+// F16: both operands hold fp16 values (A an activation stored in fp16, B the fp16 image of a
+// weight); the f16 form of the matrix instruction is used and the 16-bit outputs are fp16.
+template <int EPI, bool B_IMG, bool KM = false, bool F16 = false>
 __global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
   static_assert(!(KM && B_IMG), "images are K-contiguous");
+  static_assert(!F16 || B_IMG, "fp16 products read the weight through its fp16 image");
   constexpr int BM = 256, BN = 256, BK = 32, NS = 4, NW = 4, WGN = 2;
   constexpr int WM = BM / 2, WN = BN / WGN, NB = WM / 16;   // 8 x 8 blocks of 16 x 16 per wave
   constexpr int A_BYTES = BM * BK * 2, STAGE = A_BYTES + BN * BK * 2, RB = BK * 2;
@@ -760,7 +775,7 @@ __global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
         // exactly one operand changes from one instruction to the next)
         static_for<4>([&](auto q_c) {
           constexpr int ib = g / 2, j0 = 4 * (g % 2) + decltype(q_c)::value, jb = (ib & 1) ? NB - 1 - j0 : j0;
-          mfma16_at<4 * (NB * ib + jb)>(fb[cur][jb], fa[cur][ib]);
+          mfma16_at<4 * (NB * ib + jb), F16>(fb[cur][jb], fa[cur][ib]);
         });
         __builtin_amdgcn_sched_barrier(0);
         // one fragment of the next slice
@@ -789,12 +804,13 @@ __global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
       *reinterpret_cast<f32x4*>(stg + stage_slot<WN>(ii * 16 + (lane & 15), jb * 4 + (lane >> 4))) = v;
     });
   };
-  gemm_epilogue<BM, BN, EPI, NW, NS * STAGE>(write_pass, a, lds, m0, n0, wm, wn, wave, lane);
+  gemm_epilogue<BM, BN, EPI, NW, NS * STAGE, F16>(write_pass, a, lds, m0, n0, wm, wn, wave, lane);
 }
 
-template <int EPI, bool B_IMG, bool KM = false> hipError_t launch_mi16(const MfmaArgs& a, hipStream_t st) {
+template <int EPI, bool B_IMG, bool KM = false, bool F16 = false>
+hipError_t launch_mi16(const MfmaArgs& a, hipStream_t st) {
   const int tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
-  hipLaunchKernelGGL((gemm_mi16_kernel<EPI, B_IMG, KM>), dim3(tiles), dim3(256), 0, st, a);
+  hipLaunchKernelGGL((gemm_mi16_kernel<EPI, B_IMG, KM, F16>), dim3(tiles), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
@@ -830,6 +846,10 @@ template <bool AK, bool BKM, int EPI> hipError_t pick_tile(const MfmaArgs& a, hi
 // element (n, k) of the operand is src[n*sn + k*sk].  Rows past N are zero.  One
 // workgroup per (slice, tile): the 32 x 256 source patch goes through LDS so that both
 // the reads (along whichever index is contiguous in src) and the writes are coalesced.
+// TO_F16: the image holds the values converted to fp16 (exact for magnitudes in
+// [2^-14, 65504]; smaller ones become fp16 subnormals, absolute error <= 2^-25; larger ones
+// saturate), for products whose other operand is an fp16 activation.
+template <bool TO_F16>
 __global__ __launch_bounds__(256) void prepare_image_kernel(const bf16* __restrict__ src, bf16* __restrict__ img,
                                                             int N, int K, size_t sn, size_t sk) {
   __shared__ bf16 patch[256][32 + 2];   // [row n][k], padded
@@ -858,10 +878,17 @@ __global__ __launch_bounds__(256) void prepare_image_kernel(const bf16* __restri
   bf16* out = img + ((size_t)tn * nk + kt) * (256 * 32);
   for (int slot = threadIdx.x; slot < 256 * 4; slot += 256) {
     const int r = slot >> 2, c = (slot & 3) ^ swz_kc<4>(r);
-    bf16x8 v;
+    if constexpr (TO_F16) {
+      f16x8 v;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = patch[r][c * 8 + e];
-    *reinterpret_cast<bf16x8*>(out + (size_t)slot * 8) = v;
+      for (int e = 0; e < 8; ++e) v[e] = sat_f16((float)patch[r][c * 8 + e]);
+      *reinterpret_cast<f16x8*>(out + (size_t)slot * 8) = v;
+    } else {
+      bf16x8 v;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = patch[r][c * 8 + e];
+      *reinterpret_cast<bf16x8*>(out + (size_t)slot * 8) = v;
+    }
   }
 }
 
@@ -880,12 +907,40 @@ int gemm_mfma_colsum_rows(int M, int N) {
 
 size_t gemm_image_elems(int N, int K) { return (size_t)((N + 255) / 256) * 256 * K; }
 
-hipError_t gemm_prepare_image(const void* src, void* img, int N, int K, bool transposed, hipStream_t st) {
+hipError_t gemm_prepare_image(const void* src, void* img, int N, int K, bool transposed, hipStream_t st,
+                              bool to_f16) {
   // operand element (n, k) = src[n*K + k] (src is [N,K]) or src[k*N + n] (src is [K,N])
   dim3 g(K / 32, (N + 255) / 256);
-  hipLaunchKernelGGL(prepare_image_kernel, g, dim3(256), 0, st, (const bf16*)src, (bf16*)img, N, K,
-                     transposed ? (size_t)1 : (size_t)K, transposed ? (size_t)N : (size_t)1);
+  const size_t sn = transposed ? (size_t)1 : (size_t)K, sk = transposed ? (size_t)N : (size_t)1;
+  if (to_f16)
+    hipLaunchKernelGGL(prepare_image_kernel<true>, g, dim3(256), 0, st, (const bf16*)src, (bf16*)img, N, K, sn, sk);
+  else
+    hipLaunchKernelGGL(prepare_image_kernel<false>, g, dim3(256), 0, st, (const bf16*)src, (bf16*)img, N, K, sn, sk);
   return hipGetLastError();
+}
+
+bool gemm_fwd_f16_supported(int M, int N, int K) {
+  return M >= 1 && N >= 8 && N % 8 == 0 && K >= 128 && K % 128 == 0 && (size_t)M * K < (1ull << 31) &&
+         (size_t)((N + 255) / 256) * 256 * K < (1ull << 31);
+}
+
+hipError_t gemm_fwd_f16(int M, int N, int K, const void* A, const void* b_image, void* C,
+                        const GemmEpilogue& ep, hipStream_t st) {
+  if (!gemm_fwd_f16_supported(M, N, K) || !b_image) return hipErrorInvalidValue;
+  MfmaArgs a;
+  a.A = (const bf16*)A; a.B = (const bf16*)b_image; a.C = C;
+  a.M = M; a.N = N; a.K = K;
+  a.bias = (const bf16*)ep.bias; a.residual = ep.residual;
+  a.gelu_out = (bf16*)ep.gelu_out; a.dgelu_u = nullptr; a.colsum = nullptr;
+  if (ep.gelu_out)
+    return ep.gelu_kind == 0 ? launch_mi16<EPI_GELU_TANH, true, false, true>(a, st)
+                             : launch_mi16<EPI_GELU_ERF, true, false, true>(a, st);
+  if (ep.residual) {
+    if (!ep.residual_f32) return hipErrorInvalidValue;
+    return ep.out_f32 ? launch_mi16<EPI_BIAS_RES32_OUT32, true, false, true>(a, st)
+                      : launch_mi16<EPI_BIAS_RES32_OUT16, true, false, true>(a, st);
+  }
+  return launch_mi16<EPI_BIAS, true, false, true>(a, st);
 }
 
 hipError_t gemm_mfma(int form, int M, int N, int K, const void* A, const void* B, void* C,

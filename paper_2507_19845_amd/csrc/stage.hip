@@ -70,7 +70,10 @@ StashLayer stash_layer(const gpt_stage_cfg& c) {
   StashLayer s;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
-  const bool full = c.recompute == 0;   // with recomputation A, A2 and G are not stashed
+  // with recomputation, and always when the forward activations are fp16 (the backward phase
+  // needs bf16 copies and rebuilds them), A, A2 and G are not stashed; with fwd_fp16 the
+  // stashed QKV, C and U hold fp16 values (same size)
+  const bool full = c.recompute == 0 && c.fwd_fp16 == 0;
   s.X = take((size_t)D.T * D.H * kResBytes);
   s.stat1 = take((size_t)2 * D.T * 4);
   s.A = full ? take((size_t)D.T * D.H * e) : kAbsent;
@@ -101,14 +104,16 @@ FwdWs fwd_ws(const gpt_stage_cfg& c) {
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
   w.attn = take(attention_scratch_bytes(c.dtype, D.B, D.S, D.a, D.d, 0));
-  w.A = c.recompute ? take((size_t)D.T * D.H * e) : kAbsent;
-  w.G = c.recompute ? take((size_t)D.T * D.F * e) : kAbsent;
+  const bool transient = c.recompute || c.fwd_fp16;
+  w.A = transient ? take((size_t)D.T * D.H * e) : kAbsent;
+  w.G = transient ? take((size_t)D.T * D.F * e) : kAbsent;
   w.end = o;
   return w;
 }
 size_t fwd_ws_bytes(const gpt_stage_cfg& c) { return fwd_ws(c).end; }
 struct BwdWs {
   size_t dU, dA, dX1, dC, dQKV, attn, ping, pong, ln_part, cs_part, rA, rG, rstat, end;
+  size_t bQKV, bC, bU;   // fwd_fp16: bf16 copies of the fp16 QKV, C and U of the stash
 };
 BwdWs bwd_ws(const gpt_stage_cfg& c) {
   Dims D(c);
@@ -130,9 +135,13 @@ BwdWs bwd_ws(const gpt_stage_cfg& c) {
   if (D.F > maxn) maxn = D.F;
   w.cs_part = take(colsum_scratch_bytes(D.T, maxn));
   // recomputed LayerNorm output (one buffer, used for A2 and then A), GeLU output, statistics
-  w.rA = c.recompute ? take((size_t)D.T * D.H * e) : kAbsent;
-  w.rG = c.recompute ? take((size_t)D.T * D.F * e) : kAbsent;
-  w.rstat = c.recompute ? take((size_t)2 * D.T * 4) : kAbsent;
+  const bool rebuild = c.recompute || c.fwd_fp16;
+  w.rA = rebuild ? take((size_t)D.T * D.H * e) : kAbsent;
+  w.rG = rebuild ? take((size_t)D.T * D.F * e) : kAbsent;
+  w.rstat = rebuild ? take((size_t)2 * D.T * 4) : kAbsent;
+  w.bQKV = c.fwd_fp16 ? take((size_t)D.T * 3 * D.P * e) : kAbsent;
+  w.bC = c.fwd_fp16 ? take((size_t)D.T * D.P * e) : kAbsent;
+  w.bU = c.fwd_fp16 ? take((size_t)D.T * D.F * e) : kAbsent;
   w.end = o;
   return w;
 }
@@ -224,21 +233,26 @@ hipError_t gemm(int dtype, int form, int M, int N, int K, const void* A, const v
 
 // Attention: MFMA kernels for bf16 with head_dim 64/128, the plain FMA kernels otherwise.
 // scratch: attention_scratch_bytes(.., phase) bytes of device memory.
-bool attention_uses_mfma(int dtype, int d) { return dtype == GPTS_BF16 && (d == 64 || d == 128); }
+bool attention_uses_mfma(int dtype, int B, int S, int a, int d) {
+  return dtype == GPTS_BF16 && attention_mfma_supported(B, S, a, d);
+}
 size_t attention_scratch_bytes(int dtype, int B, int S, int a, int d, int phase) {
-  if (attention_uses_mfma(dtype, d)) return attention_mfma_scratch_bytes(B, S, a, d, phase);
+  if (attention_uses_mfma(dtype, B, S, a, d)) return attention_mfma_scratch_bytes(B, S, a, d, phase);
   return phase == 0 ? 0 : align_up((size_t)B * a * S * sizeof(float), 256);  // delta
 }
+// f16 / qkv_f16: the fp16 forward-activation variants (matrix-core path only)
 hipError_t attention_fwd(int dtype, int B, int S, int a, int d, const void* qkv, void* out,
-                         float* lse, void* scratch, hipStream_t st) {
-  if (attention_uses_mfma(dtype, d)) return attention_fwd_mfma(B, S, a, d, qkv, out, lse, scratch, st);
+                         float* lse, void* scratch, hipStream_t st, bool f16 = false) {
+  if (attention_uses_mfma(dtype, B, S, a, d)) return attention_fwd_mfma(B, S, a, d, qkv, out, lse, scratch, st, f16);
+  if (f16) return hipErrorInvalidValue;
   return attention_fwd_simple(dtype, B, S, a, d, qkv, out, lse, st);
 }
 hipError_t attention_bwd(int dtype, int B, int S, int a, int d, const void* qkv, const void* out,
                          const float* lse, const void* dout, void* dqkv, void* scratch,
-                         hipStream_t st) {
-  if (attention_uses_mfma(dtype, d))
-    return attention_bwd_mfma(B, S, a, d, qkv, out, lse, dout, dqkv, scratch, st);
+                         hipStream_t st, const void* qkv_f16 = nullptr) {
+  if (attention_uses_mfma(dtype, B, S, a, d))
+    return attention_bwd_mfma(B, S, a, d, qkv, out, lse, dout, dqkv, scratch, st, qkv_f16);
+  if (qkv_f16) return hipErrorInvalidValue;
   return attention_bwd_simple(dtype, B, S, a, d, qkv, out, lse, dout, dqkv, static_cast<float*>(scratch), st);
 }
 
@@ -251,10 +265,16 @@ int check_call(const gpt_stage_params* p) {
   if (p->prepared && misaligned(p->prepared)) return fail(GPTS_EINVAL, "prepared not 16-byte aligned");
   return GPTS_OK;
 }
+int need_prepared(const gpt_stage_params* p) {
+  if (p->cfg.fwd_fp16 && !p->prepared)
+    return fail(GPTS_EINVAL, "cfg.fwd_fp16 needs prepared weights (gpt_stage_prepare with the same cfg)");
+  return GPTS_OK;
+}
 
 int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, hipStream_t st) {
   int rc = check_call(p);
   if (rc != GPTS_OK) return rc;
+  if ((rc = need_prepared(p)) != GPTS_OK) return rc;
   Tracer* tr = static_cast<Tracer*>(p->trace);
   if (!x || !act_stash || !y || misaligned(x) || misaligned(act_stash) || misaligned(y))
     return fail(GPTS_EINVAL, "x / act_stash / y NULL or not 16-byte aligned");
@@ -292,39 +312,46 @@ int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, 
     float* stat1 = reinterpret_cast<float*>(s + sl.stat1);
     float* stat2 = reinterpret_cast<float*>(s + sl.stat2);
     void* Yout = (l == D.L - 1) ? y : (void*)(s + sl.end + sl.X);
-    // with recomputation the LayerNorm and GeLU outputs only live in the workspace
-    void* A = c.recompute ? fwk + fw.A : s + sl.A;
-    void* A2 = c.recompute ? fwk + fw.A : s + sl.A2;
-    void* G = c.recompute ? fwk + fw.G : s + sl.G;
+    // with recomputation (and with fp16 forward activations) the LayerNorm and GeLU outputs
+    // only live in the workspace
+    const bool transient = c.recompute || c.fwd_fp16;
+    const bool h16 = c.fwd_fp16 != 0;   // A, QKV, C, A2, U, G hold fp16 values
+    void* A = transient ? fwk + fw.A : s + sl.A;
+    void* A2 = transient ? fwk + fw.A : s + sl.A2;
+    void* G = transient ? fwk + fw.G : s + sl.G;
+    // one forward product: fp16 operands through the weight's fp16 image, or the bf16 paths
+    auto fwd_gemm = [&](int N, int K, const void* Ain, int wid, void* Cout, const GemmEpilogue& ep_) {
+      return h16 ? gemm_fwd_f16(D.T, N, K, Ain, ep_.b_image, Cout, ep_, st) : gemm(dt, 0, D.T, N, K, Ain, w(l, wid), Cout, ep_, st);
+    };
     GPTS_OP(GPTS_TR_LN_FWD, 0, 0, 0.0, TH * (kResBytes + e), ln_fwd(dt, bf, D.T, D.H, c.ln_eps, X, w(l, GPTS_LN1_G), w(l, GPTS_LN1_B), A, stat1,
-                    stat1 + D.T, st), "ln1 fwd");
+                    stat1 + D.T, st, h16), "ln1 fwd");
     GemmEpilogue ep;
     ep.bias = w(l, GPTS_B_QKV);
     ep.b_image = img(l, 0, 0);
-    GPTS_OP(GPTS_TR_GEMM_FWD, 0, 0, gf(D.T, 3 * D.P, D.H), gb(D.T, 3 * D.P, D.H, e), gemm(dt, 0, D.T, 3 * D.P, D.H, A, w(l, GPTS_W_QKV), s + sl.QKV, ep, st), "qkv gemm");
+    GPTS_OP(GPTS_TR_GEMM_FWD, 0, 0, gf(D.T, 3 * D.P, D.H), gb(D.T, 3 * D.P, D.H, e), fwd_gemm(3 * D.P, D.H, A, GPTS_W_QKV, s + sl.QKV, ep), "qkv gemm");
     GPTS_OP(GPTS_TR_ATTN_FWD, 0, 0, attn_fl, (double)D.T * 4 * D.P * e, attention_fwd(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
-                                  reinterpret_cast<float*>(s + sl.LSE), fwk + fw.attn, st), "attention fwd");
+                                  reinterpret_cast<float*>(s + sl.LSE), fwk + fw.attn, st, h16), "attention fwd");
     ep = GemmEpilogue();
     ep.bias = w(l, GPTS_B_O);
     ep.residual = X;
     ep.residual_f32 = ep.out_f32 = bf;
     ep.b_image = img(l, 1, 0);
-    GPTS_OP(GPTS_TR_GEMM_FWD, 1, 0, gf(D.T, D.H, D.P), gb(D.T, D.H, D.P, 2 * kResBytes), gemm(dt, 0, D.T, D.H, D.P, s + sl.C, w(l, GPTS_W_O), s + sl.X1, ep, st), "out-proj gemm");
+    GPTS_OP(GPTS_TR_GEMM_FWD, 1, 0, gf(D.T, D.H, D.P), gb(D.T, D.H, D.P, 2 * kResBytes), fwd_gemm(D.H, D.P, s + sl.C, GPTS_W_O, s + sl.X1, ep), "out-proj gemm");
     GPTS_OP(GPTS_TR_LN_FWD, 1, 0, 0.0, TH * (kResBytes + e), ln_fwd(dt, bf, D.T, D.H, c.ln_eps, s + sl.X1, w(l, GPTS_LN2_G), w(l, GPTS_LN2_B), A2,
-                    stat2, stat2 + D.T, st), "ln2 fwd");
+                    stat2, stat2 + D.T, st, h16), "ln2 fwd");
     ep = GemmEpilogue();
     ep.bias = w(l, GPTS_B_FC1);
     ep.gelu_out = G;
     ep.gelu_kind = c.gelu;
     ep.b_image = img(l, 2, 0);
-    GPTS_OP(GPTS_TR_GEMM_FWD, 2, 0, gf(D.T, D.F, D.H), gb(D.T, D.F, D.H, 2 * e), gemm(dt, 0, D.T, D.F, D.H, A2, w(l, GPTS_W_FC1), s + sl.U, ep, st), "fc1 gemm");
+    GPTS_OP(GPTS_TR_GEMM_FWD, 2, 0, gf(D.T, D.F, D.H), gb(D.T, D.F, D.H, 2 * e), fwd_gemm(D.F, D.H, A2, GPTS_W_FC1, s + sl.U, ep), "fc1 gemm");
     ep = GemmEpilogue();
     ep.bias = w(l, GPTS_B_FC2);
     ep.residual = s + sl.X1;
     ep.residual_f32 = bf;
     ep.out_f32 = bf && l != D.L - 1;   // the stage output y is bf16, the stream between layers fp32
     ep.b_image = img(l, 3, 0);
-    GPTS_OP(GPTS_TR_GEMM_FWD, 3, 0, gf(D.T, D.H, D.F), gb(D.T, D.H, D.F, 2 * kResBytes), gemm(dt, 0, D.T, D.H, D.F, G, w(l, GPTS_W_FC2), Yout, ep, st), "fc2 gemm");
+    GPTS_OP(GPTS_TR_GEMM_FWD, 3, 0, gf(D.T, D.H, D.F), gb(D.T, D.H, D.F, 2 * kResBytes), fwd_gemm(D.H, D.F, G, GPTS_W_FC2, Yout, ep), "fc2 gemm");
   }
   return GPTS_OK;
 }
@@ -333,6 +360,7 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
             void* dparams, hipStream_t st) {
   int rc = check_call(p);
   if (rc != GPTS_OK) return rc;
+  if ((rc = need_prepared(p)) != GPTS_OK) return rc;
   Tracer* tr = static_cast<Tracer*>(p->trace);
   if (!act_stash || !dy || !dx || !dparams || misaligned(act_stash) || misaligned(dy) ||
       misaligned(dx) || misaligned(dparams))
@@ -380,8 +408,18 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     d_o.b_image = img(l, 1);
     d_qkv.b_image = img(l, 0);
     // y = x1 + g W2^T + b2 ;  g = gelu(u)
+    const bool h16 = c.fwd_fp16 != 0;            // QKV, C, U of the stash hold fp16 values
+    const bool rebuild = c.recompute || h16;     // A, A2, G are rebuilt here (as bf16)
+    const void* U = s + sl.U;
+    if (h16) {
+      // gradients need bf16's range, so every backward product is bf16: it reads bf16 copies of
+      // the fp16 forward activations (only the attention logits are recomputed from the fp16
+      // Q and K, the operands the forward pass formed them from)
+      GPTS_OP(GPTS_TR_CONVERT, 2, 1, 0.0, (double)D.T * D.F * 2 * e, f16_to_bf16(s + sl.U, wk + ws.bU, (size_t)D.T * D.F, st), "u to bf16");
+      U = wk + ws.bU;
+    }
     GemmEpilogue ep;
-    ep.dgelu_u = s + sl.U;
+    ep.dgelu_u = U;
     ep.gelu_kind = c.gelu;
     ep.b_image = img(l, 3);
     // the matrix-core product also leaves the column sums of dU (the fc1 bias gradient) as
@@ -393,8 +431,8 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     if (fused_b1)
       GPTS_OP(GPTS_TR_BIAS_GRAD, 2, 1, 0.0, (double)cs_rows * D.F * 4, reduce_colsum_partials(cs_part, cs_rows, D.F, g(l, GPTS_B_FC1), st), "fc1 bias grad (partials from the fc2 dgrad epilogue)");
     const void* G = s + sl.G;
-    if (c.recompute) {
-      GPTS_OP(GPTS_TR_RECOMPUTE, 2, 1, 0.0, (double)D.T * D.F * 2 * e, gelu_fwd(dt, c.gelu, s + sl.U, wk + ws.rG, (size_t)D.T * D.F, st), "gelu recompute");
+    if (rebuild) {
+      GPTS_OP(GPTS_TR_RECOMPUTE, 2, 1, 0.0, (double)D.T * D.F * 2 * e, gelu_fwd(dt, c.gelu, s + sl.U, wk + ws.rG, (size_t)D.T * D.F, st, h16), "gelu recompute");
       G = wk + ws.rG;
     }
     GPTS_OP(GPTS_TR_GEMM_WGRAD, 3, 1, gf(D.H, D.F, D.T), gb(D.H, D.F, D.T, 8), gemm(dt, 2, D.H, D.F, D.T, dY, G, g(l, GPTS_W_FC2), none, st), "fc2 wgrad");
@@ -405,7 +443,7 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     // u = a2 W1^T + b1
     GPTS_OP(GPTS_TR_GEMM_DGRAD, 2, 1, gf(D.T, D.H, D.F), gb(D.T, D.H, D.F, e), gemm(dt, 1, D.T, D.H, D.F, dU, w(l, GPTS_W_FC1), dA, d_fc1, st), "fc1 dgrad");
     const void* A2 = s + sl.A2;
-    if (c.recompute) {
+    if (rebuild) {
       float* rs = reinterpret_cast<float*>(wk + ws.rstat);
       GPTS_OP(GPTS_TR_RECOMPUTE, 1, 1, 0.0, TH * (kResBytes + e), ln_fwd(dt, dt == GPTS_BF16, D.T, D.H, c.ln_eps, s + sl.X1, w(l, GPTS_LN2_G), w(l, GPTS_LN2_B),
                       wk + ws.rA, rs, rs + D.T, st), "ln2 recompute");
@@ -419,15 +457,23 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
                     g(l, GPTS_LN2_G), g(l, GPTS_LN2_B), g(l, GPTS_B_O), ln_part, st), "ln2 bwd (+ out-proj bias grad)");
     // x1 = x + c Wo^T + bo
     GPTS_OP(GPTS_TR_GEMM_DGRAD, 1, 1, gf(D.T, D.P, D.H), gb(D.T, D.P, D.H, e), gemm(dt, 1, D.T, D.P, D.H, dX1, w(l, GPTS_W_O), dC, d_o, st), "out-proj dgrad");
-    GPTS_OP(GPTS_TR_GEMM_WGRAD, 1, 1, gf(D.H, D.P, D.T), gb(D.H, D.P, D.T, 8), gemm(dt, 2, D.H, D.P, D.T, dX1, s + sl.C, g(l, GPTS_W_O), none, st), "out-proj wgrad");
+    const void* Cb = s + sl.C;
+    const void* QKVb = s + sl.QKV;
+    if (h16) {
+      GPTS_OP(GPTS_TR_CONVERT, 1, 1, 0.0, (double)D.T * D.P * 2 * e, f16_to_bf16(s + sl.C, wk + ws.bC, (size_t)D.T * D.P, st), "c to bf16");
+      GPTS_OP(GPTS_TR_CONVERT, 0, 1, 0.0, (double)D.T * 3 * D.P * 2 * e, f16_to_bf16(s + sl.QKV, wk + ws.bQKV, (size_t)D.T * 3 * D.P, st), "qkv to bf16");
+      Cb = wk + ws.bC;
+      QKVb = wk + ws.bQKV;
+    }
+    GPTS_OP(GPTS_TR_GEMM_WGRAD, 1, 1, gf(D.H, D.P, D.T), gb(D.H, D.P, D.T, 8), gemm(dt, 2, D.H, D.P, D.T, dX1, Cb, g(l, GPTS_W_O), none, st), "out-proj wgrad");
     // c = attention(qkv)
-    GPTS_OP(GPTS_TR_ATTN_BWD, 0, 1, 2.0 * attn_fl, (double)D.T * 9 * D.P * e, attention_bwd(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
-                                  reinterpret_cast<const float*>(s + sl.LSE), dC, dQKV, attn_scratch, st),
+    GPTS_OP(GPTS_TR_ATTN_BWD, 0, 1, 2.0 * attn_fl, (double)D.T * 9 * D.P * e, attention_bwd(dt, D.B, D.S, D.a, D.d, QKVb, s + sl.C,
+                                  reinterpret_cast<const float*>(s + sl.LSE), dC, dQKV, attn_scratch, st, h16 ? s + sl.QKV : nullptr),
              "attention bwd");
     // qkv = a Wqkv^T + bqkv
     GPTS_OP(GPTS_TR_GEMM_DGRAD, 0, 1, gf(D.T, D.H, 3 * D.P), gb(D.T, D.H, 3 * D.P, e), gemm(dt, 1, D.T, D.H, 3 * D.P, dQKV, w(l, GPTS_W_QKV), dA, d_qkv, st), "qkv dgrad");
     const void* A = s + sl.A;
-    if (c.recompute) {
+    if (rebuild) {
       float* rs = reinterpret_cast<float*>(wk + ws.rstat);
       GPTS_OP(GPTS_TR_RECOMPUTE, 0, 1, 0.0, TH * (kResBytes + e), ln_fwd(dt, dt == GPTS_BF16, D.T, D.H, c.ln_eps, s + sl.X, w(l, GPTS_LN1_G), w(l, GPTS_LN1_B),
                       wk + ws.rA, rs, rs + D.T, st), "ln1 recompute");
@@ -458,6 +504,8 @@ int gpt_stage_validate(const gpt_stage_cfg* c) {
   if (c->gelu != GPTS_GELU_TANH && c->gelu != GPTS_GELU_ERF) return fail(GPTS_EINVAL, "gelu must be GPTS_GELU_TANH or GPTS_GELU_ERF");
   if (!(c->ln_eps >= 0.f)) return fail(GPTS_EINVAL, "ln_eps must be >= 0");
   if (c->recompute != 0 && c->recompute != 1) return fail(GPTS_EINVAL, "recompute must be 0 or 1");
+  if (c->fwd_fp16 != 0 && c->fwd_fp16 != 1) return fail(GPTS_EINVAL, "fwd_fp16 must be 0 or 1");
+  if (c->fwd_fp16 && c->dtype != GPTS_BF16) return fail(GPTS_EINVAL, "fwd_fp16 applies to bf16 stages only");
   if (c->n_layers < 1 || c->batch < 1 || c->seq < 1 || c->n_heads < 1 || c->hidden < 1 || c->ffn < 1)
     return fail(GPTS_ESHAPE, "n_layers, batch, seq, n_heads, hidden, ffn must be >= 1");
   if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128)
@@ -468,6 +516,16 @@ int gpt_stage_validate(const gpt_stage_cfg* c) {
   if (T > (1 << 24) || P > (1 << 20) || c->ffn > (1 << 20)) return fail(GPTS_ESHAPE, "tokens, attention width or ffn too large");
   if (c->dtype == GPTS_BF16 && (T % 64 || c->hidden % 64 || P % 64 || c->ffn % 64))
     return fail(GPTS_ESHAPE, "bf16 stages need tokens, hidden, attention width and ffn to be multiples of 64");
+  if (c->fwd_fp16) {
+    const int Pi = (int)P, Ti = (int)T;
+    if (c->hidden % 128 || P % 128 || c->ffn % 128)
+      return fail(GPTS_ESHAPE, "fwd_fp16 needs hidden, attention width and ffn to be multiples of 128");
+    if (!attention_mfma_supported(c->batch, c->seq, c->n_heads, c->head_dim))
+      return fail(GPTS_ESHAPE, "fwd_fp16 needs head_dim 64 or 128 and seq*3*width < 2^31");
+    if (!gemm_fwd_f16_supported(Ti, 3 * Pi, c->hidden) || !gemm_fwd_f16_supported(Ti, c->hidden, Pi) ||
+        !gemm_fwd_f16_supported(Ti, c->ffn, c->hidden) || !gemm_fwd_f16_supported(Ti, c->hidden, c->ffn))
+      return fail(GPTS_ESHAPE, "fwd_fp16: a forward product exceeds the 32-bit operand offsets of the kernels");
+  }
   return GPTS_OK;
 }
 
@@ -531,7 +589,7 @@ int gpt_stage_prepare(const gpt_stage_params* p, void* prepared, void* stream) {
   for (int l = 0; l < D.L; ++l)
     for (int i = 0; i < 4; ++i) {
       const bf16* w = W + tensor_off(D, l, L[i].wid);
-      GPTS_TRY(gemm_prepare_image(w, out + prepared_off(D, l, i, 0), L[i].out, L[i].in, false, st), "prepare fwd image");
+      GPTS_TRY(gemm_prepare_image(w, out + prepared_off(D, l, i, 0), L[i].out, L[i].in, false, st, p->cfg.fwd_fp16 != 0), "prepare fwd image");
       GPTS_TRY(gemm_prepare_image(w, out + prepared_off(D, l, i, 1), L[i].in, L[i].out, true, st), "prepare dgrad image");
     }
   return GPTS_OK;
@@ -633,6 +691,7 @@ const char* gpt_stage_trace_op_name(int op) {
     case GPTS_TR_LN_BWD: return "layernorm_bwd";
     case GPTS_TR_ATTN_BWD: return "attention_bwd";
     case GPTS_TR_RECOMPUTE: return "recompute";
+    case GPTS_TR_CONVERT: return "convert";
   }
   return "unknown";
 }

@@ -30,9 +30,10 @@ class StageRunner:
                 ys: Sequence[torch.Tensor], dxs: Sequence[torch.Tensor],
                 stream: Optional[torch.cuda.Stream] = None) -> None:
         b = self.b
+        p = b.params()
         for x, dy, y, dx in zip(xs, dys, ys, dxs):
-            B.gpt_stage_fwd(b.cfg, b.weights, b.workspace, x, b.stash[0], y, stream)
-            B.gpt_stage_bwd(b.cfg, b.weights, b.workspace, b.stash[0], dy, dx, b.dparams, stream)
+            B.gpt_stage_fwd(p, x, b.stash[0], y, stream)
+            B.gpt_stage_bwd(p, b.stash[0], dy, dx, b.dparams, stream)
 
     def decoupled(self, xs, dys, ys, dxs) -> None:
         """All forwards on fwd_stream, then all backwards on bwd_stream.  The
@@ -42,11 +43,12 @@ class StageRunner:
         cur = torch.cuda.current_stream()
         self.fwd_stream.wait_stream(cur)
         n = len(xs)
+        p = b.params()
         for i in range(n):
-            B.gpt_stage_fwd_only(b.cfg, b.weights, b.workspace, xs[i], b.stash[i], ys[i],
+            B.gpt_stage_fwd_only(p, xs[i], b.stash[i], ys[i],
                                  self.fwd_stream, self.event if i == n - 1 else None)
         for i in range(n):
-            B.gpt_stage_bwd_only(b.cfg, b.weights, b.workspace, b.stash[i], dys[i], dxs[i],
+            B.gpt_stage_bwd_only(p, b.stash[i], dys[i], dxs[i],
                                  b.dparams, self.bwd_stream, self.event if i == 0 else None)
         cur.wait_stream(self.bwd_stream)
 

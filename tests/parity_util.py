@@ -22,13 +22,14 @@ def p64(params):
     return [{k: v.astype(np.float64) for k, v in p.items()} for p in params]
 
 
-def gpu_run(shape, params, xs, dys, decoupled=False, bufs=None):
+def gpu_run(shape, params, xs, dys, decoupled=False, bufs=None, trace=None):
     """Returns (ys, dxs, grads) as float64 numpy, parameter gradients accumulated
-    over the given micro-batches."""
+    over the given micro-batches.  trace: tracer handle attached to the stage calls."""
     n = len(xs)
     if bufs is None:
         bufs = B.StageBuffers(shape, n_stash=n if decoupled else 1)
         bufs.load_params(params)
+    bufs.trace = trace
     bufs.dparams.zero_()
     dxs_in = [B.to_device(x, shape.dtype) for x in xs]
     dys_in = [B.to_device(d, shape.dtype) for d in dys]
@@ -40,6 +41,7 @@ def gpu_run(shape, params, xs, dys, decoupled=False, bufs=None):
     else:
         runner.coupled(dxs_in, dys_in, ys, dxs)
     torch.cuda.synchronize()
+    bufs.trace = None
     return [B.to_host(y) for y in ys], [B.to_host(d) for d in dxs], bufs.read_grads()
 
 

@@ -44,6 +44,12 @@ SMALL = [
                seq=320, batch=1, bias_std=0.02, ln_jitter=0.1),
     W[1].with_(name="bf16_erf", n_layers=1, hidden=256, n_heads=4, head_dim=64, ffn=512, seq=64,
                batch=1, gelu="erf", bias_std=0.02),
+    # fp16 forward activations (cfg.fwd_fp16): ragged token count against the 256-row tiles,
+    # attention width != hidden, both head dimensions, both GeLU forms
+    W[1].with_(name="bf16_fwd16_d128", n_layers=2, hidden=512, n_heads=3, head_dim=128, ffn=640,
+               seq=320, batch=1, bias_std=0.02, ln_jitter=0.1, fwd_fp16=True),
+    W[1].with_(name="bf16_fwd16_d64_erf", n_layers=2, hidden=384, n_heads=4, head_dim=64, ffn=896,
+               seq=192, batch=2, gelu="erf", bias_std=0.02, ln_jitter=0.1, fwd_fp16=True),
 ]
 
 
@@ -105,12 +111,16 @@ def test_backward_stream_waits_for_the_forward_event():
             assert np.array_equal(ga[k], gb[k]), k
 
 
-def test_prepared_weights_give_identical_results():
+@pytest.mark.parametrize("ffn", [16384 - 64, 8192], ids=["ffn_ragged", "ffn_mult_128"])
+def test_prepared_weights_give_identical_results(ffn):
     """With the weight images of gpt_stage_prepare() the forward and dgrad products read
     the same numbers through a different layout: every output must be bit-identical to
     the run on the raw weights.  One layer of the decoupled workload's shape (large
-    enough for the 256x256 tiles the images are made for), ragged N via ffn."""
-    shape = W[3].with_(name="bf16_prepared", n_layers=1, ffn=16384 - 64, n_microbatches=1, bias_std=0.02)
+    enough for the 256x256 tiles the images are made for).  ffn 16320: ragged N, and a
+    contraction length that is not a multiple of 128 (the fc2 forward and fc1 dgrad images
+    then feed the 32x32x16 kernel); ffn 8192: every image-fed product takes the 16x16x32
+    kernel, as in the benchmark."""
+    shape = W[3].with_(name="bf16_prepared", n_layers=1, ffn=ffn, n_microbatches=1, bias_std=0.02)
     print(f"[case] prepared weights {shape}", flush=True)
     params, xs, dys = _inputs(shape)
     bufs = B.StageBuffers(shape)
@@ -139,12 +149,8 @@ def test_operator_tracer_records_every_operator():
     params, xs, dys = _inputs(shape)
     ref = gpu_run(shape, params, xs, dys)
     tr = B.gpt_stage_trace_create(64)
-    B.set_trace(tr)
-    try:
-        got = gpu_run(shape, params, xs, dys)
-        recs, dropped = B.gpt_stage_trace_collect(tr, 64)
-    finally:
-        B.set_trace(None)
+    got = gpu_run(shape, params, xs, dys, trace=tr)
+    recs, dropped = B.gpt_stage_trace_collect(tr, 64)
     # per layer 7 forward and 13 backward operators (the out-proj and fc2 bias gradients ride on
     # the LayerNorm backward kernels), plus the top layer's fc2 bias gradient
     n_ops = 20 * shape.n_layers + 1
@@ -163,12 +169,10 @@ def test_operator_tracer_records_every_operator():
     # capacity overflow is counted, not fatal
     B.gpt_stage_trace_reset(tr)
     small = B.gpt_stage_trace_create(5)
-    B.set_trace(small)
     try:
-        gpu_run(shape, params, xs, dys)
+        gpu_run(shape, params, xs, dys, trace=small)
         recs2, dropped2 = B.gpt_stage_trace_collect(small, 5)
     finally:
-        B.set_trace(None)
         B.gpt_stage_trace_destroy(small)
         B.gpt_stage_trace_destroy(tr)
     assert len(recs2) == 5 and dropped2 == n_ops - 5
@@ -245,49 +249,46 @@ def test_workload3_full_size():
 
 
 def test_workload5_full_size():
-    """One GPU's tensor-parallel share of a 175B-shaped layer at full size.
+    """One GPU's tensor-parallel share of a 175B-shaped layer at full size, every output
+    tensor against the oracle at the bf16 bar.
 
-    The forward output meets the 2e-2 bar.  The gradients do not, and cannot with
-    bf16-stored activations: with N(0, 0.02) weights at hidden 12288 the attention
-    logits have a standard deviation of ~4.9 (max ~23), and the softmax amplifies the
-    2^-9 rounding of the LayerNorm output and of q/k so much that the ORACLE ITSELF,
-    fed activations rounded to bf16 at the points where the stage stores them, moves
-    its layer-1 qkv gradients by 3-4e-2 (tests/test_oracle_pins.py::
-    test_workload5_conditioning shows this on the CPU).  What is asserted here:
-    y within 2e-2; every gradient within 6e-2 in the tensor-max-normalised max norm and
-    within 5e-2 in the relative L2 norm (about 1.5x what the rounded oracle shows); the
-    worst values are printed."""
+    With N(0, 0.02) weights at hidden 12288 the attention logits have a standard deviation
+    of ~4.9 (max ~23) and the softmax amplifies the rounding of every forward activation:
+    with bf16 forward activations the gradients miss the bar by a factor of two (the CPU
+    emulation in tests/test_rounding_emulation.py reproduces that with the oracle's own
+    arithmetic and shows which tensors matter).  The workload therefore runs with
+    cfg.fwd_fp16: forward activations in fp16, everything else bf16.  The same stage with
+    bf16 forward activations is run too and must show the larger error, so that the
+    switch is known to be what brings the workload inside the bar."""
     shape = W[4]
+    assert shape.fwd_fp16
     print(f"[case] full {shape}", flush=True)
     params, xs, dys = _inputs(shape)
     got = gpu_run(shape, params, xs, dys)
     ref = oracle_run(shape, params, xs, dys)
-    assert max_norm_err(got[0][0], ref[0][0]) <= TOL["bf16"]
-    errs = compare(shape, got, ref, tol=6e-2)
+    errs = compare(shape, got, ref)          # asserts TOL["bf16"] = 2e-2 for every tensor
     _report(shape.name, errs)
-    rel_l2 = lambda a, b: float(np.linalg.norm(a - b) / np.linalg.norm(b))
-    l2 = {"dx": rel_l2(got[1][0], ref[1][0])}
-    for l, (ga, gb) in enumerate(zip(got[2], ref[2])):
-        for k in gb:
-            if np.any(gb[k]):
-                l2[f"L{l}.{k}"] = rel_l2(ga[k], gb[k])
-    worst = max(l2, key=l2.get)
-    print(f"[parity] {shape.name}: worst relative L2 error {worst} = {l2[worst]:.3e}", flush=True)
-    assert l2[worst] <= 5e-2
+    plain = shape.with_(name="tp_share_175b_bf16_plain", fwd_fp16=False)
+    got_plain = gpu_run(plain, params, xs, dys)
+    errs_plain = compare(plain, got_plain, ref, tol=1.0)
+    _report(plain.name, errs_plain)
+    assert max(errs_plain.values()) > 1.5 * max(errs.values())
 
 
 def test_workload4_full_size_decoupled():
     """The decoupled workload at full size in the launch configuration the benchmark
-    times (8 micro-batches, all forwards on one stream then all backwards on another,
-    8 stash slots, one gradient buffer).  The oracle cannot run all 8 micro-batches in
-    test time, so:
-      * micro-batch 0 is checked tensor by tensor against the oracle: y, dx, and the
-        parameter gradients of a single-micro-batch run;
+    times: 8 micro-batches, all forwards on one stream then all backwards on another,
+    8 stash slots, one gradient buffer, PREPARED weight images.  The oracle cannot run all
+    8 micro-batches in test time, so:
+      * the prepared-weights decoupled run (what bench.py times) must equal the raw-weights
+        decoupled run bit for bit: y, dx of every micro-batch and every gradient;
+      * y and dx of every micro-batch in the decoupled run equal coupled
+        single-micro-batch runs bit for bit;
       * the 8-micro-batch gradients must equal, bit for bit, the fp32 sum (in call
         order) of the 8 single-micro-batch gradient buffers -- accumulation is `+=`
         into fp32, so this holds exactly and pins the accumulation semantics;
-      * y and dx of every micro-batch in the decoupled run equal the coupled
-        single-micro-batch runs bit for bit."""
+      * micro-batches 0 and 7 (first and last stash slot) are checked tensor by tensor
+        against the oracle: y, dx, and the parameter gradients of their single runs."""
     shape = W[3]
     n = shape.n_microbatches
     print(f"[case] full {shape}", flush=True)
@@ -296,16 +297,28 @@ def test_workload4_full_size_decoupled():
     dys = [synth.make_dy(shape, 0, m) for m in range(n)]
     bufs = B.StageBuffers(shape, n_stash=n)
     bufs.load_params(params)
+    bufs.prepare()
     ys, dxs, g_all = gpu_run(shape, params, xs, dys, decoupled=True, bufs=bufs)
-    print("[step] decoupled 8 micro-batches done", flush=True)
+    print("[step] decoupled 8 micro-batches on prepared weights done", flush=True)
+    bufs.unprepare()
+    ys_raw, dxs_raw, g_raw = gpu_run(shape, params, xs, dys, decoupled=True, bufs=bufs)
+    for m in range(n):
+        assert np.array_equal(ys[m], ys_raw[m]) and np.array_equal(dxs[m], dxs_raw[m]), m
+    for la, lb in zip(g_all, g_raw):
+        for k in la:
+            assert np.array_equal(la[k], lb[k]), k
+    print("[step] prepared == raw, bit for bit", flush=True)
+    del ys_raw, dxs_raw, g_raw
+    bufs.prepare()
     acc = None
-    g0 = None
+    singles = {}
     for m in range(n):
         y1, dx1, g1 = gpu_run(shape, params, [xs[m]], [dys[m]], decoupled=False, bufs=bufs)
         assert np.array_equal(y1[0], ys[m]) and np.array_equal(dx1[0], dxs[m]), m
         flat = [{k: v.astype(np.float32) for k, v in layer.items()} for layer in g1]
+        if m in (0, n - 1):
+            singles[m] = g1
         if m == 0:
-            g0 = g1
             acc = flat
         else:
             for la, lb in zip(acc, flat):
@@ -314,11 +327,41 @@ def test_workload4_full_size_decoupled():
     for la, lb in zip(acc, g_all):
         for k in la:
             assert np.array_equal(la[k].astype(np.float64), lb[k]), k
-    print("[step] accumulation property holds; running the oracle on micro-batch 0", flush=True)
-    del bufs
+    print("[step] accumulation property holds; running the oracle on micro-batches 0 and 7", flush=True)
+    del bufs, acc, g_all
     torch.cuda.empty_cache()
-    ref = oracle_run(shape, params, xs[:1], dys[:1])
-    _report(shape.name, compare(shape, ([ys[0]], [dxs[0]], g0), ref))
+    for m in (0, n - 1):
+        ref = oracle_run(shape, params, [xs[m]], [dys[m]])
+        _report(f"{shape.name} micro-batch {m}", compare(shape, ([ys[m]], [dxs[m]], singles[m]), ref))
+
+
+def test_boundary_contracts_dx_may_alias_dy_and_backward_keeps_the_stash():
+    """Two promises of the header: dx may alias dy (the backward phase reads dy before the
+    last kernel writes dx), and the backward phase does not modify the stash (running it
+    twice on one stash gives the same bits)."""
+    shape = W[1].with_(name="bf16_contracts", n_layers=2, hidden=512, n_heads=4, head_dim=128, ffn=1024,
+                       seq=256, batch=2, bias_std=0.02, ln_jitter=0.1)
+    print(f"[case] contracts {shape}", flush=True)
+    params, xs, dys = _inputs(shape)
+    bufs = B.StageBuffers(shape)
+    bufs.load_params(params)
+    p = bufs.params()
+    x, dy = B.to_device(xs[0], shape.dtype), B.to_device(dys[0], shape.dtype)
+    y, dx1, dx2 = bufs.act(), bufs.act(), bufs.act()
+    B.gpt_stage_fwd(p, x, bufs.stash[0], y)
+    stash_before = bufs.stash[0].clone()
+    bufs.dparams.zero_()
+    B.gpt_stage_bwd(p, bufs.stash[0], dy, dx1, bufs.dparams)
+    g1 = bufs.dparams.clone()
+    assert torch.equal(bufs.stash[0], stash_before)
+    bufs.dparams.zero_()
+    B.gpt_stage_bwd(p, bufs.stash[0], dy, dx2, bufs.dparams)
+    assert torch.equal(dx1, dx2) and torch.equal(g1, bufs.dparams)
+    alias = dy.clone()
+    bufs.dparams.zero_()
+    B.gpt_stage_bwd(p, bufs.stash[0], alias, alias, bufs.dparams)      # dx written over dy
+    torch.cuda.synchronize()
+    assert torch.equal(alias, dx1) and torch.equal(g1, bufs.dparams)
 
 
 # ------------------------------------------------------- single operations ----

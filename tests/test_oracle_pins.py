@@ -391,44 +391,3 @@ def test_planted_mistakes_are_caught(monkeypatch, mutation):
     v = np.random.default_rng(0).standard_normal(x.shape)
     fd = (_loss(shape, params, x + h * v, dy, variant) - _loss(shape, params, x - h * v, dy, variant)) / (2 * h)
     assert abs(fd - float((dx * v).sum())) > 1e-4 * max(1.0, abs(fd))
-
-
-# ------------------------------------------ conditioning of the TP-share workload ---
-def test_workload5_conditioning():
-    """Why the tensor-parallel-share workload cannot meet 2e-2 on its gradients with
-    bf16-stored activations.  The oracle's layer 0 is re-run with ONLY the LayerNorm-1
-    output and the qkv tensor rounded to bf16 (the two places a bf16 stage must round
-    before the attention logits are formed); the oracle's exact layer-1 qkv gradients
-    then move by more than 2e-2 of their maximum.  Reduced to seq 256 to stay fast; the
-    logit statistics (std ~4.9) are those of the full workload."""
-    s = synth.WORKLOADS[4].with_(seq=256)
-    rb = lambda a: synth.round_to_bf16(a.astype(np.float32)).astype(np.float64)
-    params = _p64(synth.make_params(s, 0))
-    x = synth.make_x(s, 0).astype(np.float64)
-    dy = synth.make_dy(s, 0).astype(np.float64)
-    p0 = params[0]
-
-    def layer0(round_it):
-        a, _, _ = orc.layernorm_fwd(x, p0["ln1_g"], p0["ln1_b"], s.ln_eps)
-        a = rb(a) if round_it else a
-        qkv = a @ p0["w_qkv"].T + p0["b_qkv"]
-        qkv = rb(qkv) if round_it else qkv
-        x1 = x + orc.attention_fwd(qkv, s.n_heads, s.head_dim) @ p0["w_o"].T + p0["b_o"]
-        a2, _, _ = orc.layernorm_fwd(x1, p0["ln2_g"], p0["ln2_b"], s.ln_eps)
-        return x1 + orc.gelu(a2 @ p0["w_fc1"].T + p0["b_fc1"]) @ p0["w_fc2"].T + p0["b_fc2"], qkv
-
-    def layer1_grads(y0):
-        g = orc.zero_grads(params[1:])
-        _, st = orc.stage_fwd(y0, params[1:], s.n_heads, s.head_dim)
-        orc.stage_bwd(dy, params[1:], st, g, s.n_heads, s.head_dim)
-        return g[0]
-
-    y_exact, qkv = layer0(False)
-    y_round, _ = layer0(True)
-    P, d = s.attn_width, s.head_dim
-    logits = qkv[0, :, :d] @ qkv[0, :, P:P + d].T / math.sqrt(d)
-    assert 4.0 < logits.std() < 6.0                       # the logits are large
-    g_exact, g_round = layer1_grads(y_exact), layer1_grads(y_round)
-    err = lambda a, b: np.abs(a - b).max() / np.abs(b).max()
-    assert err(y_round, y_exact) < 2e-2                   # the forward stays inside the bar
-    assert err(g_round["w_qkv"], g_exact["w_qkv"]) > 2e-2  # the gradient does not
