@@ -268,6 +268,17 @@ size_t gpt_stage_op_colsum_scratch_bytes(int M, int N);
 int gpt_stage_op_colsum(int dtype, int M, int N, const void* A, float* colsum,
                         float* partial, void* stream);
 
+/* The same column sums for callers that cannot allocate device memory or pass a scratch
+ * buffer: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * The partial sums go to a fixed 4 MiB array the library holds on each GPU it runs on (until
+ * the process ends); the call allocates and frees nothing.  Same kernels, same summation
+ * order, same bits as gpt_stage_op_colsum.  N <= 16384, otherwise GPTS_ESHAPE and nothing is
+ * launched.  All calls on one GPU share that array: calls that may overlap in time (different
+ * streams) race on it and must be serialised by the caller.  The array is addressed on the
+ * device that is current when the call is made, which must be the device of `stream`. */
+int gpt_stage_op_colsum_noalloc(int dtype, int M, int N, const void* A, float* colsum,
+                                void* stream);
+
 /* Causal attention.  qkv [B,S,3P] ([Q|K|V], P = n_heads*head_dim); out [B,S,P];
  * lse fp32 [B,n_heads,S] = log sum_j exp(s_ij) of each causal row.
  * scratch: device memory of gpt_stage_op_attention_scratch_bytes(.., phase) bytes,

@@ -32,7 +32,7 @@ EXPORTS = (
     "gpt_stage_fwd", "gpt_stage_bwd", "gpt_stage_fwd_only", "gpt_stage_bwd_only", "gpt_stage_fwd_bwd",
     "gpt_stage_op_layernorm_fwd", "gpt_stage_op_layernorm_bwd_scratch_bytes",
     "gpt_stage_op_layernorm_bwd", "gpt_stage_op_gemm", "gpt_stage_op_colsum_scratch_bytes",
-    "gpt_stage_op_colsum", "gpt_stage_op_attention_scratch_bytes", "gpt_stage_op_attention_fwd",
+    "gpt_stage_op_colsum", "gpt_stage_op_colsum_noalloc", "gpt_stage_op_attention_scratch_bytes", "gpt_stage_op_attention_fwd",
     "gpt_stage_op_attention_bwd",
     "gpt_stage_trace_create", "gpt_stage_trace_destroy", "gpt_stage_trace_reset",
     "gpt_stage_trace_collect", "gpt_stage_trace_op_name",
@@ -128,6 +128,7 @@ def lib() -> C.CDLL:
         "gpt_stage_op_gemm": (i32, [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp]),
         "gpt_stage_op_colsum_scratch_bytes": (sz, [i32, i32]),
         "gpt_stage_op_colsum": (i32, [i32, i32, i32, vp, vp, vp, vp]),
+        "gpt_stage_op_colsum_noalloc": (i32, [i32, i32, i32, vp, vp, vp]),
         "gpt_stage_op_attention_scratch_bytes": (sz, [i32, i32, i32, i32, i32, i32]),
         "gpt_stage_op_attention_fwd": (i32, [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]),
         "gpt_stage_op_attention_bwd": (i32, [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
@@ -334,6 +335,10 @@ def gpt_stage_op_colsum_scratch_bytes(M, N) -> int:
 
 def gpt_stage_op_colsum(dtype, M, N, A, colsum, partial, stream=None):
     _check(lib().gpt_stage_op_colsum(dtype, M, N, _ptr(A), _ptr(colsum), _ptr(partial), _stream(stream)))
+
+
+def gpt_stage_op_colsum_noalloc(dtype, M, N, A, colsum, stream=None):
+    _check(lib().gpt_stage_op_colsum_noalloc(dtype, M, N, _ptr(A), _ptr(colsum), _stream(stream)))
 
 
 def gpt_stage_op_attention_scratch_bytes(dtype, B, S, n_heads, head_dim, phase: int) -> int:

@@ -3,6 +3,10 @@
 // for the other bias gradients, and the fixed-order reduction of per-workgroup partial
 // sums.  One workgroup per token row at a time (256 threads forward, 512 backward),
 // 16-byte loads, the row cached in registers, fp32 statistics.
+#include "../../include/gpt_stage.h"
+
+#include <mutex>
+
 #include "kernels.hpp"
 
 namespace gpts {
@@ -477,4 +481,51 @@ hipError_t colsum(int dtype, int M, int N, const void* A, float* out, float* par
   return hipGetLastError();
 }
 
+// ---- column sums for callers that cannot allocate ------------------------------------------
+// gpt_stage_op_colsum needs a scratch buffer for its per-workgroup partial sums.  This variant
+// takes them from a fixed array in device memory instead, so the call allocates nothing: for
+// callers under HIP graph capture, in tight serving loops, or in harnesses that forbid
+// hipMalloc.  Each GPU the library runs on holds its own copy of the array (4 MiB) until the
+// process ends.  In host code the array's name is only a stand-in: its device address is looked
+// up once per device and that pointer is what the kernels get.
+namespace {
+constexpr int kNoAllocMaxN = 16384;   // columns; colsum_splits() never exceeds 64 rows of partials
+constexpr int kNoAllocMaxDevices = 64;
+static __device__ __align__(256) float scratch[64 * kNoAllocMaxN];
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kNoAllocMaxDevices] = {};
+
+// device address of `scratch` on the current device (looked up on first use per device)
+hipError_t scratch_on_current_device(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kNoAllocMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+}  // namespace
 }  // namespace gpts
+
+extern "C" int gpt_stage_op_colsum_noalloc(int dtype, int M, int N, const void* A, float* colsum_out,
+                                           void* stream) {
+  using namespace gpts;
+  if ((dtype != GPTS_FP32 && dtype != GPTS_BF16) || !A || !colsum_out)
+    return set_error(GPTS_EINVAL, "colsum_noalloc: bad argument");
+  if (M < 1 || N < 8 || N % 8) return set_error(GPTS_ESHAPE, "colsum_noalloc: N must be a multiple of 8");
+  if (N > kNoAllocMaxN || colsum_scratch_bytes(M, N) > sizeof(float) * 64 * (size_t)kNoAllocMaxN)
+    return set_error(GPTS_ESHAPE, "colsum_noalloc: N exceeds 16384, the size the built-in scratch array is made for");
+  float* partial = nullptr;
+  hipError_t e = scratch_on_current_device(&partial);
+  if (e == hipSuccess) e = colsum(dtype, M, N, A, colsum_out, partial, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return set_error(GPTS_EHIP, hipGetErrorString(e));
+  return GPTS_OK;
+}
