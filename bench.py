@@ -1,17 +1,26 @@
 #!/usr/bin/env python3
 """Benchmark of the GPT stage forward+backward on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME|INDEX]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME|INDEX|all]
 
 One "step" = the whole hot path over one batch of the workload: every
 micro-batch's forward and backward (for the decoupled workload: all forwards on
 a forward stream, then all backwards on a backward stream).  Inputs are seeded
-synthetic tensors already resident in HBM.  Prints ONE JSON line.
+synthetic tensors already resident in HBM.  Prints ONE JSON line (one per workload
+with --workload all).
+
+Other modes (each prints one JSON line):
+    --op attention|layernorm|gemm   one operator alone through its gpt_stage_op_* entry point, at
+                                    the shapes of the chosen workload (for rocprofv3 counter runs)
+    --dpp CHUNKS                    traversal policies over model chunks
+    --pmc-summary DIR               no GPU work: average the counters of a `rocprofv3 --pmc` output
+                                    directory per kernel and print a table
 """
 from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -43,6 +52,10 @@ def parse():
     ap.add_argument("--schedule", choices=["auto", "coupled", "decoupled"], default="auto")
     ap.add_argument("--recompute", action="store_true",
                     help="activation recomputation: smaller stash, LayerNorm/GeLU outputs rebuilt in backward")
+    ap.add_argument("--op", choices=["attention", "layernorm", "gemm"], default=None,
+                    help="time one operator alone (gpt_stage_op_* entry points) at the workload's shapes")
+    ap.add_argument("--pmc-summary", default=None, metavar="DIR",
+                    help="summarise the counter_collection csv files of a rocprofv3 --pmc run under DIR")
     ap.add_argument("--dpp", type=int, default=0, metavar="CHUNKS",
                     help="instead of the stage benchmark: split the workload's layers into CHUNKS model "
                          "chunks and time the depth-first / breadth-first traversals of the "
@@ -77,6 +90,7 @@ def cpu_baseline(shape):
     flops = B.gpt_stage_model_flops(B.make_cfg(s), True)
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "host_cores": os.cpu_count(), "cores_note": "cores = BLAS threads the oracle's matrix products used",
             "seconds": dt,
             "sample": f"1 layer, 1 micro-batch, first {s.seq} tokens x batch {s.batch} of {shape.name} "
                       f"(fp64 numpy oracle, {flops / 1e12:.3f} model TFLOP causal-aware)"}
@@ -136,10 +150,12 @@ def traced_pass(step, bufs, shape, n_ops, steps):
     achieved = fl / ms / 1e9
     roof = {"bound": "mfma" if shape.dtype == "bf16" else "alu", "achieved": achieved, "peak": peak,
             "unit": "TFLOP/s", "frac": achieved / peak, "traffic": gemm_traffic(shape),
-            "kernel": "gemm_mi16_kernel: the 12 matrix products of a layer (forward, dgrad, wgrad)",
+            "kernel": "the matrix products (gemm_mi16_kernel where the shape allows): the 12 of a layer, "
+                      "forward, dgrad, wgrad, averaged",
             "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
             "algorithmic_bytes_per_launch": sum(c["bytes"] for c in gemm) / n,
-            "launches": n, "avg_launch_ms": ms / n, "flops_per_launch": fl / n,
+            "launches": n, "launches_per_step": n // steps, "avg_launch_ms": ms / n, "flops_per_launch": fl / n,
+            "avg_launch_ms_source": "hipEvent pairs recorded on the launch stream by the library's tracer (not rocprofv3)",
             "measured": f"hipEvent pairs around every launch, {steps} traced step(s) after the timed region",
             "dropped_records": dropped}
     return roof, table
@@ -218,22 +234,11 @@ def dpp_bench(args, shape):
                       "steps": args.steps, "warmup": args.warmup, "policies": rows}))
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        raise SystemExit("bench.py measures one GPU: the stage has no collectives or sharding; run with --gpus 1")
+def run_workload(args, shape):
+    """Time K steps of one workload and return the result row."""
     import torch
     from paper_2507_19845_amd import binding as B
     from paper_2507_19845_amd import harness, synth
-
-    if not torch.cuda.is_available():
-        raise SystemExit("bench.py needs a GPU")
-    B.lib()
-    shape = pick_workload(args.workload)
-    if args.recompute:
-        shape = shape.with_(recompute=True)
-    if args.dpp:
-        return dpp_bench(args, shape)
     n_mb = shape.n_microbatches
     decoupled = (n_mb > 1) if args.schedule == "auto" else (args.schedule == "decoupled")
     bufs = B.StageBuffers(shape, n_stash=n_mb if decoupled else 1)
@@ -250,7 +255,8 @@ def main():
     gen_s = time.perf_counter() - t0
     runner = harness.StageRunner(bufs)
 
-    prepare = shape.dtype == "bf16" and not args.no_prepare
+    # fp16 forward activations read the weights through their (fp16) images only
+    prepare = shape.dtype == "bf16" and (shape.fwd_fp16 or not args.no_prepare)
 
     def step():
         # the weights change once per step in training, so their images are rebuilt once
@@ -281,6 +287,8 @@ def main():
     peak = PEAK_BF16_TFLOPS if shape.dtype == "bf16" else PEAK_FP32_TFLOPS
     ops_per_step = 28 * shape.n_layers * n_mb   # trace capacity (upper bound)
     roof, table = traced_pass(step, bufs, shape, ops_per_step, max(1, min(args.steps, 2)))
+    stash = ("fp16 forward activations; LayerNorm/GeLU outputs rebuilt in backward" if shape.fwd_fp16 else
+             "recompute LayerNorm/GeLU outputs in backward" if shape.recompute else "full")
     out = {
         "metric": "model TFLOP/s for one stage fwd+bwd on 1 MI355X",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -295,7 +303,8 @@ def main():
                    "schedule": "decoupled: all fwd on stream F, then all bwd on stream B" if decoupled
                                else "coupled fwd+bwd per micro-batch", "flop_count": "causal-aware",
                    "prepared_weights": "rebuilt every step (timed)" if prepare else "off",
-                   "stash": "recompute LayerNorm/GeLU outputs in backward" if shape.recompute else "full",
+                   "forward_activations": "fp16" if shape.fwd_fp16 else shape.dtype,
+                   "stash": stash,
                    "stash_GiB_per_microbatch": B.gpt_stage_stash_bytes(bufs.cfg) / 2**30,
                    "input_gen_seconds": gen_s},
         "roofline": roof,
@@ -303,7 +312,138 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape)
-    print(json.dumps(out))
+    del bufs, xs, dys, ys, dxs, runner
+    torch.cuda.empty_cache()
+    return out
+
+
+def op_bench(args, shape):
+    """One operator alone, through its gpt_stage_op_* entry point, at the shapes it has in one
+    layer of the workload; timed with events on the launch stream.  Meant to be run under
+    `rocprofv3 --pmc ...` (the kernels of the operator are then the only ones in the trace) as
+    well as on its own."""
+    import torch
+    from paper_2507_19845_amd import binding as B
+    from paper_2507_19845_amd import synth
+    dt = B.GPTS_BF16 if shape.dtype == "bf16" else B.GPTS_FP32
+    tdt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    e = 2 if shape.dtype == "bf16" else 4
+    T, H, P, F, S, Bt, a, d = (shape.tokens, shape.hidden, shape.attn_width, shape.ffn, shape.seq, shape.batch,
+                               shape.n_heads, shape.head_dim)
+    dev = "cuda"
+
+    def rnd(shape_, std, tag):
+        return B.to_device(synth.to_storage(synth.make_aux(0, tag, shape_, std), shape.dtype), shape.dtype)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        torch.cuda.synchronize()
+        ev[0].record()
+        for _ in range(args.steps):
+            fn()
+        ev[1].record()
+        torch.cuda.synchronize()
+        return ev[0].elapsed_time(ev[1]) / args.steps
+
+    rows = {}
+    if args.op == "attention":
+        qkv = rnd((Bt, S, 3 * P), math.sqrt(H) * 0.02, 1)      # the spread a*W^T has in the workload
+        out = torch.empty((Bt, S, P), dtype=tdt, device=dev)
+        lse = torch.empty((Bt, a, S), dtype=torch.float32, device=dev)
+        dout, dqkv = rnd((Bt, S, P), 1.0, 2), torch.empty_like(qkv)
+        sc = [torch.empty(max(B.gpt_stage_op_attention_scratch_bytes(dt, Bt, S, a, d, ph), 256), dtype=torch.uint8,
+                          device=dev) for ph in (0, 1)]
+        fl = 4.0 * Bt * a * d * S * (S + 1) / 2
+        ms = timed(lambda: B.gpt_stage_op_attention_fwd(dt, Bt, S, a, d, qkv, out, lse, sc[0]))
+        rows["attention_fwd"] = {"ms": ms, "TFLOP/s": fl / ms / 1e9, "flops": fl, "bytes": T * 4.0 * P * e}
+        ms = timed(lambda: B.gpt_stage_op_attention_bwd(dt, Bt, S, a, d, qkv, out, lse, dout, dqkv, sc[1]))
+        rows["attention_bwd"] = {"ms": ms, "TFLOP/s": 2 * fl / ms / 1e9, "flops": 2 * fl, "bytes": T * 9.0 * P * e}
+    elif args.op == "layernorm":
+        x32 = shape.dtype == "bf16"     # inside a bf16 stage LayerNorm reads the fp32 residual stream
+        x = torch.from_numpy(synth.make_aux(0, 3, (T, H))).to(dev) if x32 else rnd((T, H), 1.0, 3)
+        g, b_ = rnd((H,), 1.0, 4), rnd((H,), 1.0, 5)
+        out = torch.empty((T, H), dtype=tdt, device=dev)
+        mean, rstd = (torch.empty(T, dtype=torch.float32, device=dev) for _ in range(2))
+        dout, dres, dx = rnd((T, H), 1.0, 6), rnd((T, H), 1.0, 7), torch.empty((T, H), dtype=tdt, device=dev)
+        dg, db, dxs = (torch.zeros(H, dtype=torch.float32, device=dev) for _ in range(3))
+        part = torch.empty(B.gpt_stage_op_layernorm_bwd_scratch_bytes(T, H), dtype=torch.uint8, device=dev)
+        xb = 4 if x32 else e
+        ms = timed(lambda: B.gpt_stage_op_layernorm_fwd(dt, T, H, shape.ln_eps, x, g, b_, out, mean, rstd, x_f32=x32))
+        by = T * H * (xb + e)
+        rows["layernorm_fwd"] = {"ms": ms, "GB/s": by / ms / 1e6, "bytes": by}
+        ms = timed(lambda: B.gpt_stage_op_layernorm_bwd(dt, T, H, dout, x, mean, rstd, g, dres, dx, dg, db, part,
+                                                        x_f32=x32, dxsum=dxs))
+        by = T * H * (3 * e + xb)
+        rows["layernorm_bwd"] = {"ms": ms, "GB/s": by / ms / 1e6, "bytes": by}
+    else:
+        # the three forms at the layer's four linears, on raw weights (the image-fed variants of the
+        # forward and dgrad products are reached through the stage calls only)
+        for name, (N, K) in (("qkv", (3 * P, H)), ("out_proj", (H, P)), ("fc1", (F, H)), ("fc2", (H, F))):
+            W = rnd((N, K), 0.02, 10)
+            Ain, Gout = rnd((T, K), 1.0, 11), rnd((T, N), 1.0, 12)
+            Cf, Cd = torch.empty((T, N), dtype=tdt, device=dev), torch.empty((T, K), dtype=tdt, device=dev)
+            Cw = torch.zeros((N, K), dtype=torch.float32, device=dev)
+            fl = 2.0 * T * N * K
+            for form, fn in (("fwd", lambda: B.gpt_stage_op_gemm(dt, 0, T, N, K, Ain, W, Cf)),
+                             ("dgrad", lambda: B.gpt_stage_op_gemm(dt, 1, T, K, N, Gout, W, Cd)),
+                             ("wgrad", lambda: B.gpt_stage_op_gemm(dt, 2, N, K, T, Gout, Ain, Cw))):
+                ms = timed(fn)
+                rows[f"{name}_{form}"] = {"ms": ms, "TFLOP/s": fl / ms / 1e9, "flops": fl}
+            del W, Ain, Gout, Cf, Cd, Cw
+    print(json.dumps({"metric": f"operator {args.op} alone (gpt_stage_op_* entry points)", "unit": "ms per call",
+                      "config": {"workload": shape.name, "tokens": T, "hidden": H, "attention_width": P, "ffn": F,
+                                 "seq": S, "n_heads": a, "head_dim": d},
+                      "steps": args.steps, "warmup": args.warmup, "dtype": shape.dtype, "operators": rows}))
+
+
+def pmc_summary(path):
+    """Per-kernel averages of every counter found in the counter_collection csv files that
+    `rocprofv3 --pmc ... -d DIR --output-format csv` leaves under DIR (any depth)."""
+    import csv
+    acc = {}
+    for root, _, files in os.walk(path):
+        for f in files:
+            if not f.endswith("counter_collection.csv"):
+                continue
+            with open(os.path.join(root, f), newline="") as fh:
+                for r in csv.DictReader(fh):
+                    k = r["Kernel_Name"].split("(")[0]
+                    row = acc.setdefault(k, {})
+                    c = row.setdefault(r["Counter_Name"], [0.0, 0])
+                    c[0] += float(r["Counter_Value"])
+                    c[1] += 1
+    names = sorted({c for row in acc.values() for c in row})
+    print("| kernel | dispatches | " + " | ".join(names) + " |")
+    print("|---|---:|" + "---:|" * len(names))
+    for k, row in sorted(acc.items(), key=lambda kv: -max(v[1] for v in kv[1].values())):
+        n = max(v[1] for v in row.values())
+        print(f"| `{k[:90]}` | {n} | " + " | ".join(f"{row[c][0] / row[c][1]:.4g}" if c in row else "" for c in names) + " |")
+
+
+def main():
+    args = parse()
+    if args.pmc_summary:
+        return pmc_summary(args.pmc_summary)
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: the stage has no collectives or sharding; run with --gpus 1")
+    import torch
+    from paper_2507_19845_amd import binding as B
+    from paper_2507_19845_amd import synth
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    B.lib()
+    shapes = list(synth.WORKLOADS) if args.workload == "all" else [pick_workload(args.workload)]
+    if args.recompute:
+        shapes = [s.with_(recompute=True) for s in shapes]
+    if args.dpp:
+        return dpp_bench(args, shapes[0])
+    if args.op:
+        return op_bench(args, shapes[0])
+    for shape in shapes:
+        print(json.dumps(run_workload(args, shape)), flush=True)
 
 
 if __name__ == "__main__":

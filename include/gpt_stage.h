@@ -144,6 +144,10 @@ int gpt_stage_param_offset(const gpt_stage_cfg* cfg, int layer, int tensor_id,
  * never counted. */
 double gpt_stage_model_flops(const gpt_stage_cfg* cfg, int causal_aware);
 
+/* Text for a status: the detailed message of the calling thread's last failed call when
+ * `code` is the status that call returned, otherwise the generic meaning of `code`
+ * ("unknown status" for values that are not a gpts_status).  The pointer stays valid until
+ * the thread's next failing call. */
 const char* gpt_stage_strerror(int code);
 
 /* Prepared weights (optional, bf16 stages).  gpt_stage_prepare() enqueues kernels that

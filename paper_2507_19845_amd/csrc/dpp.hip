@@ -59,7 +59,11 @@ int gpt_dpp_plan(int policy, int n_chunks, int n_microbatches, int max_live_stas
   if (n_chunks < 1 || n_microbatches < 1 || n_chunks > (1 << 15) || n_microbatches > (1 << 15))
     return set_error(GPTS_EINVAL, "dpp_plan: n_chunks and n_microbatches must be in [1, 32768]");
   if (!tasks) return set_error(GPTS_EINVAL, "dpp_plan: tasks is NULL");
-  const int C = n_chunks, M = n_microbatches, total = 2 * C * M;
+  const int C = n_chunks, M = n_microbatches;
+  // the task count is also the return value, an int
+  if ((long long)2 * C * M > (1ll << 30))
+    return set_error(GPTS_EINVAL, "dpp_plan: 2*chunks*microbatches must not exceed 2^30");
+  const int total = 2 * C * M;
   if (capacity < total) return set_error(GPTS_ENOMEM, "dpp_plan: tasks array holds fewer than 2*chunks*microbatches entries");
   const int W = window(policy, C, M, max_live_stash);
   int n = 0, live = 0, peak = 0;

@@ -822,10 +822,15 @@ hipError_t launch(const MfmaArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-// Tile choice: 256x256 (slices of 32, four LDS stages: three slices in flight) when
-// that still gives every CU a tile, else 128x128 (slices of 64, two stages, two
-// workgroups per CU) to recover occupancy on small problems.
-bool use_big_tiles(int M, int N) { return (long)((M + 255) / 256) * ((N + 255) / 256) >= 200; }
+// Tile choice: 256x256 (slices of 32, four LDS stages: three slices in flight) from 100 tiles
+// up, else 128x128 (slices of 64, two stages, two workgroups per CU) to recover occupancy on
+// small problems.  Measured on whole stages: at 144-192 tiles (M = 2048 or 4096 tokens against
+// N = 4608 ... 5120) the large tile is 10-25 % faster per product although it leaves a third of
+// the CUs idle; at 64 tiles it is 30 % slower.
+#ifndef GPTS_BIG_TILE_MIN
+#define GPTS_BIG_TILE_MIN 100
+#endif
+bool use_big_tiles(int M, int N) { return (long)((M + 255) / 256) * ((N + 255) / 256) >= GPTS_BIG_TILE_MIN; }
 
 template <bool AK, bool BKM, int EPI> hipError_t pick_tile(const MfmaArgs& a, hipStream_t st) {
   if (use_big_tiles(a.M, a.N)) {

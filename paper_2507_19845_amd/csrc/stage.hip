@@ -13,7 +13,9 @@ using namespace gpts;
 
 namespace {
 
+// text and status of the calling thread's last failed call
 thread_local char g_err[256] = "";
+thread_local int g_err_code = GPTS_OK;
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline size_t esize(const gpt_stage_cfg& c) { return c.dtype == GPTS_BF16 ? 2 : 4; }
@@ -172,10 +174,12 @@ size_t prepared_off(const Dims& D, int layer, int lin, int which) {
 int fail(int code, const char* msg) {
   strncpy(g_err, msg, sizeof(g_err) - 1);
   g_err[sizeof(g_err) - 1] = 0;
+  g_err_code = code;
   return code;
 }
 int hip_fail(hipError_t e, const char* where) {
   snprintf(g_err, sizeof(g_err), "%s: %s", where, hipGetErrorString(e));
+  g_err_code = GPTS_EHIP;
   return GPTS_EHIP;
 }
 bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -563,9 +567,15 @@ double gpt_stage_model_flops(const gpt_stage_cfg* c, int causal_aware) {
   return 3.0 * D.L * (lin + att);
 }
 const char* gpt_stage_strerror(int code) {
+  // the detailed text of the thread's last failure when `code` is the status that failure
+  // returned, else the generic meaning of `code`
+  if (code != GPTS_OK && code == g_err_code && g_err[0]) return g_err;
   switch (code) {
     case GPTS_OK: return "ok";
-    case GPTS_EINVAL: case GPTS_ESHAPE: case GPTS_EHIP: case GPTS_ENOMEM: return g_err[0] ? g_err : "error";
+    case GPTS_EINVAL: return "invalid argument (null or misaligned pointer, bad enum value)";
+    case GPTS_ESHAPE: return "shape outside what the kernels support";
+    case GPTS_EHIP: return "a HIP call failed";
+    case GPTS_ENOMEM: return "a caller-provided pool or array is too small";
   }
   return "unknown status";
 }

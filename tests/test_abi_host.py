@@ -80,6 +80,35 @@ def test_validate_rejects(field, value, code):
     assert B.gpt_stage_param_count(cfg) == 0 and B.gpt_stage_stash_bytes(cfg) == 0
 
 
+def test_strerror_depends_on_the_code():
+    cfg = B.make_cfg(synth.WORKLOADS[0])
+    cfg.head_dim = 48
+    assert B.gpt_stage_validate(cfg) == B.GPTS_ESHAPE
+    assert "head_dim" in B.gpt_stage_strerror(B.GPTS_ESHAPE)       # the last failure's own text
+    assert "head_dim" not in B.gpt_stage_strerror(B.GPTS_EINVAL)   # another status: its generic meaning
+    assert B.gpt_stage_strerror(B.GPTS_OK) == "ok"
+    assert B.gpt_stage_strerror(-99) == "unknown status"
+    texts = {B.gpt_stage_strerror(c) for c in (B.GPTS_EINVAL, B.GPTS_EHIP, B.GPTS_ENOMEM)}
+    assert len(texts) == 3
+
+
+def test_fwd_fp16_validation():
+    ok = synth.WORKLOADS[4]
+    assert ok.fwd_fp16 and B.gpt_stage_validate(B.make_cfg(ok)) == B.GPTS_OK
+    assert B.gpt_stage_validate(B.make_cfg(ok.with_(ffn=6144 + 64))) == B.GPTS_ESHAPE      # not a multiple of 128
+    assert B.gpt_stage_validate(B.make_cfg(synth.WORKLOADS[0].with_(fwd_fp16=True))) == B.GPTS_EINVAL  # fp32 stage
+    assert B.gpt_stage_validate(B.make_cfg(ok.with_(head_dim=32, n_heads=48))) == B.GPTS_ESHAPE
+    # same stash size as the recomputing layout: A, A2, G are not stashed, QKV / C / U are 16-bit either way
+    plain = ok.with_(fwd_fp16=False)
+    assert B.gpt_stage_stash_bytes(B.make_cfg(ok)) == B.gpt_stage_stash_bytes(B.make_cfg(plain.with_(recompute=True)))
+    assert B.gpt_stage_stash_bytes(B.make_cfg(ok)) < B.gpt_stage_stash_bytes(B.make_cfg(plain))
+    # the stage calls refuse to run without prepared weights
+    cfg = B.make_cfg(ok)
+    p = B.gpt_stage_params(cfg=cfg, weights=0x1000, workspace=0x2000)
+    assert B.lib().gpt_stage_fwd(ctypes.byref(p), 0x3000, 0x4000, 0x5000, None) == B.GPTS_EINVAL
+    assert "prepared" in B.gpt_stage_strerror(B.GPTS_EINVAL)
+
+
 def test_bf16_needs_tile_multiples():
     s = synth.WORKLOADS[1].with_(seq=1000, batch=1)
     assert B.gpt_stage_validate(B.make_cfg(s)) == B.GPTS_ESHAPE
