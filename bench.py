@@ -50,6 +50,10 @@ def parse():
     ap.add_argument("--no-prepare", action="store_true",
                     help="run the products on the raw weights instead of the prepared images")
     ap.add_argument("--schedule", choices=["auto", "coupled", "decoupled"], default="auto")
+    ap.add_argument("--wgrad", choices=["auto", "flush", "per-microbatch"], default="auto",
+                    help="decoupled schedule: weight gradients in one weight phase after all backward data "
+                         "phases (flush; auto picks it when there are several micro-batches) or inside every "
+                         "micro-batch's backward call")
     ap.add_argument("--recompute", action="store_true",
                     help="activation recomputation: smaller stash, LayerNorm/GeLU outputs rebuilt in backward")
     ap.add_argument("--op", choices=["attention", "layernorm", "gemm"], default=None,
@@ -254,6 +258,7 @@ def run_workload(args, shape):
     dxs = [bufs.act() for _ in range(n_mb)]
     gen_s = time.perf_counter() - t0
     runner = harness.StageRunner(bufs)
+    split = decoupled and n_mb > 1 and args.wgrad != "per-microbatch"
 
     # fp16 forward activations read the weights through their (fp16) images only
     prepare = shape.dtype == "bf16" and (shape.fwd_fp16 or not args.no_prepare)
@@ -264,7 +269,7 @@ def run_workload(args, shape):
         if prepare:
             bufs.prepare()
         if decoupled:
-            runner.decoupled(xs, dys, ys, dxs)
+            runner.decoupled(xs, dys, ys, dxs, split_wgrad=split)
         else:
             runner.coupled(xs, dys, ys, dxs)
 
@@ -302,6 +307,10 @@ def run_workload(args, shape):
                    "seq": shape.seq, "micro_batch": shape.batch, "n_microbatches": n_mb,
                    "schedule": "decoupled: all fwd on stream F, then all bwd on stream B" if decoupled
                                else "coupled fwd+bwd per micro-batch", "flop_count": "causal-aware",
+                   "weight_gradients": "one weight phase over all micro-batches after their backward data phases "
+                                       "(gpt_stage_bwd_data_only x n, gpt_stage_wgrad_flush)" if split
+                                       else "inside every micro-batch's backward call",
+                   "grad_stash_GiB_per_microbatch": B.gpt_stage_grad_stash_bytes(bufs.cfg) / 2**30 if split else 0.0,
                    "prepared_weights": "rebuilt every step (timed)" if prepare else "off",
                    "forward_activations": "fp16" if shape.fwd_fp16 else shape.dtype,
                    "stash": stash,

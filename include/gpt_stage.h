@@ -195,6 +195,34 @@ int gpt_stage_fwd_only(const gpt_stage_params* p, const void* x, void* act_stash
 int gpt_stage_bwd_only(const gpt_stage_params* p, const void* act_stash, const void* dy,
                        void* dx, void* dparams, void* stream, void* wait_event);
 
+/* Backward phase split into a data phase and a weight phase (section 5.2: with a breadth-first
+ * traversal a chunk's weight gradients are only needed once ALL its micro-batches have been
+ * through it, which is when its gradient exchange starts).
+ *
+ * gpt_stage_bwd_data_only: gpt_stage_bwd_only without the weight-gradient products.  Writes dx,
+ * adds the bias and LayerNorm parameter gradients to dparams (exactly as gpt_stage_bwd does),
+ * and leaves in grad_stash (device, gpt_stage_grad_stash_bytes(), one per in-flight
+ * micro-batch, written, opaque) the output gradients of every linear layer.  The activation
+ * stash must stay alive until the weight phase has run.
+ *
+ * gpt_stage_wgrad_flush: the weight phase for n micro-batches at once: for every linear layer
+ * dW += sum_m (output gradient of micro-batch m)^T (its input activation), added to dparams.
+ * act_stashes / grad_stashes are HOST arrays of n device pointers.  When the n buffers of each
+ * kind are equally spaced in memory (e.g. slices of one allocation), the stash holds the
+ * activations (no recompute, no fwd_fp16) and the shape suits the 256x256 tiles, each linear
+ * is ONE product contracting over all micro-batches' tokens: the fp32 gradient matrix is read
+ * and written once instead of n times.  Otherwise it is one accumulating product per
+ * micro-batch, as in gpt_stage_bwd.  Same mathematics either way; the fp32 summation order
+ * over tokens differs from n separate calls of gpt_stage_bwd.  Needs p->workspace of
+ * workspace_bytes(cfg, 1).  Deterministic. */
+size_t gpt_stage_grad_stash_bytes(const gpt_stage_cfg* cfg);
+int gpt_stage_bwd_data_only(const gpt_stage_params* p, const void* act_stash, const void* dy,
+                            void* dx, void* dparams, void* grad_stash, void* stream,
+                            void* wait_event);
+int gpt_stage_wgrad_flush(const gpt_stage_params* p, int n_microbatches,
+                          const void* const* act_stashes, const void* const* grad_stashes,
+                          void* dparams, void* stream);
+
 /* Coupled convenience: forward then backward of one micro-batch on one stream.
  * p->workspace must hold max(workspace_bytes(cfg,0), workspace_bytes(cfg,1)). */
 int gpt_stage_fwd_bwd(const gpt_stage_params* p, const void* x, const void* dy,

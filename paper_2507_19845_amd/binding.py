@@ -30,6 +30,7 @@ EXPORTS = (
     "gpt_stage_stash_bytes", "gpt_stage_workspace_bytes", "gpt_stage_param_offset",
     "gpt_stage_model_flops", "gpt_stage_strerror", "gpt_stage_prepared_bytes", "gpt_stage_prepare",
     "gpt_stage_fwd", "gpt_stage_bwd", "gpt_stage_fwd_only", "gpt_stage_bwd_only", "gpt_stage_fwd_bwd",
+    "gpt_stage_grad_stash_bytes", "gpt_stage_bwd_data_only", "gpt_stage_wgrad_flush",
     "gpt_stage_op_layernorm_fwd", "gpt_stage_op_layernorm_bwd_scratch_bytes",
     "gpt_stage_op_layernorm_bwd", "gpt_stage_op_gemm", "gpt_stage_op_colsum_scratch_bytes",
     "gpt_stage_op_colsum", "gpt_stage_op_colsum_noalloc", "gpt_stage_op_attention_scratch_bytes", "gpt_stage_op_attention_fwd",
@@ -122,6 +123,9 @@ def lib() -> C.CDLL:
         "gpt_stage_fwd_only": (i32, [parp, vp, vp, vp, vp, vp]),
         "gpt_stage_bwd_only": (i32, [parp, vp, vp, vp, vp, vp, vp]),
         "gpt_stage_fwd_bwd": (i32, [parp, vp, vp, vp, vp, vp, vp, vp]),
+        "gpt_stage_grad_stash_bytes": (sz, [cfgp]),
+        "gpt_stage_bwd_data_only": (i32, [parp, vp, vp, vp, vp, vp, vp, vp]),
+        "gpt_stage_wgrad_flush": (i32, [parp, i32, C.POINTER(vp), C.POINTER(vp), vp, vp]),
         "gpt_stage_op_layernorm_fwd": (i32, [i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp]),
         "gpt_stage_op_layernorm_bwd_scratch_bytes": (sz, [i32, i32]),
         "gpt_stage_op_layernorm_bwd": (i32, [i32, i32, i32, i32] + [vp] * 12),
@@ -268,6 +272,24 @@ def gpt_stage_bwd_only(p: gpt_stage_params, act_stash, dy, dx, dparams, stream=N
     ev = _event(wait_event)
     _check(lib().gpt_stage_bwd_only(C.byref(p), _ptr(act_stash), _ptr(dy), _ptr(dx), _ptr(dparams),
                                     _stream(stream), ev))
+
+
+def gpt_stage_grad_stash_bytes(cfg) -> int:
+    return lib().gpt_stage_grad_stash_bytes(C.byref(cfg))
+
+
+def gpt_stage_bwd_data_only(p: gpt_stage_params, act_stash, dy, dx, dparams, grad_stash, stream=None,
+                            wait_event: Optional[torch.cuda.Event] = None) -> None:
+    ev = _event(wait_event)
+    _check(lib().gpt_stage_bwd_data_only(C.byref(p), _ptr(act_stash), _ptr(dy), _ptr(dx), _ptr(dparams),
+                                         _ptr(grad_stash), _stream(stream), ev))
+
+
+def gpt_stage_wgrad_flush(p: gpt_stage_params, act_stashes, grad_stashes, dparams, stream=None) -> None:
+    n = len(act_stashes)
+    assert len(grad_stashes) == n
+    a, g = (C.c_void_p * n)(*[_ptr(t) for t in act_stashes]), (C.c_void_p * n)(*[_ptr(t) for t in grad_stashes])
+    _check(lib().gpt_stage_wgrad_flush(C.byref(p), n, a, g, _ptr(dparams), _stream(stream)))
 
 
 def gpt_stage_fwd_bwd(p: gpt_stage_params, x, dy, act_stash, y, dx, dparams, stream=None) -> None:
@@ -512,13 +534,25 @@ class StageBuffers:
         self.n_param = gpt_stage_param_count(self.cfg)
         self.weights = torch.zeros(self.n_param, dtype=self.tdtype, device=device)
         self.dparams = torch.zeros(self.n_param, dtype=torch.float32, device=device)
-        self.stash = [torch.empty(gpt_stage_stash_bytes(self.cfg), dtype=torch.uint8, device=device)
-                      for _ in range(n_stash)]
+        # the slots are slices of one allocation, equally spaced: what the weight phase
+        # (gpt_stage_wgrad_flush) needs to contract over all micro-batches in one product
+        sb = gpt_stage_stash_bytes(self.cfg)
+        self._stash_all = torch.empty(sb * n_stash, dtype=torch.uint8, device=device)
+        self.stash = [self._stash_all[i * sb:(i + 1) * sb] for i in range(n_stash)]
+        self.grad_stash: List[torch.Tensor] = []        # filled by alloc_grad_stash()
         wb = max(gpt_stage_workspace_bytes(self.cfg, 0), gpt_stage_workspace_bytes(self.cfg, 1), 256)
         self.workspace = torch.empty(wb, dtype=torch.uint8, device=device)
         self.prepared: Optional[torch.Tensor] = None    # passed as params.prepared when set
         self._prepared_buf: Optional[torch.Tensor] = None
         self.trace: Optional[int] = None                # tracer handle passed as params.trace
+
+    def alloc_grad_stash(self, n: int) -> None:
+        """n gradient-stash slots (slices of one allocation) for the split backward phase."""
+        if len(self.grad_stash) >= n:
+            return
+        gb = gpt_stage_grad_stash_bytes(self.cfg)
+        self._grad_all = torch.empty(gb * n, dtype=torch.uint8, device=self.device)
+        self.grad_stash = [self._grad_all[i * gb:(i + 1) * gb] for i in range(n)]
 
     def params(self) -> gpt_stage_params:
         """gpt_stage_params for the stage calls: this object's weights and workspace, the

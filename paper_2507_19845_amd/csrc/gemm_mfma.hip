@@ -62,6 +62,11 @@ struct MfmaArgs {
   bf16* gelu_out;
   const bf16* dgelu_u;
   float* colsum;   // GeLU' epilogue only, may be null: per-wave-row column sums of C
+  // K-major products only (weight gradients): the contraction runs over `k_segments` pieces of
+  // K rows each (K is then the length of ONE piece), piece s of A starting seg_stride_a elements
+  // after piece s-1, likewise B: the tokens of several micro-batches, each in its own buffer.
+  int k_segments = 1;
+  size_t seg_stride_a = 0, seg_stride_b = 0;
 };
 
 // 16-byte chunk swizzle of a K-contiguous tile row with CPR chunks per row.  Chosen
@@ -148,6 +153,13 @@ template <int R, int WR, int BK, bool KMAJOR, bool NAT, bool IMG = false, int NW
   __device__ __forceinline__ void issue_one(const bf16* __restrict__ X, size_t ld, int kt,
                                             uint32_t lds_tile, int wave, int i) const {
     const bf16* base = IMG ? X + (size_t)kt * R * BK : (KMAJOR ? X + (size_t)kt * BK * ld : X + (size_t)kt * BK);
+    const uint32_t dst = lds_tile + (wave * NI + i) * 1024;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 ::"s"(dst), "v"(goff[i]), "s"(base)
+                 : "memory");
+  }
+  // the same with the slice's base address given (X advanced to the slice by the caller)
+  __device__ __forceinline__ void issue_at(const bf16* __restrict__ base, uint32_t lds_tile, int wave, int i) const {
     const uint32_t dst = lds_tile + (wave * NI + i) * 1024;
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  ::"s"(dst), "v"(goff[i]), "s"(base)
@@ -702,7 +714,8 @@ __global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
   const int gsz = min(tiles_m - first_m, GROUP);
   const int tm_i = first_m + (id % per_group) % gsz, tn_i = (id % per_group) / gsz;
   const int m0 = tm_i * BM, n0 = tn_i * BN;
-  const int nk = a.K / BK;                      // a multiple of 4 (checked by the dispatcher)
+  const int sps = a.K / BK;                     // slices per K segment: a multiple of 4 (checked by the dispatcher)
+  const int nk = sps * a.k_segments;
 
   const size_t lda = KM ? (size_t)a.M : (size_t)a.K, ldb = KM ? (size_t)a.N : (size_t)a.K;
   Operand<BM, WM, BK, KM, true, false, NW> opA;
@@ -744,15 +757,44 @@ __global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
 
   agpr_clear_all();
 
+  // K-major operands may come in segments (see MfmaArgs): the slice being fetched is tracked by
+  // its base addresses, advanced once per slice with wave-uniform arithmetic -- one slice down
+  // inside a segment, to the next segment's start at its end.  The first NS-1 slices lie in the
+  // first segment (a segment has at least 4 slices).
+  const bf16* fillA = a.A;
+  const bf16* fillB = a.B;
+  int fill_slice = 0, fill_in_seg = 0;
+  auto advance_fill = [&]() {
+    if constexpr (KM) {
+      if (fill_slice < nk - 1) {     // past the end the last slice is fetched again (redundant, branch-free loop)
+        ++fill_slice;
+        if (++fill_in_seg == sps) {
+          fill_in_seg = 0;
+          fillA += a.seg_stride_a - (size_t)(sps - 1) * BK * lda;
+          fillB += a.seg_stride_b - (size_t)(sps - 1) * BK * ldb;
+        } else {
+          fillA += (size_t)BK * lda;
+          fillB += (size_t)BK * ldb;
+        }
+      }
+    }
+  };
   auto dma = [&](int slice, int stage, int i) {   // DMA instruction i of a slice: A first, then B
-    const int sl = min(slice, nk - 1);
-    if (i < NIA) opA.issue_one(a.A, lda, sl, lds_base + stage * STAGE, wave, i);
-    else opB.issue_one(a.B, ldb, sl, lds_base + stage * STAGE + A_BYTES, wave, i - NIA);
+    if constexpr (KM) {
+      if (i < NIA) opA.issue_at(fillA, lds_base + stage * STAGE, wave, i);
+      else opB.issue_at(fillB, lds_base + stage * STAGE + A_BYTES, wave, i - NIA);
+    } else {
+      const int sl = min(slice, nk - 1);
+      if (i < NIA) opA.issue_one(a.A, lda, sl, lds_base + stage * STAGE, wave, i);
+      else opB.issue_one(a.B, ldb, sl, lds_base + stage * STAGE + A_BYTES, wave, i - NIA);
+    }
   };
 #pragma unroll
-  for (int s0 = 0; s0 < NS - 1; ++s0)
+  for (int s0 = 0; s0 < NS - 1; ++s0) {
 #pragma unroll
     for (int i = 0; i < N_DMA; ++i) dma(s0, s0, i);
+    advance_fill();
+  }
   wait_dma_and_barrier<(NS - 2) * N_DMA>();   // slice 0 has landed
 #pragma unroll
   for (int u = 0; u < NB; ++u) {
@@ -785,6 +827,7 @@ __global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
         if constexpr (g % 2 == 1) dma(t + NS - 1, st_fill, g / 2);
         __builtin_amdgcn_sched_barrier(0);
       });
+      advance_fill();
     });
   }
   // no DMA may still be writing LDS when the staging starts; the matrix pipeline must have
@@ -905,6 +948,13 @@ bool gemm_mfma_supported(int form, int M, int N, int K) {
          (size_t)M * K < (1ull << 31) && (size_t)N * K < (1ull << 31);
 }
 
+// A weight-gradient product whose contraction is split over several buffers runs as one launch
+// of the 16x16x32 K-major kernel: the shape must be one that kernel takes (K here is the
+// length of one segment).
+bool gemm_wgrad_segments_supported(int form, int M, int N, int K) {
+  return form == 2 && gemm_mfma_supported(form, M, N, K) && use_big_tiles(M, N) && K % 128 == 0;
+}
+
 int gemm_mfma_colsum_rows(int M, int N) {
   const int bm = use_big_tiles(M, N) ? 256 : 128;
   return 2 * ((M + bm - 1) / bm);
@@ -956,6 +1006,13 @@ hipError_t gemm_mfma(int form, int M, int N, int K, const void* A, const void* B
   a.bias = (const bf16*)ep.bias; a.residual = ep.residual;
   a.gelu_out = (bf16*)ep.gelu_out; a.dgelu_u = (const bf16*)ep.dgelu_u;
   a.colsum = ep.dgelu_u ? ep.colsum_partial : nullptr;
+  if (ep.k_segments > 1) {
+    if (!gemm_wgrad_segments_supported(form, M, N, K)) return hipErrorInvalidValue;
+    a.k_segments = ep.k_segments;
+    a.seg_stride_a = ep.seg_stride_a;
+    a.seg_stride_b = ep.seg_stride_b;
+    return launch_mi16<EPI_ACCUM, false, true>(a, st);
+  }
   if (ep.b_image && form != 2 && use_big_tiles(M, N)) {
     // B comes as the image of its [N rows, K] K-contiguous view: forward and dgrad are
     // then the same product with different epilogues.

@@ -46,6 +46,11 @@ struct GemmEpilogue {
                                    // over the rows is sum_m C[m, :]
   const void* b_image = nullptr;   // forms 0/1, bf16: B re-laid-out by gemm_prepare_image() as the
                                    // tiled image of its [N rows, K contiguous] view (optional)
+  // form 2, bf16 MFMA path only (gemm_wgrad_segments_supported): the contraction runs over
+  // k_segments pieces of K rows each; piece s of A (B) starts seg_stride_a (seg_stride_b)
+  // ELEMENTS after piece s-1.  One launch, one read-modify-write of C.
+  int k_segments = 1;
+  size_t seg_stride_a = 0, seg_stride_b = 0;
 };
 // form 0: C[M,N] = A[M,K] B[N,K]^T ; form 1: C[M,N] = A[M,K] B[K,N] ;
 // form 2: Cf32[M,N] += A[K,M]^T B[K,N].
@@ -69,6 +74,7 @@ hipError_t gemm_fwd_f16(int M, int N, int K, const void* A, const void* b_image,
                         const GemmEpilogue& ep, hipStream_t st);
 hipError_t gemm_mfma(int form, int M, int N, int K, const void* A, const void* B, void* C,
                      const GemmEpilogue& ep, hipStream_t st);
+bool gemm_wgrad_segments_supported(int form, int M, int N, int K);
 // rows of GemmEpilogue::colsum_partial that gemm_mfma() writes for an [M,N] product
 int gemm_mfma_colsum_rows(int M, int N);
 

@@ -148,6 +148,26 @@ BwdWs bwd_ws(const gpt_stage_cfg& c) {
   return w;
 }
 
+// ---- gradient stash of one micro-batch (backward split into a data and a weight phase):
+// per layer the output gradients of its four linears, the operands the weight-gradient
+// products need besides the activation stash:  dY [T,H]  dU [T,F]  dX1 [T,H]  dQKV [T,3P]
+struct GradStashLayer {
+  size_t dY, dU, dX1, dQKV, end;
+};
+GradStashLayer grad_stash_layer(const gpt_stage_cfg& c) {
+  Dims D(c);
+  const size_t e = esize(c);
+  GradStashLayer s;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
+  s.dY = take((size_t)D.T * D.H * e);
+  s.dU = take((size_t)D.T * D.F * e);
+  s.dX1 = take((size_t)D.T * D.H * e);
+  s.dQKV = take((size_t)D.T * 3 * D.P * e);
+  s.end = o;
+  return s;
+}
+
 // ---- prepared weights: per layer and linear (qkv, out-proj, fc1, fc2) the forward
 // image ([out rows, in]) followed by the dgrad image ([in rows, out]) ---------------------
 struct LinDims { int out, in, wid; };
@@ -360,8 +380,11 @@ int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, 
   return GPTS_OK;
 }
 
+// grad_stash != nullptr: data phase only -- the four weight-gradient products of every layer
+// (and the rebuilding of their activation operands) are left out and the output gradients
+// they need are written into grad_stash instead of the workspace.
 int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, void* dx,
-            void* dparams, hipStream_t st) {
+            void* dparams, hipStream_t st, void* grad_stash = nullptr) {
   int rc = check_call(p);
   if (rc != GPTS_OK) return rc;
   if ((rc = need_prepared(p)) != GPTS_OK) return rc;
@@ -390,6 +413,10 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
   void* dC = wk + ws.dC;
   void* dQKV = wk + ws.dQKV;
   void* attn_scratch = wk + ws.attn;
+  const bool data_only = grad_stash != nullptr;
+  if (data_only && misaligned(grad_stash)) return fail(GPTS_EINVAL, "grad_stash not 16-byte aligned");
+  const GradStashLayer gl = grad_stash_layer(c);
+  char* gs = static_cast<char*>(grad_stash);
 
   // algorithmic work of one operator, for the tracer: flops of an M x N x K product and
   // the bytes it must move (operands once, result once)
@@ -401,11 +428,24 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     return prep ? (const void*)(prep + prepared_off(D, l, lin, 1)) : nullptr;
   };
   const void* dY = dy;
+  if (data_only) {
+    // the top layer's output gradient is the caller's buffer: keep a copy for the weight phase
+    void* top = gs + (size_t)(D.L - 1) * gl.end + gl.dY;
+    GPTS_TRY(hipMemcpyAsync(top, dy, (size_t)D.T * D.H * e, hipMemcpyDeviceToDevice, st), "copy dy");
+    dY = top;
+  }
   for (int l = D.L - 1; l >= 0; --l) {
     const char* s = stash + (size_t)l * sl.end;
     const float* stat1 = reinterpret_cast<const float*>(s + sl.stat1);
     const float* stat2 = reinterpret_cast<const float*>(s + sl.stat2);
     void* dXout = (l == 0) ? dx : (void*)(wk + (((D.L - 1 - l) & 1) ? ws.pong : ws.ping));
+    if (data_only) {
+      char* g0 = gs + (size_t)l * gl.end;
+      dU = g0 + gl.dU;
+      dX1 = g0 + gl.dX1;
+      dQKV = g0 + gl.dQKV;
+      if (l > 0) dXout = gs + (size_t)(l - 1) * gl.end + gl.dY;   // the layer below reads it as its dY
+    }
     GemmEpilogue none;
     GemmEpilogue d_fc1, d_o, d_qkv;   // plain dgrads, each with the image of its weight
     d_fc1.b_image = img(l, 2);
@@ -435,11 +475,12 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     if (fused_b1)
       GPTS_OP(GPTS_TR_BIAS_GRAD, 2, 1, 0.0, (double)cs_rows * D.F * 4, reduce_colsum_partials(cs_part, cs_rows, D.F, g(l, GPTS_B_FC1), st), "fc1 bias grad (partials from the fc2 dgrad epilogue)");
     const void* G = s + sl.G;
-    if (rebuild) {
+    if (rebuild && !data_only) {
       GPTS_OP(GPTS_TR_RECOMPUTE, 2, 1, 0.0, (double)D.T * D.F * 2 * e, gelu_fwd(dt, c.gelu, s + sl.U, wk + ws.rG, (size_t)D.T * D.F, st, h16), "gelu recompute");
       G = wk + ws.rG;
     }
-    GPTS_OP(GPTS_TR_GEMM_WGRAD, 3, 1, gf(D.H, D.F, D.T), gb(D.H, D.F, D.T, 8), gemm(dt, 2, D.H, D.F, D.T, dY, G, g(l, GPTS_W_FC2), none, st), "fc2 wgrad");
+    if (!data_only)
+      GPTS_OP(GPTS_TR_GEMM_WGRAD, 3, 1, gf(D.H, D.F, D.T), gb(D.H, D.F, D.T, 8), gemm(dt, 2, D.H, D.F, D.T, dY, G, g(l, GPTS_W_FC2), none, st), "fc2 wgrad");
     // the bias gradient of fc2 is the column sum of the layer's incoming gradient: below the
     // top layer the LayerNorm backward that produced that gradient has summed it already
     if (l == c.n_layers - 1)
@@ -447,13 +488,14 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     // u = a2 W1^T + b1
     GPTS_OP(GPTS_TR_GEMM_DGRAD, 2, 1, gf(D.T, D.H, D.F), gb(D.T, D.H, D.F, e), gemm(dt, 1, D.T, D.H, D.F, dU, w(l, GPTS_W_FC1), dA, d_fc1, st), "fc1 dgrad");
     const void* A2 = s + sl.A2;
-    if (rebuild) {
+    if (rebuild && !data_only) {
       float* rs = reinterpret_cast<float*>(wk + ws.rstat);
       GPTS_OP(GPTS_TR_RECOMPUTE, 1, 1, 0.0, TH * (kResBytes + e), ln_fwd(dt, dt == GPTS_BF16, D.T, D.H, c.ln_eps, s + sl.X1, w(l, GPTS_LN2_G), w(l, GPTS_LN2_B),
                       wk + ws.rA, rs, rs + D.T, st), "ln2 recompute");
       A2 = wk + ws.rA;
     }
-    GPTS_OP(GPTS_TR_GEMM_WGRAD, 2, 1, gf(D.F, D.H, D.T), gb(D.F, D.H, D.T, 8), gemm(dt, 2, D.F, D.H, D.T, dU, A2, g(l, GPTS_W_FC1), none, st), "fc1 wgrad");
+    if (!data_only)
+      GPTS_OP(GPTS_TR_GEMM_WGRAD, 2, 1, gf(D.F, D.H, D.T), gb(D.F, D.H, D.T, 8), gemm(dt, 2, D.F, D.H, D.T, dU, A2, g(l, GPTS_W_FC1), none, st), "fc1 wgrad");
     if (!fused_b1)
       GPTS_OP(GPTS_TR_BIAS_GRAD, 2, 1, 0.0, (double)D.T * D.F * e, colsum(dt, D.T, D.F, dU, g(l, GPTS_B_FC1), cs_part, st), "fc1 bias grad");
     // a2 = LN2(x1), x1 also feeds the residual
@@ -464,12 +506,14 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     const void* Cb = s + sl.C;
     const void* QKVb = s + sl.QKV;
     if (h16) {
-      GPTS_OP(GPTS_TR_CONVERT, 1, 1, 0.0, (double)D.T * D.P * 2 * e, f16_to_bf16(s + sl.C, wk + ws.bC, (size_t)D.T * D.P, st), "c to bf16");
+      if (!data_only)
+        GPTS_OP(GPTS_TR_CONVERT, 1, 1, 0.0, (double)D.T * D.P * 2 * e, f16_to_bf16(s + sl.C, wk + ws.bC, (size_t)D.T * D.P, st), "c to bf16");
       GPTS_OP(GPTS_TR_CONVERT, 0, 1, 0.0, (double)D.T * 3 * D.P * 2 * e, f16_to_bf16(s + sl.QKV, wk + ws.bQKV, (size_t)D.T * 3 * D.P, st), "qkv to bf16");
       Cb = wk + ws.bC;
       QKVb = wk + ws.bQKV;
     }
-    GPTS_OP(GPTS_TR_GEMM_WGRAD, 1, 1, gf(D.H, D.P, D.T), gb(D.H, D.P, D.T, 8), gemm(dt, 2, D.H, D.P, D.T, dX1, Cb, g(l, GPTS_W_O), none, st), "out-proj wgrad");
+    if (!data_only)
+      GPTS_OP(GPTS_TR_GEMM_WGRAD, 1, 1, gf(D.H, D.P, D.T), gb(D.H, D.P, D.T, 8), gemm(dt, 2, D.H, D.P, D.T, dX1, Cb, g(l, GPTS_W_O), none, st), "out-proj wgrad");
     // c = attention(qkv)
     GPTS_OP(GPTS_TR_ATTN_BWD, 0, 1, 2.0 * attn_fl, (double)D.T * 9 * D.P * e, attention_bwd(dt, D.B, D.S, D.a, D.d, QKVb, s + sl.C,
                                   reinterpret_cast<const float*>(s + sl.LSE), dC, dQKV, attn_scratch, st, h16 ? s + sl.QKV : nullptr),
@@ -477,19 +521,112 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     // qkv = a Wqkv^T + bqkv
     GPTS_OP(GPTS_TR_GEMM_DGRAD, 0, 1, gf(D.T, D.H, 3 * D.P), gb(D.T, D.H, 3 * D.P, e), gemm(dt, 1, D.T, D.H, 3 * D.P, dQKV, w(l, GPTS_W_QKV), dA, d_qkv, st), "qkv dgrad");
     const void* A = s + sl.A;
-    if (rebuild) {
+    if (rebuild && !data_only) {
       float* rs = reinterpret_cast<float*>(wk + ws.rstat);
       GPTS_OP(GPTS_TR_RECOMPUTE, 0, 1, 0.0, TH * (kResBytes + e), ln_fwd(dt, dt == GPTS_BF16, D.T, D.H, c.ln_eps, s + sl.X, w(l, GPTS_LN1_G), w(l, GPTS_LN1_B),
                       wk + ws.rA, rs, rs + D.T, st), "ln1 recompute");
       A = wk + ws.rA;
     }
-    GPTS_OP(GPTS_TR_GEMM_WGRAD, 0, 1, gf(3 * D.P, D.H, D.T), gb(3 * D.P, D.H, D.T, 8), gemm(dt, 2, 3 * D.P, D.H, D.T, dQKV, A, g(l, GPTS_W_QKV), none, st), "qkv wgrad");
+    if (!data_only)
+      GPTS_OP(GPTS_TR_GEMM_WGRAD, 0, 1, gf(3 * D.P, D.H, D.T), gb(3 * D.P, D.H, D.T, 8), gemm(dt, 2, 3 * D.P, D.H, D.T, dQKV, A, g(l, GPTS_W_QKV), none, st), "qkv wgrad");
     GPTS_OP(GPTS_TR_BIAS_GRAD, 0, 1, 0.0, (double)D.T * 3 * D.P * e, colsum(dt, D.T, 3 * D.P, dQKV, g(l, GPTS_B_QKV), cs_part, st), "qkv bias grad");
     // a = LN1(x), x also feeds the residual
     GPTS_OP(GPTS_TR_LN_BWD, 0, 1, 0.0, TH * (3 * e + kResBytes), ln_bwd(dt, dt == GPTS_BF16, D.T, D.H, dA, s + sl.X, stat1, stat1 + D.T, w(l, GPTS_LN1_G), dX1, dXout,
                     g(l, GPTS_LN1_G), g(l, GPTS_LN1_B), l > 0 ? g(l - 1, GPTS_B_FC2) : nullptr, ln_part, st),
             "ln1 bwd (+ fc2 bias grad of the layer below)");
     dY = dXout;
+  }
+  return GPTS_OK;
+}
+
+// Weight phase: dW += sum over the n micro-batches of (output gradient)^T (input activation),
+// for the four linears of every layer.  When the stash holds the input activations as bf16
+// (full stash), the buffers are equally spaced and the shape suits the segmented kernel, one
+// launch per linear contracts over all micro-batches' tokens (one read-modify-write of dW);
+// otherwise one accumulating product per micro-batch, with the activations rebuilt first where
+// the stash does not hold them (recompute, fwd_fp16).
+int run_wgrad_flush(const gpt_stage_params* p, int n, const void* const* act_stashes,
+                    const void* const* grad_stashes, void* dparams, hipStream_t st) {
+  int rc = check_call(p);
+  if (rc != GPTS_OK) return rc;
+  if (n < 1 || !act_stashes || !grad_stashes || !dparams || misaligned(dparams))
+    return fail(GPTS_EINVAL, "wgrad_flush: n < 1, NULL array or dparams NULL / misaligned");
+  for (int m = 0; m < n; ++m)
+    if (!act_stashes[m] || !grad_stashes[m] || misaligned(act_stashes[m]) || misaligned(grad_stashes[m]))
+      return fail(GPTS_EINVAL, "wgrad_flush: a stash pointer is NULL or not 16-byte aligned");
+  if (!p->workspace) return fail(GPTS_EINVAL, "wgrad_flush needs the backward workspace");
+  Tracer* tr = static_cast<Tracer*>(p->trace);
+  const gpt_stage_cfg& c = p->cfg;
+  const Dims D(c);
+  const size_t e = esize(c);
+  const int dt = c.dtype;
+  const StashLayer sl = stash_layer(c);
+  const GradStashLayer gl = grad_stash_layer(c);
+  const BwdWs ws = bwd_ws(c);
+  const char* W = static_cast<const char*>(p->weights);
+  char* wk = static_cast<char*>(p->workspace);
+  float* dP = static_cast<float*>(dparams);
+  auto w = [&](int l, int id) { return (const void*)(W + tensor_off(D, l, id) * e); };
+  auto g = [&](int l, int id) { return dP + tensor_off(D, l, id); };
+  auto gf = [](double M, double N, double K) { return 2.0 * M * N * K; };
+  auto gb = [&](double M, double N, double K, double out_bytes) { return (M * K + N * K) * e + M * N * out_bytes; };
+  const bool h16 = c.fwd_fp16 != 0, rebuild = c.recompute || h16;
+  // equal spacing of the micro-batches' buffers (byte strides; 0 when n == 1)
+  auto stride_of = [&](const void* const* ptrs, ptrdiff_t* out) {
+    *out = 0;
+    if (n == 1) return true;
+    const ptrdiff_t d0 = static_cast<const char*>(ptrs[1]) - static_cast<const char*>(ptrs[0]);
+    if (d0 <= 0 || d0 % (ptrdiff_t)e) return false;
+    for (int m = 2; m < n; ++m)
+      if (static_cast<const char*>(ptrs[m]) - static_cast<const char*>(ptrs[m - 1]) != d0) return false;
+    *out = d0;
+    return true;
+  };
+  ptrdiff_t act_stride = 0, grad_stride = 0;
+  const bool spaced = dt == GPTS_BF16 && !rebuild && stride_of(act_stashes, &act_stride) && stride_of(grad_stashes, &grad_stride);
+  struct Lin { int sub, M, N, wid; size_t dout, in; };   // dW[M,N] += dOut[T,M]^T In[T,N]
+  const Lin lins[4] = {{3, D.H, D.F, GPTS_W_FC2, gl.dY, sl.G}, {2, D.F, D.H, GPTS_W_FC1, gl.dU, sl.A2},
+                       {1, D.H, D.P, GPTS_W_O, gl.dX1, sl.C}, {0, 3 * D.P, D.H, GPTS_W_QKV, gl.dQKV, sl.A}};
+  for (int l = D.L - 1; l >= 0; --l) {
+    for (const Lin& L : lins) {
+      auto dout_of = [&](int m) { return static_cast<const char*>(grad_stashes[m]) + (size_t)l * gl.end + L.dout; };
+      if (spaced && (n == 1 || gemm_wgrad_segments_supported(2, L.M, L.N, D.T))) {
+        GemmEpilogue ep;
+        ep.k_segments = n;
+        ep.seg_stride_a = (size_t)grad_stride / e;
+        ep.seg_stride_b = (size_t)act_stride / e;
+        const void* in0 = static_cast<const char*>(act_stashes[0]) + (size_t)l * sl.end + L.in;
+        GPTS_OP(GPTS_TR_GEMM_WGRAD, L.sub, 1, gf(L.M, L.N, (double)D.T * n), gb(L.M, L.N, (double)D.T * n, 8),
+                gemm(dt, 2, L.M, L.N, D.T, dout_of(0), in0, g(l, L.wid), ep, st), "wgrad over all micro-batches");
+        continue;
+      }
+      for (int m = 0; m < n; ++m) {
+        const char* s = static_cast<const char*>(act_stashes[m]) + (size_t)l * sl.end;
+        const void* in = rebuild ? nullptr : (const void*)(s + L.in);
+        if (rebuild) {
+          float* rs = reinterpret_cast<float*>(wk + ws.rstat);
+          if (L.sub == 3) {
+            GPTS_OP(GPTS_TR_RECOMPUTE, 2, 1, 0.0, (double)D.T * D.F * 2 * e, gelu_fwd(dt, c.gelu, s + sl.U, wk + ws.rG, (size_t)D.T * D.F, st, h16), "gelu recompute");
+            in = wk + ws.rG;
+          } else if (L.sub == 1) {
+            in = s + sl.C;
+            if (h16) {
+              GPTS_OP(GPTS_TR_CONVERT, 1, 1, 0.0, (double)D.T * D.P * 2 * e, f16_to_bf16(s + sl.C, wk + ws.bC, (size_t)D.T * D.P, st), "c to bf16");
+              in = wk + ws.bC;
+            }
+          } else {
+            const bool second = L.sub == 2;
+            GPTS_OP(GPTS_TR_RECOMPUTE, second ? 1 : 0, 1, 0.0, (double)D.T * D.H * (kResBytes + e),
+                    ln_fwd(dt, dt == GPTS_BF16, D.T, D.H, c.ln_eps, s + (second ? sl.X1 : sl.X), w(l, second ? GPTS_LN2_G : GPTS_LN1_G),
+                           w(l, second ? GPTS_LN2_B : GPTS_LN1_B), wk + ws.rA, rs, rs + D.T, st), "layernorm recompute");
+            in = wk + ws.rA;
+          }
+        }
+        GemmEpilogue none;
+        GPTS_OP(GPTS_TR_GEMM_WGRAD, L.sub, 1, gf(L.M, L.N, D.T), gb(L.M, L.N, D.T, 8),
+                gemm(dt, 2, L.M, L.N, D.T, dout_of(m), in, g(l, L.wid), none, st), "wgrad of one micro-batch");
+      }
+    }
   }
   return GPTS_OK;
 }
@@ -627,6 +764,23 @@ int gpt_stage_bwd_only(const gpt_stage_params* p, const void* act_stash, const v
   if (rc != GPTS_OK) return rc;
   if (wait_event) GPTS_TRY(hipStreamWaitEvent(st, static_cast<hipEvent_t>(wait_event), 0), "wait on wait_event");
   return run_bwd(p, act_stash, dy, dx, dparams, st);
+}
+size_t gpt_stage_grad_stash_bytes(const gpt_stage_cfg* c) {
+  if (gpt_stage_validate(c) != GPTS_OK) return 0;
+  return grad_stash_layer(*c).end * c->n_layers;
+}
+int gpt_stage_bwd_data_only(const gpt_stage_params* p, const void* act_stash, const void* dy, void* dx,
+                            void* dparams, void* grad_stash, void* stream, void* wait_event) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rc = check_call(p);  // validate before touching the stream
+  if (rc != GPTS_OK) return rc;
+  if (!grad_stash) return fail(GPTS_EINVAL, "bwd_data_only: grad_stash is NULL");
+  if (wait_event) GPTS_TRY(hipStreamWaitEvent(st, static_cast<hipEvent_t>(wait_event), 0), "wait on wait_event");
+  return run_bwd(p, act_stash, dy, dx, dparams, st, grad_stash);
+}
+int gpt_stage_wgrad_flush(const gpt_stage_params* p, int n_microbatches, const void* const* act_stashes,
+                          const void* const* grad_stashes, void* dparams, void* stream) {
+  return run_wgrad_flush(p, n_microbatches, act_stashes, grad_stashes, dparams, static_cast<hipStream_t>(stream));
 }
 int gpt_stage_fwd_bwd(const gpt_stage_params* p, const void* x, const void* dy, void* act_stash,
                       void* y, void* dx, void* dparams, void* stream) {

@@ -35,9 +35,12 @@ class StageRunner:
             B.gpt_stage_fwd(p, x, b.stash[0], y, stream)
             B.gpt_stage_bwd(p, b.stash[0], dy, dx, b.dparams, stream)
 
-    def decoupled(self, xs, dys, ys, dxs) -> None:
+    def decoupled(self, xs, dys, ys, dxs, split_wgrad: bool = False) -> None:
         """All forwards on fwd_stream, then all backwards on bwd_stream.  The
-        caller's current stream is joined on both sides."""
+        caller's current stream is joined on both sides.  split_wgrad: the backward
+        calls run the data phase only and one weight phase over all micro-batches
+        follows on bwd_stream (section 5.2: a chunk's gradients are due once all its
+        micro-batches have passed)."""
         b = self.b
         assert len(b.stash) >= len(xs), "one stash slot per in-flight micro-batch"
         cur = torch.cuda.current_stream()
@@ -47,9 +50,16 @@ class StageRunner:
         for i in range(n):
             B.gpt_stage_fwd_only(p, xs[i], b.stash[i], ys[i],
                                  self.fwd_stream, self.event if i == n - 1 else None)
-        for i in range(n):
-            B.gpt_stage_bwd_only(p, b.stash[i], dys[i], dxs[i],
-                                 b.dparams, self.bwd_stream, self.event if i == 0 else None)
+        if split_wgrad:
+            b.alloc_grad_stash(n)
+            for i in range(n):
+                B.gpt_stage_bwd_data_only(p, b.stash[i], dys[i], dxs[i], b.dparams, b.grad_stash[i],
+                                          self.bwd_stream, self.event if i == 0 else None)
+            B.gpt_stage_wgrad_flush(p, b.stash[:n], b.grad_stash[:n], b.dparams, self.bwd_stream)
+        else:
+            for i in range(n):
+                B.gpt_stage_bwd_only(p, b.stash[i], dys[i], dxs[i],
+                                     b.dparams, self.bwd_stream, self.event if i == 0 else None)
         cur.wait_stream(self.bwd_stream)
 
 

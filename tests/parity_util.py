@@ -22,7 +22,7 @@ def p64(params):
     return [{k: v.astype(np.float64) for k, v in p.items()} for p in params]
 
 
-def gpu_run(shape, params, xs, dys, decoupled=False, bufs=None, trace=None):
+def gpu_run(shape, params, xs, dys, decoupled=False, bufs=None, trace=None, split_wgrad=False):
     """Returns (ys, dxs, grads) as float64 numpy, parameter gradients accumulated
     over the given micro-batches.  trace: tracer handle attached to the stage calls."""
     n = len(xs)
@@ -37,7 +37,7 @@ def gpu_run(shape, params, xs, dys, decoupled=False, bufs=None, trace=None):
     dxs = [bufs.act() for _ in range(n)]
     runner = harness.StageRunner(bufs)
     if decoupled:
-        runner.decoupled(dxs_in, dys_in, ys, dxs)
+        runner.decoupled(dxs_in, dys_in, ys, dxs, split_wgrad=split_wgrad)
     else:
         runner.coupled(dxs_in, dys_in, ys, dxs)
     torch.cuda.synchronize()
