@@ -30,12 +30,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
-# HBM traffic of the matrix-product kernel on the default workload, from two rocprofv3 --pmc
-# passes (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, averaged over the 768 launches of a step; the
-# summary under profiles/ has the commands and the per-kernel figures).  Only reported while
-# the kernel source is the one the counters were taken on.
-GEMM_TRAFFIC = {"workload": "decoupled_bf16", "bytes_per_launch": 784.2 * 2**20,
-                "source_sha256_16": "becfdd5c80417f46"}
+# Memory traffic of the matrix-product kernels on the default workload and schedule (one weight
+# phase per step), from two rocprofv3 --pmc passes: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 averaged
+# over the 272 matrix-product launches of a step (the summary under profiles/ has the commands
+# and the per-kernel figures).  Only reported while the kernel source is the one the counters
+# were taken on.
+GEMM_TRAFFIC = {"workload": "decoupled_bf16", "weight_phase": True, "bytes_per_launch": 1011.6 * 2**20,
+                "source_sha256_16": "e15f56856a140c7d"}
 PEAK_FP32_TFLOPS = 157.3    # MI355X fp32 vector
 DEFAULT_WORKLOAD = "decoupled_bf16"
 
@@ -100,7 +101,7 @@ def cpu_baseline(shape):
                       f"(fp64 numpy oracle, {flops / 1e12:.3f} model TFLOP causal-aware)"}
 
 
-def gemm_traffic(shape):
+def gemm_traffic(shape, weight_phase):
     """Measured HBM bytes per launch of the matrix-product kernel, or None when no counters
     exist for this workload or the kernel source has changed since they were taken."""
     import hashlib
@@ -109,12 +110,13 @@ def gemm_traffic(shape):
         sha = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
     except OSError:
         return None
-    if shape.name != GEMM_TRAFFIC["workload"] or sha != GEMM_TRAFFIC["source_sha256_16"]:
+    if (shape.name != GEMM_TRAFFIC["workload"] or sha != GEMM_TRAFFIC["source_sha256_16"]
+            or weight_phase != GEMM_TRAFFIC["weight_phase"]):
         return None
     return GEMM_TRAFFIC["bytes_per_launch"]
 
 
-def traced_pass(step, bufs, shape, n_ops, steps):
+def traced_pass(step, bufs, shape, n_ops, steps, weight_phase):
     """Run `steps` more steps of the same workload with the library's operator tracer
     attached: a start/end hipEvent pair is recorded around every operator on the stream
     it is launched on.  Returns per-operator-class totals and the roofline object of
@@ -153,7 +155,7 @@ def traced_pass(step, bufs, shape, n_ops, steps):
     peak = PEAK_BF16_TFLOPS if shape.dtype == "bf16" else PEAK_FP32_TFLOPS
     achieved = fl / ms / 1e9
     roof = {"bound": "mfma" if shape.dtype == "bf16" else "alu", "achieved": achieved, "peak": peak,
-            "unit": "TFLOP/s", "frac": achieved / peak, "traffic": gemm_traffic(shape),
+            "unit": "TFLOP/s", "frac": achieved / peak, "traffic": gemm_traffic(shape, weight_phase),
             "kernel": "the matrix products (gemm_mi16_kernel where the shape allows): the 12 of a layer, "
                       "forward, dgrad, wgrad, averaged",
             "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
@@ -291,7 +293,7 @@ def run_workload(args, shape):
     tflops = flops / (ms * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if shape.dtype == "bf16" else PEAK_FP32_TFLOPS
     ops_per_step = 28 * shape.n_layers * n_mb   # trace capacity (upper bound)
-    roof, table = traced_pass(step, bufs, shape, ops_per_step, max(1, min(args.steps, 2)))
+    roof, table = traced_pass(step, bufs, shape, ops_per_step, max(1, min(args.steps, 2)), split)
     stash = ("fp16 forward activations; LayerNorm/GeLU outputs rebuilt in backward" if shape.fwd_fp16 else
              "recompute LayerNorm/GeLU outputs in backward" if shape.recompute else "full")
     out = {
@@ -418,7 +420,8 @@ def pmc_summary(path):
                 continue
             with open(os.path.join(root, f), newline="") as fh:
                 for r in csv.DictReader(fh):
-                    k = r["Kernel_Name"].split("(")[0]
+                    k = r["Kernel_Name"].replace("(anonymous namespace)::", "").replace("void ", "")
+                    k = k.split("(")[0]   # drop the argument list
                     row = acc.setdefault(k, {})
                     c = row.setdefault(r["Counter_Name"], [0.0, 0])
                     c[0] += float(r["Counter_Value"])

@@ -450,6 +450,11 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma_kernel(
   const int aoff = natural_frag_off<D>(ql, h);
   const int ioff = image_frag_off(ql, h);
 
+  // The query tiles are walked from the LAST one down to the key block's own diagonal: every
+  // key block of a head then starts at the same tile and they move in step, so the tiles one
+  // workgroup streams are the ones its neighbours (same head, same XCD) are streaming at that
+  // moment and come out of the L2 instead of HBM.  (Walking upwards from the diagonal, each
+  // block is 256 rows ahead of the next one and the window does not fit the cache.)
   const int qt0 = k0 / BKV;
   auto fetch = [&](int qt, int stage) {
     // the lane index is made opaque here so that the per-lane DMA offsets are recomputed
@@ -467,16 +472,16 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma_kernel(
     if (wave == 0) dma_floats(lse_h, qc, stat[stage][0]);
     if (wave == 1) dma_floats(delta_h, qc, stat[stage][1]);
   };
-  fetch(qt0, 0);
+  fetch(ntile - 1, 0);
 
-  for (int qt = qt0; qt < ntile; ++qt) {
-    const int stage = (qt - qt0) & 1;
+  for (int qt = ntile - 1; qt >= qt0; --qt) {
+    const int stage = (ntile - 1 - qt) & 1;
     asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     const char* tQ = lds + stage * 4 * TILE;
     const char* tO = tQ + TILE;
     const char* tQT = tQ + 2 * TILE;
     const char* tOT = tQ + 3 * TILE;
-    if (qt + 1 < ntile) fetch(qt + 1, stage ^ 1);
+    if (qt > qt0) fetch(qt - 1, stage ^ 1);
 #pragma unroll 1
     for (int qb = 0; qb < 2; ++qb) {
       const int qmin = qt * BKV + qb * 32;
