@@ -55,8 +55,9 @@ def parse():
                     help="decoupled schedule: weight gradients in one weight phase after all backward data "
                          "phases (flush; auto picks it when there are several micro-batches) or inside every "
                          "micro-batch's backward call")
-    ap.add_argument("--recompute", action="store_true",
-                    help="activation recomputation: smaller stash, LayerNorm/GeLU outputs rebuilt in backward")
+    ap.add_argument("--recompute", type=int, nargs="?", const=1, default=0, choices=[0, 1, 2],
+                    help="activation recomputation: 1 = LayerNorm/GeLU outputs rebuilt in backward, "
+                         "2 = only each layer's input is stashed and backward re-runs the layer's forward")
     ap.add_argument("--op", choices=["attention", "layernorm", "gemm"], default=None,
                     help="time one operator alone (gpt_stage_op_* entry points) at the workload's shapes")
     ap.add_argument("--pmc-summary", default=None, metavar="DIR",
@@ -260,7 +261,7 @@ def run_workload(args, shape):
     dxs = [bufs.act() for _ in range(n_mb)]
     gen_s = time.perf_counter() - t0
     runner = harness.StageRunner(bufs)
-    split = decoupled and n_mb > 1 and args.wgrad != "per-microbatch"
+    split = decoupled and n_mb > 1 and args.wgrad != "per-microbatch" and shape.recompute != 2
 
     # fp16 forward activations read the weights through their (fp16) images only
     prepare = shape.dtype == "bf16" and (shape.fwd_fp16 or not args.no_prepare)
@@ -295,6 +296,7 @@ def run_workload(args, shape):
     ops_per_step = 28 * shape.n_layers * n_mb   # trace capacity (upper bound)
     roof, table = traced_pass(step, bufs, shape, ops_per_step, max(1, min(args.steps, 2)), split)
     stash = ("fp16 forward activations; LayerNorm/GeLU outputs rebuilt in backward" if shape.fwd_fp16 else
+             "only each layer's input; backward re-runs the layer's forward" if shape.recompute == 2 else
              "recompute LayerNorm/GeLU outputs in backward" if shape.recompute else "full")
     out = {
         "metric": "model TFLOP/s for one stage fwd+bwd on 1 MI355X",
@@ -449,7 +451,7 @@ def main():
     B.lib()
     shapes = list(synth.WORKLOADS) if args.workload == "all" else [pick_workload(args.workload)]
     if args.recompute:
-        shapes = [s.with_(recompute=True) for s in shapes]
+        shapes = [s.with_(recompute=args.recompute) for s in shapes]
     if args.dpp:
         return dpp_bench(args, shapes[0])
     if args.op:

@@ -76,13 +76,19 @@ typedef struct {
                         and parameter gradients fp32.                        */
   int32_t gelu;      /* GPTS_GELU_TANH or GPTS_GELU_ERF                      */
   float   ln_eps;    /* LayerNorm epsilon (inside the square root)           */
-  int32_t recompute; /* 0: the stash holds every tensor the backward phase reads.
-                        1: activation recomputation (sections 4.1, 5.2: the backward
-                        phase "involves ... activation recomputation"): the two
-                        LayerNorm outputs and the GeLU output are not stashed; the
-                        backward phase recomputes them from the stashed x, x1
-                        (with the stashed statistics' inputs) and u.  One third less
-                        stash, about 3 % more backward time, identical results.  */
+  int32_t recompute; /* Activation recomputation (sections 4.1, 5.2: the backward phase
+                        "involves ... activation recomputation"; the traversal choice is tied
+                        to activation memory).  Identical results at every level.
+                        0: the stash holds every tensor the backward phase reads.
+                        1: the two LayerNorm outputs and the GeLU output are not stashed; the
+                           backward phase rebuilds them from the stashed x, x1 and u.  One third
+                           less stash, about 2 % more time per step.
+                        2: the stash keeps only each layer's input x; the backward phase runs
+                           the layer's forward again (up to the GeLU) into its workspace before
+                           the layer's backward.  One ninth of the stash at hidden = width,
+                           ffn = 4 hidden; one more forward minus the last product per layer.
+                           The split backward (bwd_data_only / wgrad_flush) is not available
+                           at this level: it would need the activations a second time.     */
   int32_t fwd_fp16;  /* bf16 stages only.  0: forward activations are bf16.  1: the forward
                         phase keeps the activations that branch off the residual stream
                         (both LayerNorm outputs, qkv, the attention probabilities and

@@ -193,7 +193,7 @@ def make_cfg(s: synth.StageShape) -> gpt_stage_cfg:
                          ffn=s.ffn, seq=s.seq, batch=s.batch,
                          dtype=GPTS_BF16 if s.dtype == "bf16" else GPTS_FP32,
                          gelu=GPTS_GELU_ERF if s.gelu == "erf" else GPTS_GELU_TANH,
-                         ln_eps=s.ln_eps, recompute=1 if s.recompute else 0,
+                         ln_eps=s.ln_eps, recompute=int(s.recompute),
                          fwd_fp16=1 if s.fwd_fp16 else 0)
 
 

@@ -66,16 +66,20 @@ constexpr size_t kAbsent = ~(size_t)0;
 struct StashLayer {
   size_t X, stat1, A, QKV, C, LSE, X1, stat2, A2, U, G, end;   // kAbsent: not stashed
 };
-StashLayer stash_layer(const gpt_stage_cfg& c) {
+// layer_block(): every tensor one layer's backward reads, in the order above.  It is what a
+// layer of the stash holds -- except with recompute == 2, where the stash keeps only X per layer
+// (stash_layer()) and the block is a workspace buffer the backward phase refills, layer by
+// layer, by running the layer's forward again.
+StashLayer layer_block(const gpt_stage_cfg& c) {
   Dims D(c);
   const size_t e = esize(c);
   StashLayer s;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
-  // with recomputation, and always when the forward activations are fp16 (the backward phase
-  // needs bf16 copies and rebuilds them), A, A2 and G are not stashed; with fwd_fp16 the
-  // stashed QKV, C and U hold fp16 values (same size)
-  const bool full = c.recompute == 0 && c.fwd_fp16 == 0;
+  // with the light recomputation, and always when the forward activations are fp16 (the backward
+  // phase needs bf16 copies and rebuilds them), A, A2 and G are not kept; with fwd_fp16 the
+  // kept QKV, C and U hold fp16 values (same size)
+  const bool full = c.recompute != 1 && c.fwd_fp16 == 0;
   s.X = take((size_t)D.T * D.H * kResBytes);
   s.stat1 = take((size_t)2 * D.T * 4);
   s.A = full ? take((size_t)D.T * D.H * e) : kAbsent;
@@ -90,6 +94,15 @@ StashLayer stash_layer(const gpt_stage_cfg& c) {
   s.end = o;
   return s;
 }
+StashLayer stash_layer(const gpt_stage_cfg& c) {
+  if (c.recompute != 2) return layer_block(c);
+  Dims D(c);
+  StashLayer s;
+  s.X = 0;
+  s.stat1 = s.A = s.QKV = s.C = s.LSE = s.X1 = s.stat2 = s.A2 = s.U = s.G = kAbsent;
+  s.end = align_up((size_t)D.T * D.H * kResBytes, 256);
+  return s;
+}
 
 // ---- workspace ---------------------------------------------------------------------
 // [forward region | backward region]: a forward and a backward call on different streams
@@ -97,7 +110,8 @@ StashLayer stash_layer(const gpt_stage_cfg& c) {
 // attention kernels' scratch; offsets in BwdWs are relative to the whole workspace.
 size_t attention_scratch_bytes(int dtype, int B, int S, int a, int d, int phase);
 struct FwdWs {
-  size_t attn, A, G, end;   // A (shared by both LayerNorm outputs) and G only with recomputation
+  size_t attn, A, G, blk, end;   // A (shared by both LayerNorm outputs) and G only where they are
+                                 // not kept; blk: the layer block with recompute == 2
 };
 FwdWs fwd_ws(const gpt_stage_cfg& c) {
   Dims D(c);
@@ -106,9 +120,10 @@ FwdWs fwd_ws(const gpt_stage_cfg& c) {
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
   w.attn = take(attention_scratch_bytes(c.dtype, D.B, D.S, D.a, D.d, 0));
-  const bool transient = c.recompute || c.fwd_fp16;
+  const bool transient = c.recompute == 1 || c.fwd_fp16;
   w.A = transient ? take((size_t)D.T * D.H * e) : kAbsent;
   w.G = transient ? take((size_t)D.T * D.F * e) : kAbsent;
+  w.blk = c.recompute == 2 ? take(layer_block(c).end) : kAbsent;
   w.end = o;
   return w;
 }
@@ -116,6 +131,7 @@ size_t fwd_ws_bytes(const gpt_stage_cfg& c) { return fwd_ws(c).end; }
 struct BwdWs {
   size_t dU, dA, dX1, dC, dQKV, attn, ping, pong, ln_part, cs_part, rA, rG, rstat, end;
   size_t bQKV, bC, bU;   // fwd_fp16: bf16 copies of the fp16 QKV, C and U of the stash
+  size_t fwd2;           // recompute == 2: a forward workspace of the backward phase's own
 };
 BwdWs bwd_ws(const gpt_stage_cfg& c) {
   Dims D(c);
@@ -137,13 +153,14 @@ BwdWs bwd_ws(const gpt_stage_cfg& c) {
   if (D.F > maxn) maxn = D.F;
   w.cs_part = take(colsum_scratch_bytes(D.T, maxn));
   // recomputed LayerNorm output (one buffer, used for A2 and then A), GeLU output, statistics
-  const bool rebuild = c.recompute || c.fwd_fp16;
+  const bool rebuild = c.recompute == 1 || c.fwd_fp16;
   w.rA = rebuild ? take((size_t)D.T * D.H * e) : kAbsent;
   w.rG = rebuild ? take((size_t)D.T * D.F * e) : kAbsent;
   w.rstat = rebuild ? take((size_t)2 * D.T * 4) : kAbsent;
   w.bQKV = c.fwd_fp16 ? take((size_t)D.T * 3 * D.P * e) : kAbsent;
   w.bC = c.fwd_fp16 ? take((size_t)D.T * D.P * e) : kAbsent;
   w.bU = c.fwd_fp16 ? take((size_t)D.T * D.F * e) : kAbsent;
+  w.fwd2 = c.recompute == 2 ? take(fwd_ws_bytes(c)) : kAbsent;
   w.end = o;
   return w;
 }
@@ -295,24 +312,22 @@ int need_prepared(const gpt_stage_params* p) {
   return GPTS_OK;
 }
 
-int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, hipStream_t st) {
-  int rc = check_call(p);
-  if (rc != GPTS_OK) return rc;
-  if ((rc = need_prepared(p)) != GPTS_OK) return rc;
+// Forward of layer l.  X: the layer's input (residual stream); blk: the layer block that
+// receives every tensor the backward phase reads (layer_block() layout; its X slot is not
+// written here); Yout: the layer's output, or nullptr to stop after the GeLU (the re-run of a
+// layer inside the backward phase needs nothing beyond it); fwk: a forward workspace (fwd_ws
+// layout).  phase: what the tracer records (0 forward phase, 1 backward phase).
+int fwd_layer(const gpt_stage_params* p, int l, const void* X, char* blk, void* Yout, bool y_f32,
+              char* fwk, hipStream_t st, int phase) {
   Tracer* tr = static_cast<Tracer*>(p->trace);
-  if (!x || !act_stash || !y || misaligned(x) || misaligned(act_stash) || misaligned(y))
-    return fail(GPTS_EINVAL, "x / act_stash / y NULL or not 16-byte aligned");
-  if (x == y) return fail(GPTS_EINVAL, "y must not alias x");
-  if (!p->workspace && fwd_ws_bytes(p->cfg) > 0) return fail(GPTS_EINVAL, "forward needs a workspace");
   const gpt_stage_cfg& c = p->cfg;
   const Dims D(c);
   const size_t e = esize(c);
   const int dt = c.dtype;
-  const StashLayer sl = stash_layer(c);
+  const StashLayer sl = layer_block(c);
+  const FwdWs fw = fwd_ws(c);
   const char* W = static_cast<const char*>(p->weights);
-  char* stash = static_cast<char*>(act_stash);
-  auto w = [&](int l, int id) { return (const void*)(W + tensor_off(D, l, id) * e); };
-
+  auto w = [&](int l_, int id) { return (const void*)(W + tensor_off(D, l_, id) * e); };
   // algorithmic work of one operator, for the tracer: flops of an M x N x K product and
   // the bytes it must move (operands once, result once)
   auto gf = [](double M, double N, double K) { return 2.0 * M * N * K; };
@@ -320,11 +335,74 @@ int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, 
   const double TH = (double)D.T * D.H, attn_fl = 4.0 * D.B * D.a * D.d * ((double)D.S * (D.S + 1) / 2.0);
   const bool bf = dt == GPTS_BF16;
   const bf16* prep = bf ? static_cast<const bf16*>(p->prepared) : nullptr;
-  auto img = [&](int l, int lin, int which) -> const void* {
-    return prep ? (const void*)(prep + prepared_off(D, l, lin, which)) : nullptr;
+  auto img = [&](int l_, int lin, int which) -> const void* {
+    return prep ? (const void*)(prep + prepared_off(D, l_, lin, which)) : nullptr;
   };
+  const int top = phase == 0 ? GPTS_TR_LN_FWD : GPTS_TR_RECOMPUTE;   // a re-run counts as recomputation
+  const int top_gemm = phase == 0 ? GPTS_TR_GEMM_FWD : GPTS_TR_RECOMPUTE;
+  const int top_attn = phase == 0 ? GPTS_TR_ATTN_FWD : GPTS_TR_RECOMPUTE;
+  char* s = blk;
+  float* stat1 = reinterpret_cast<float*>(s + sl.stat1);
+  float* stat2 = reinterpret_cast<float*>(s + sl.stat2);
+  // with the light recomputation (and with fp16 forward activations) the LayerNorm and GeLU
+  // outputs only live in the workspace
+  const bool transient = c.recompute == 1 || c.fwd_fp16;
+  const bool h16 = c.fwd_fp16 != 0;   // A, QKV, C, A2, U, G hold fp16 values
+  void* A = transient ? fwk + fw.A : s + sl.A;
+  void* A2 = transient ? fwk + fw.A : s + sl.A2;
+  void* G = transient ? fwk + fw.G : s + sl.G;
+  // one forward product: fp16 operands through the weight's fp16 image, or the bf16 paths
+  auto fwd_gemm = [&](int N, int K, const void* Ain, int wid, void* Cout, const GemmEpilogue& ep_) {
+    return h16 ? gemm_fwd_f16(D.T, N, K, Ain, ep_.b_image, Cout, ep_, st) : gemm(dt, 0, D.T, N, K, Ain, w(l, wid), Cout, ep_, st);
+  };
+  GPTS_OP(top, 0, phase, 0.0, TH * (kResBytes + e), ln_fwd(dt, bf, D.T, D.H, c.ln_eps, X, w(l, GPTS_LN1_G), w(l, GPTS_LN1_B), A, stat1,
+                  stat1 + D.T, st, h16), "ln1 fwd");
+  GemmEpilogue ep;
+  ep.bias = w(l, GPTS_B_QKV);
+  ep.b_image = img(l, 0, 0);
+  GPTS_OP(top_gemm, 0, phase, gf(D.T, 3 * D.P, D.H), gb(D.T, 3 * D.P, D.H, e), fwd_gemm(3 * D.P, D.H, A, GPTS_W_QKV, s + sl.QKV, ep), "qkv gemm");
+  GPTS_OP(top_attn, 0, phase, attn_fl, (double)D.T * 4 * D.P * e, attention_fwd(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
+                                reinterpret_cast<float*>(s + sl.LSE), fwk + fw.attn, st, h16), "attention fwd");
+  ep = GemmEpilogue();
+  ep.bias = w(l, GPTS_B_O);
+  ep.residual = X;
+  ep.residual_f32 = ep.out_f32 = bf;
+  ep.b_image = img(l, 1, 0);
+  GPTS_OP(top_gemm, 1, phase, gf(D.T, D.H, D.P), gb(D.T, D.H, D.P, 2 * kResBytes), fwd_gemm(D.H, D.P, s + sl.C, GPTS_W_O, s + sl.X1, ep), "out-proj gemm");
+  GPTS_OP(top, 1, phase, 0.0, TH * (kResBytes + e), ln_fwd(dt, bf, D.T, D.H, c.ln_eps, s + sl.X1, w(l, GPTS_LN2_G), w(l, GPTS_LN2_B), A2,
+                  stat2, stat2 + D.T, st, h16), "ln2 fwd");
+  ep = GemmEpilogue();
+  ep.bias = w(l, GPTS_B_FC1);
+  ep.gelu_out = G;
+  ep.gelu_kind = c.gelu;
+  ep.b_image = img(l, 2, 0);
+  GPTS_OP(top_gemm, 2, phase, gf(D.T, D.F, D.H), gb(D.T, D.F, D.H, 2 * e), fwd_gemm(D.F, D.H, A2, GPTS_W_FC1, s + sl.U, ep), "fc1 gemm");
+  if (!Yout) return GPTS_OK;
+  ep = GemmEpilogue();
+  ep.bias = w(l, GPTS_B_FC2);
+  ep.residual = s + sl.X1;
+  ep.residual_f32 = bf;
+  ep.out_f32 = bf && y_f32;   // the stage output y is bf16, the stream between layers fp32
+  ep.b_image = img(l, 3, 0);
+  GPTS_OP(top_gemm, 3, phase, gf(D.T, D.H, D.F), gb(D.T, D.H, D.F, 2 * kResBytes), fwd_gemm(D.H, D.F, G, GPTS_W_FC2, Yout, ep), "fc2 gemm");
+  return GPTS_OK;
+}
+
+int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, hipStream_t st) {
+  int rc = check_call(p);
+  if (rc != GPTS_OK) return rc;
+  if ((rc = need_prepared(p)) != GPTS_OK) return rc;
+  if (!x || !act_stash || !y || misaligned(x) || misaligned(act_stash) || misaligned(y))
+    return fail(GPTS_EINVAL, "x / act_stash / y NULL or not 16-byte aligned");
+  if (x == y) return fail(GPTS_EINVAL, "y must not alias x");
+  if (!p->workspace && fwd_ws_bytes(p->cfg) > 0) return fail(GPTS_EINVAL, "forward needs a workspace");
+  const gpt_stage_cfg& c = p->cfg;
+  const Dims D(c);
+  const size_t e = esize(c);
+  const StashLayer sl = stash_layer(c);
+  char* stash = static_cast<char*>(act_stash);
   // layer 0 keeps its own (fp32) copy of x so the backward phase never needs the caller's buffer
-  if (bf)
+  if (c.dtype == GPTS_BF16)
     GPTS_TRY(widen_to_f32(x, reinterpret_cast<float*>(stash + sl.X), (size_t)D.T * D.H, st), "widen x");
   else
     GPTS_TRY(hipMemcpyAsync(stash + sl.X, x, (size_t)D.T * D.H * e, hipMemcpyDeviceToDevice, st), "copy x");
@@ -332,50 +410,12 @@ int run_fwd(const gpt_stage_params* p, const void* x, void* act_stash, void* y, 
   char* fwk = static_cast<char*>(p->workspace);
   for (int l = 0; l < D.L; ++l) {
     char* s = stash + (size_t)l * sl.end;
-    void* X = s + sl.X;
-    float* stat1 = reinterpret_cast<float*>(s + sl.stat1);
-    float* stat2 = reinterpret_cast<float*>(s + sl.stat2);
-    void* Yout = (l == D.L - 1) ? y : (void*)(s + sl.end + sl.X);
-    // with recomputation (and with fp16 forward activations) the LayerNorm and GeLU outputs
-    // only live in the workspace
-    const bool transient = c.recompute || c.fwd_fp16;
-    const bool h16 = c.fwd_fp16 != 0;   // A, QKV, C, A2, U, G hold fp16 values
-    void* A = transient ? fwk + fw.A : s + sl.A;
-    void* A2 = transient ? fwk + fw.A : s + sl.A2;
-    void* G = transient ? fwk + fw.G : s + sl.G;
-    // one forward product: fp16 operands through the weight's fp16 image, or the bf16 paths
-    auto fwd_gemm = [&](int N, int K, const void* Ain, int wid, void* Cout, const GemmEpilogue& ep_) {
-      return h16 ? gemm_fwd_f16(D.T, N, K, Ain, ep_.b_image, Cout, ep_, st) : gemm(dt, 0, D.T, N, K, Ain, w(l, wid), Cout, ep_, st);
-    };
-    GPTS_OP(GPTS_TR_LN_FWD, 0, 0, 0.0, TH * (kResBytes + e), ln_fwd(dt, bf, D.T, D.H, c.ln_eps, X, w(l, GPTS_LN1_G), w(l, GPTS_LN1_B), A, stat1,
-                    stat1 + D.T, st, h16), "ln1 fwd");
-    GemmEpilogue ep;
-    ep.bias = w(l, GPTS_B_QKV);
-    ep.b_image = img(l, 0, 0);
-    GPTS_OP(GPTS_TR_GEMM_FWD, 0, 0, gf(D.T, 3 * D.P, D.H), gb(D.T, 3 * D.P, D.H, e), fwd_gemm(3 * D.P, D.H, A, GPTS_W_QKV, s + sl.QKV, ep), "qkv gemm");
-    GPTS_OP(GPTS_TR_ATTN_FWD, 0, 0, attn_fl, (double)D.T * 4 * D.P * e, attention_fwd(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
-                                  reinterpret_cast<float*>(s + sl.LSE), fwk + fw.attn, st, h16), "attention fwd");
-    ep = GemmEpilogue();
-    ep.bias = w(l, GPTS_B_O);
-    ep.residual = X;
-    ep.residual_f32 = ep.out_f32 = bf;
-    ep.b_image = img(l, 1, 0);
-    GPTS_OP(GPTS_TR_GEMM_FWD, 1, 0, gf(D.T, D.H, D.P), gb(D.T, D.H, D.P, 2 * kResBytes), fwd_gemm(D.H, D.P, s + sl.C, GPTS_W_O, s + sl.X1, ep), "out-proj gemm");
-    GPTS_OP(GPTS_TR_LN_FWD, 1, 0, 0.0, TH * (kResBytes + e), ln_fwd(dt, bf, D.T, D.H, c.ln_eps, s + sl.X1, w(l, GPTS_LN2_G), w(l, GPTS_LN2_B), A2,
-                    stat2, stat2 + D.T, st, h16), "ln2 fwd");
-    ep = GemmEpilogue();
-    ep.bias = w(l, GPTS_B_FC1);
-    ep.gelu_out = G;
-    ep.gelu_kind = c.gelu;
-    ep.b_image = img(l, 2, 0);
-    GPTS_OP(GPTS_TR_GEMM_FWD, 2, 0, gf(D.T, D.F, D.H), gb(D.T, D.F, D.H, 2 * e), fwd_gemm(D.F, D.H, A2, GPTS_W_FC1, s + sl.U, ep), "fc1 gemm");
-    ep = GemmEpilogue();
-    ep.bias = w(l, GPTS_B_FC2);
-    ep.residual = s + sl.X1;
-    ep.residual_f32 = bf;
-    ep.out_f32 = bf && l != D.L - 1;   // the stage output y is bf16, the stream between layers fp32
-    ep.b_image = img(l, 3, 0);
-    GPTS_OP(GPTS_TR_GEMM_FWD, 3, 0, gf(D.T, D.H, D.F), gb(D.T, D.H, D.F, 2 * kResBytes), fwd_gemm(D.H, D.F, G, GPTS_W_FC2, Yout, ep), "fc2 gemm");
+    // with recompute == 2 only X stays in the stash; the rest of the block is transient
+    char* blk = c.recompute == 2 ? fwk + fw.blk : s;
+    const bool last = l == D.L - 1;
+    void* Yout = last ? y : (void*)(s + sl.end + sl.X);
+    rc = fwd_layer(p, l, s + sl.X, blk, Yout, !last, fwk, st, 0);
+    if (rc != GPTS_OK) return rc;
   }
   return GPTS_OK;
 }
@@ -397,7 +437,11 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
   const Dims D(c);
   const size_t e = esize(c);
   const int dt = c.dtype;
-  const StashLayer sl = stash_layer(c);
+  const StashLayer xsl = stash_layer(c);   // what the stash holds per layer
+  const StashLayer sl = layer_block(c);    // the block the backward of a layer reads
+  const bool rerun = c.recompute == 2;     // the block is rebuilt by running the layer's forward again
+  if (rerun && grad_stash)
+    return fail(GPTS_EINVAL, "bwd_data_only: recompute == 2 keeps no activations for a later weight phase");
   const BwdWs ws = bwd_ws(c);
   const char* W = static_cast<const char*>(p->weights);
   const char* stash = static_cast<const char*>(act_stash);
@@ -435,7 +479,17 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     dY = top;
   }
   for (int l = D.L - 1; l >= 0; --l) {
-    const char* s = stash + (size_t)l * sl.end;
+    const char* xs = stash + (size_t)l * xsl.end + xsl.X;    // the layer's input X
+    const char* s = stash + (size_t)l * xsl.end;
+    if (rerun) {
+      // keep-only-X recomputation: run the layer's forward again, up to the GeLU, into the
+      // workspace block (same kernels on the same inputs as in the forward phase: same bits)
+      char* fwk2 = wk + ws.fwd2;
+      char* blk = fwk2 + fwd_ws(c).blk;
+      int rc2 = fwd_layer(p, l, xs, blk, nullptr, false, fwk2, st, 1);
+      if (rc2 != GPTS_OK) return rc2;
+      s = blk;
+    }
     const float* stat1 = reinterpret_cast<const float*>(s + sl.stat1);
     const float* stat2 = reinterpret_cast<const float*>(s + sl.stat2);
     void* dXout = (l == 0) ? dx : (void*)(wk + (((D.L - 1 - l) & 1) ? ws.pong : ws.ping));
@@ -453,7 +507,7 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     d_qkv.b_image = img(l, 0);
     // y = x1 + g W2^T + b2 ;  g = gelu(u)
     const bool h16 = c.fwd_fp16 != 0;            // QKV, C, U of the stash hold fp16 values
-    const bool rebuild = c.recompute || h16;     // A, A2, G are rebuilt here (as bf16)
+    const bool rebuild = c.recompute == 1 || h16;     // A, A2, G are rebuilt here (as bf16)
     const void* U = s + sl.U;
     if (h16) {
       // gradients need bf16's range, so every backward product is bf16: it reads bf16 copies of
@@ -523,7 +577,7 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     const void* A = s + sl.A;
     if (rebuild && !data_only) {
       float* rs = reinterpret_cast<float*>(wk + ws.rstat);
-      GPTS_OP(GPTS_TR_RECOMPUTE, 0, 1, 0.0, TH * (kResBytes + e), ln_fwd(dt, dt == GPTS_BF16, D.T, D.H, c.ln_eps, s + sl.X, w(l, GPTS_LN1_G), w(l, GPTS_LN1_B),
+      GPTS_OP(GPTS_TR_RECOMPUTE, 0, 1, 0.0, TH * (kResBytes + e), ln_fwd(dt, dt == GPTS_BF16, D.T, D.H, c.ln_eps, xs, w(l, GPTS_LN1_G), w(l, GPTS_LN1_B),
                       wk + ws.rA, rs, rs + D.T, st), "ln1 recompute");
       A = wk + ws.rA;
     }
@@ -531,7 +585,7 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
       GPTS_OP(GPTS_TR_GEMM_WGRAD, 0, 1, gf(3 * D.P, D.H, D.T), gb(3 * D.P, D.H, D.T, 8), gemm(dt, 2, 3 * D.P, D.H, D.T, dQKV, A, g(l, GPTS_W_QKV), none, st), "qkv wgrad");
     GPTS_OP(GPTS_TR_BIAS_GRAD, 0, 1, 0.0, (double)D.T * 3 * D.P * e, colsum(dt, D.T, 3 * D.P, dQKV, g(l, GPTS_B_QKV), cs_part, st), "qkv bias grad");
     // a = LN1(x), x also feeds the residual
-    GPTS_OP(GPTS_TR_LN_BWD, 0, 1, 0.0, TH * (3 * e + kResBytes), ln_bwd(dt, dt == GPTS_BF16, D.T, D.H, dA, s + sl.X, stat1, stat1 + D.T, w(l, GPTS_LN1_G), dX1, dXout,
+    GPTS_OP(GPTS_TR_LN_BWD, 0, 1, 0.0, TH * (3 * e + kResBytes), ln_bwd(dt, dt == GPTS_BF16, D.T, D.H, dA, xs, stat1, stat1 + D.T, w(l, GPTS_LN1_G), dX1, dXout,
                     g(l, GPTS_LN1_G), g(l, GPTS_LN1_B), l > 0 ? g(l - 1, GPTS_B_FC2) : nullptr, ln_part, st),
             "ln1 bwd (+ fc2 bias grad of the layer below)");
     dY = dXout;
@@ -570,7 +624,8 @@ int run_wgrad_flush(const gpt_stage_params* p, int n, const void* const* act_sta
   auto g = [&](int l, int id) { return dP + tensor_off(D, l, id); };
   auto gf = [](double M, double N, double K) { return 2.0 * M * N * K; };
   auto gb = [&](double M, double N, double K, double out_bytes) { return (M * K + N * K) * e + M * N * out_bytes; };
-  const bool h16 = c.fwd_fp16 != 0, rebuild = c.recompute || h16;
+  if (c.recompute == 2) return fail(GPTS_EINVAL, "wgrad_flush: recompute == 2 keeps no activations for a weight phase");
+  const bool h16 = c.fwd_fp16 != 0, rebuild = c.recompute == 1 || h16;
   // equal spacing of the micro-batches' buffers (byte strides; 0 when n == 1)
   auto stride_of = [&](const void* const* ptrs, ptrdiff_t* out) {
     *out = 0;
@@ -644,7 +699,7 @@ int gpt_stage_validate(const gpt_stage_cfg* c) {
   if (c->dtype != GPTS_FP32 && c->dtype != GPTS_BF16) return fail(GPTS_EINVAL, "dtype must be GPTS_FP32 or GPTS_BF16");
   if (c->gelu != GPTS_GELU_TANH && c->gelu != GPTS_GELU_ERF) return fail(GPTS_EINVAL, "gelu must be GPTS_GELU_TANH or GPTS_GELU_ERF");
   if (!(c->ln_eps >= 0.f)) return fail(GPTS_EINVAL, "ln_eps must be >= 0");
-  if (c->recompute != 0 && c->recompute != 1) return fail(GPTS_EINVAL, "recompute must be 0 or 1");
+  if (c->recompute < 0 || c->recompute > 2) return fail(GPTS_EINVAL, "recompute must be 0, 1 or 2");
   if (c->fwd_fp16 != 0 && c->fwd_fp16 != 1) return fail(GPTS_EINVAL, "fwd_fp16 must be 0 or 1");
   if (c->fwd_fp16 && c->dtype != GPTS_BF16) return fail(GPTS_EINVAL, "fwd_fp16 applies to bf16 stages only");
   if (c->n_layers < 1 || c->batch < 1 || c->seq < 1 || c->n_heads < 1 || c->hidden < 1 || c->ffn < 1)

@@ -51,7 +51,8 @@ class StageShape:
     out_std: float = 0.02   # std of w_o and w_fc2
     bias_std: float = 0.0
     ln_jitter: float = 0.0  # gamma = 1 + N(0, j), beta = N(0, j)
-    recompute: bool = False  # backward recomputes the LayerNorm and GeLU outputs (smaller stash)
+    recompute: int = 0       # 1: backward rebuilds the LayerNorm and GeLU outputs; 2: the stash keeps
+                             # only each layer's input and backward re-runs the layer's forward
     fwd_fp16: bool = False   # bf16 stage whose forward activations are kept in fp16
 
     @property

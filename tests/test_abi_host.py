@@ -109,6 +109,16 @@ def test_fwd_fp16_validation():
     assert "prepared" in B.gpt_stage_strerror(B.GPTS_EINVAL)
 
 
+def test_recompute_levels_validate_and_shrink_the_stash():
+    s = synth.WORKLOADS[3]
+    sizes = [B.gpt_stage_stash_bytes(B.make_cfg(s.with_(recompute=r))) for r in (0, 1, 2)]
+    assert sizes[0] > sizes[1] > sizes[2] == s.n_layers * s.tokens * s.hidden * 4
+    assert B.gpt_stage_validate(B.make_cfg(s.with_(recompute=3))) == B.GPTS_EINVAL
+    # level 2 moves the layer block into the workspaces
+    w0 = [B.gpt_stage_workspace_bytes(B.make_cfg(s.with_(recompute=r)), 0) for r in (0, 2)]
+    assert w0[1] - w0[0] >= sizes[0] // s.n_layers - s.tokens * s.hidden * 4 - 4096
+
+
 def test_bf16_needs_tile_multiples():
     s = synth.WORKLOADS[1].with_(seq=1000, batch=1)
     assert B.gpt_stage_validate(B.make_cfg(s)) == B.GPTS_ESHAPE

@@ -572,3 +572,23 @@ def test_recompute_variant_identical_results_smaller_stash(dtype):
     T, H, F = shape.tokens, shape.hidden, shape.ffn
     saved = B.gpt_stage_stash_bytes(B.make_cfg(shape)) - B.gpt_stage_stash_bytes(B.make_cfg(rshape))
     assert saved == shape.n_layers * (2 * T * H + T * F) * e
+    # level 2: the stash keeps only every layer's input; the backward phase runs the layer's
+    # forward again.  Same bits again (decoupled: the forward of micro-batch 1 has overwritten
+    # the forward workspace before the backward of micro-batch 0 re-runs its layers).
+    xshape = shape.with_(recompute=2)
+    only_x = gpu_run(xshape, params, xs, dys, decoupled=True)
+    for a, b in zip(full[0] + full[1], only_x[0] + only_x[1]):
+        assert np.array_equal(a, b)
+    for ga, gb_ in zip(full[2], only_x[2]):
+        for k in ga:
+            assert np.array_equal(ga[k], gb_[k]), k
+    res = 4   # the residual stream is fp32 in both storage types
+    assert B.gpt_stage_stash_bytes(B.make_cfg(xshape)) == shape.n_layers * T * H * res
+    if dtype == "bf16":
+        f16 = gpu_run(shape.with_(recompute=2, hidden=256, ffn=512, fwd_fp16=True), params, xs, dys, decoupled=True)
+        f16_ref = gpu_run(shape.with_(fwd_fp16=True), params, xs, dys, decoupled=True)
+        for a, b in zip(f16[0] + f16[1], f16_ref[0] + f16_ref[1]):
+            assert np.array_equal(a, b)
+        for ga, gb_ in zip(f16[2], f16_ref[2]):
+            for k in ga:
+                assert np.array_equal(ga[k], gb_[k]), k
