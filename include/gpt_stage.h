@@ -368,7 +368,9 @@ int gpt_dpp_plan(int policy, int n_chunks, int n_microbatches, int max_live_stas
                  gpt_dpp_task* tasks, int capacity, int* peak_live_stash);
 
 typedef struct {
-  int32_t n_chunks, n_microbatches, policy, max_live_stash;
+  int32_t n_chunks, n_microbatches, policy;
+  int32_t max_live_stash;         /* BEST_EFFORT: stashes that may be alive at once; <= 0: as many
+                                     as stash_pool holds (the memory at hand decides)          */
   const gpt_stage_params* chunks; /* host array [n_chunks]; all chunks share batch, seq,
                                      hidden and dtype; workspaces may be shared (one stream) */
   const void* const* x;           /* host array [M] of device pointers: inputs of chunk 0   */
@@ -395,6 +397,18 @@ typedef struct {
 
 size_t gpt_dpp_stash_slot_bytes(const gpt_stage_params* chunks, int n_chunks); /* 0 on bad input */
 size_t gpt_dpp_act_slot_bytes(const gpt_stage_cfg* cfg);                        /* 0 on bad input */
+
+/* The best-effort allowance from the memory that is free right now on the current device
+ * (section 5.2: breadth first "as long as it does not cause" out-of-memory): how many
+ * (micro-batch, chunk) activation stashes can be alive at once if the stash pool takes what
+ * hipMemGetInfo reports free, minus reserve_bytes (whatever else the caller still has to
+ * allocate) and minus the boundary-buffer pool.  Rounded down to whole windows (a multiple of
+ * n_chunks), at most n_chunks*n_microbatches, 0 if not even one micro-batch fits.  Writes the
+ * pool sizes to allocate for it (either pointer may be NULL).  Returns the allowance or a
+ * negative gpts_status.  Allocates nothing. */
+int gpt_dpp_allowance_from_free_memory(const gpt_stage_params* chunks, int n_chunks,
+                                       int n_microbatches, size_t reserve_bytes,
+                                       size_t* stash_pool_bytes, size_t* act_pool_bytes);
 
 /* Enqueues every task of the job on `stream` in the order gpt_dpp_plan gives, through the
  * decoupled entry points; stash slots and boundary buffers are taken from the two pools and

@@ -38,6 +38,7 @@ EXPORTS = (
     "gpt_stage_trace_create", "gpt_stage_trace_destroy", "gpt_stage_trace_reset",
     "gpt_stage_trace_collect", "gpt_stage_trace_op_name",
     "gpt_dpp_plan", "gpt_dpp_stash_slot_bytes", "gpt_dpp_act_slot_bytes", "gpt_dpp_run",
+    "gpt_dpp_allowance_from_free_memory",
     "gpt_fbd_coord_create", "gpt_fbd_coord_destroy", "gpt_fbd_coord_expected", "gpt_fbd_coord_register",
     "gpt_fbd_coord_align", "gpt_fbd_coord_ready", "gpt_fbd_coord_execute", "gpt_fbd_coord_simulate",
 )
@@ -146,6 +147,7 @@ def lib() -> C.CDLL:
         "gpt_dpp_stash_slot_bytes": (sz, [parp, i32]),
         "gpt_dpp_act_slot_bytes": (sz, [cfgp]),
         "gpt_dpp_run": (i32, [C.POINTER(gpt_dpp_job), vp, C.POINTER(gpt_dpp_report)]),
+        "gpt_dpp_allowance_from_free_memory": (i32, [parp, i32, i32, sz, C.POINTER(sz), C.POINTER(sz)]),
         "gpt_fbd_coord_create": (i32, [i32, i32, i32p, i32p, i32, i32p, C.POINTER(vp)]),
         "gpt_fbd_coord_destroy": (i32, [vp]),
         "gpt_fbd_coord_expected": (i32, [vp, i32, C.c_char_p]),
@@ -404,6 +406,16 @@ def gpt_dpp_stash_slot_bytes(chunks) -> int:
 
 def gpt_dpp_act_slot_bytes(cfg) -> int:
     return lib().gpt_dpp_act_slot_bytes(C.byref(cfg))
+
+
+def gpt_dpp_allowance_from_free_memory(chunks, n_microbatches: int, reserve_bytes: int = 0):
+    """-> (allowance, stash_pool_bytes, act_pool_bytes)"""
+    sp, ap = C.c_size_t(), C.c_size_t()
+    n = lib().gpt_dpp_allowance_from_free_memory(_params_array(chunks), len(chunks), n_microbatches,
+                                                 reserve_bytes, C.byref(sp), C.byref(ap))
+    if n < 0:
+        _check(n)
+    return n, sp.value, ap.value
 
 
 def gpt_dpp_run(policy: int, chunks, xs, dys, ys, dxs, dparams, stash_pool, act_pool,

@@ -100,6 +100,29 @@ size_t gpt_dpp_act_slot_bytes(const gpt_stage_cfg* cfg) {
   return align256((size_t)cfg->batch * cfg->seq * cfg->hidden * (cfg->dtype == GPTS_BF16 ? 2 : 4));
 }
 
+int gpt_dpp_allowance_from_free_memory(const gpt_stage_params* chunks, int n_chunks, int n_microbatches,
+                                       size_t reserve_bytes, size_t* stash_pool_bytes,
+                                       size_t* act_pool_bytes) {
+  if (!chunks || n_chunks < 1 || n_microbatches < 1 || n_chunks > (1 << 15) || n_microbatches > (1 << 15))
+    return set_error(GPTS_EINVAL, "dpp_allowance: chunks NULL or counts outside [1, 32768]");
+  const size_t slot = gpt_dpp_stash_slot_bytes(chunks, n_chunks);
+  const size_t act_slot = gpt_dpp_act_slot_bytes(&chunks[0].cfg);
+  if (!slot || !act_slot) return set_error(GPTS_ESHAPE, "dpp_allowance: a chunk's cfg is not valid");
+  size_t free_b = 0, total_b = 0;
+  if (hipMemGetInfo(&free_b, &total_b) != hipSuccess) return set_error(GPTS_EHIP, "dpp_allowance: hipMemGetInfo failed");
+  // boundary buffers: a window of W micro-batches keeps at most W + 1 alive; budget for the widest
+  const size_t act_bytes = ((size_t)n_microbatches + 1) * act_slot;
+  const size_t need_first = reserve_bytes + act_bytes;
+  size_t slots = free_b > need_first ? (free_b - need_first) / slot : 0;
+  const size_t all = (size_t)n_chunks * n_microbatches;
+  if (slots > all) slots = all;
+  // whole windows only: the scheduler runs W = slots / chunks micro-batches per window
+  slots = slots / n_chunks * n_chunks;
+  if (stash_pool_bytes) *stash_pool_bytes = slots * slot;
+  if (act_pool_bytes) *act_pool_bytes = act_bytes;
+  return (int)slots;
+}
+
 int gpt_dpp_run(const gpt_dpp_job* job, void* stream, gpt_dpp_report* report) {
   if (!job) return set_error(GPTS_EINVAL, "dpp_run: job is NULL");
   const int C = job->n_chunks, M = job->n_microbatches;
@@ -118,13 +141,20 @@ int gpt_dpp_run(const gpt_dpp_job* job, void* stream, gpt_dpp_report* report) {
     if (!job->x[i] || !job->dy[i] || !job->y[i] || !job->dx[i])
       return set_error(GPTS_EINVAL, "dpp_run: an x / dy / y / dx pointer is NULL");
 
-  std::vector<gpt_dpp_task> plan((size_t)2 * C * M);
-  int peak_stash = 0;
-  const int n = gpt_dpp_plan(job->policy, C, M, job->max_live_stash, plan.data(), (int)plan.size(), &peak_stash);
-  if (n < 0) return n;
-
   const size_t stash_slot = gpt_dpp_stash_slot_bytes(job->chunks, C);
   const size_t act_slot = gpt_dpp_act_slot_bytes(&job->chunks[0].cfg);
+  // best effort without a caller-given allowance: as wide as the stash pool at hand allows
+  // (section 5.2: breadth first "as long as it does not cause" out-of-memory)
+  int allowance = job->max_live_stash;
+  if (job->policy == GPT_DPP_BFC_BEST_EFFORT && allowance <= 0) {
+    const size_t slots = (job->stash_pool && stash_slot) ? job->stash_pool_bytes / stash_slot : 0;
+    allowance = slots > (size_t)C * M ? C * M : (int)slots;
+  }
+  std::vector<gpt_dpp_task> plan((size_t)2 * C * M);
+  int peak_stash = 0;
+  const int n = gpt_dpp_plan(job->policy, C, M, allowance, plan.data(), (int)plan.size(), &peak_stash);
+  if (n < 0) return n;
+
   Pool stash(job->stash_pool, stash_slot, job->stash_pool ? job->stash_pool_bytes : 0);
   Pool act(job->act_pool, act_slot, job->act_pool ? job->act_pool_bytes : 0);
 
