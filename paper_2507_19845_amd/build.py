@@ -8,6 +8,7 @@ paper_2507_19845_amd/libgptstage.so.  No GPU is needed to build.
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -25,11 +26,43 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=f
 FLAGS += os.environ.get("GPTS_HIPCC_FLAGS", "").split()   # e.g. -DGPTS_BIG_WAVES=8 for experiments
 
 
+# gemm_mi16_kernel keeps its 256 accumulators in AGPRs a0..a255 by hand, across separate inline
+# assembly statements; the compiler only knows them as clobbered.  That is safe as long as the
+# register allocator never needs an AGPR of its own in that kernel, i.e. as long as nothing is
+# spilled.  The build checks the compiler's resource report for every instance and fails
+# otherwise (a change of compiler or flags must not corrupt results silently).
+PINNED_AGPR_KERNEL = "gemm_mi16_kernel"
+
+
+def _check_pinned_accumulators(src: str, remarks: str) -> None:
+    blocks = re.split(r"remark: Function Name: ", remarks)[1:]
+    seen = 0
+    for b in blocks:
+        name = b.split()[0]
+        if PINNED_AGPR_KERNEL not in name:
+            continue
+        seen += 1
+        val = {k: int(v) for k, v in re.findall(r"remark:\s+([A-Za-z ]+?)(?: \[bytes/lane\])?: (\d+) \[", b)}
+        ok = (val.get("AGPRs") == 256 and val.get("ScratchSize") == 0 and val.get("VGPRs Spill") == 0
+              and val.get("SGPRs Spill") == 0 and val.get("VGPRs", 999) < 256)
+        if not ok:
+            raise RuntimeError(f"{src}: {name} must use exactly the 256 hand-placed AGPRs and spill nothing; "
+                               f"the compiler reports {val}")
+    if seen == 0:
+        raise RuntimeError(f"{src}: no resource report found for {PINNED_AGPR_KERNEL}")
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.basename(src) + ".o")
-    cmd = [HIPCC, *FLAGS, "-c", src, "-o", obj]
+    pinned = os.path.basename(src) == "gemm_mfma.hip"
+    extra = ["-Rpass-analysis=kernel-resource-usage"] if pinned else []
+    cmd = [HIPCC, *FLAGS, *extra, "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
-    err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+    if pinned and r.returncode == 0:
+        _check_pinned_accumulators(src, r.stderr)
+    err = "\n".join(l for l in r.stderr.splitlines()
+                    if "packed-fp32-ops" not in l and "kernel-resource-usage" not in l
+                    and not (pinned and re.match(r"^\s*\d*\s*\|", l)))   # source excerpts of the remarks
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{err}")
     if err.strip():

@@ -1,29 +1,38 @@
-// bf16 matrix products on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16,
-// fp32 accumulation) for the three forms the stage needs:
+// bf16 (and, for the forward phase of cfg.fwd_fp16 stages, fp16) matrix products on the gfx950
+// matrix cores, fp32 accumulation, for the three forms the stage needs:
 //   NT  C[M,N]   = A[M,K] B[N,K]^T     forward linears   (both operands K-contiguous)
 //   NN  C[M,N]   = A[M,K] B[K,N]       data gradients    (B is K-major)
 //   TN  Cf[M,N] += A[K,M]^T B[K,N]     weight gradients  (both operands K-major)
 //
-// Design (one workgroup = 4 waves in a 2x2 grid, one BMxBN output tile):
-//  * K is walked in slices of 64.  Each slice of both operands is copied
-//    global -> LDS by the DMA path (global_load_lds_dwordx4: no registers, no
-//    ds_write), double buffered, one barrier per slice.
-//  * The DMA writes 16-byte slots in lane order, so bank-conflict avoidance is
-//    done by choosing WHICH global chunk a lane fetches (an XOR swizzle of the
-//    chunk index), never by padding.
-//  * K-contiguous operands are stored [row][64 k] and fragments are read with
-//    ds_read_b128.  K-major operands are stored as they sit in memory
-//    ([k][rows]) and fragments are read with the transposing LDS load
-//    ds_read_b64_tr_b16, so no operand is ever transposed in HBM.  The order of
-//    k inside a fragment is a free choice as long as both operands agree; it is
-//    chosen per form so the transposing reads hit 8 consecutive k-rows.
-//  * The two MFMA operands are swapped (D = B-fragment x A-fragment), which
-//    makes each lane own 4 consecutive output columns of one row: 8-byte bf16 /
-//    16-byte fp32 global accesses in the epilogue, where bias, GeLU, GeLU',
-//    residual and the fp32 accumulation are fused.
-//  * Workgroup -> tile map: consecutive workgroup ids land on different XCDs, so
-//    ids are first regrouped per XCD and then walked in bands of 4 tile rows to
-//    keep each XCD's L2 working set to a compact patch of the output.
+// Two kernels:
+//  * gemm_mi16_kernel -- the one that does almost all the work.  256x256 output tile per
+//    workgroup of 4 waves (2x2, 128x128 per wave), K in slices of 32 through a ring of FOUR LDS
+//    stages (three slices in flight), v_mfma_f32_16x16x32 with the wave's 64 accumulator blocks
+//    placed by hand in AGPRs a0..a255 (agpr_ops.hpp).  It serves the forward products (on raw
+//    weights or on weight images), the data gradients through weight images, and the weight
+//    gradients (both operands K-major, fragments by transposing LDS reads; the contraction may
+//    run over several buffers, one per micro-batch).
+//  * gemm_mfma_kernel -- v_mfma_f32_32x32x16 with compiler-allocated accumulators, templated
+//    on tile and stage count: data gradients on raw weights (256x256x32, five-stage ring with
+//    paired fetches), contraction lengths that are not a multiple of 128, and the 128x128x64
+//    two-stage tiles for products of fewer than 100 large tiles.
+// Common to both:
+//  * Slices go global -> LDS by the DMA path (global_load_lds_dwordx4: no registers, no
+//    ds_write), issued from inline assembly and waited for with explicit vmcnt counts, spread
+//    between the matrix instructions; one barrier per slice.
+//  * The DMA writes 16-byte slots in lane order, so bank-conflict avoidance is done by
+//    choosing WHICH global chunk a lane fetches (an XOR swizzle of the chunk index), never by
+//    padding.  Weight images (prepare_image_kernel) store a weight in exactly that LDS order, so
+//    that every DMA instruction copies 1 KiB of contiguous memory.
+//  * K-major operands are stored in LDS as they sit in memory ([k][rows]) and fragments are read
+//    with the transposing LDS load ds_read_b64_tr_b16, so no operand is ever transposed in HBM.
+//  * The two MFMA operands are swapped (D = B-fragment x A-fragment): a lane owns consecutive
+//    output columns of one row.  The epilogue stages the wave's block through the (then free)
+//    pipeline LDS and reads it back row-major, so that every global access of the fused bias /
+//    GeLU / GeLU' / residual / fp32-accumulate epilogues covers whole cache lines.
+//  * Workgroup -> tile map: consecutive workgroup ids land on different XCDs, so ids are first
+//    regrouped per XCD and then walked in bands of 4 tile rows to keep each XCD's L2 working
+//    set to a compact patch of the output.
 #include <type_traits>
 #include <utility>
 
