@@ -29,10 +29,13 @@ Run as a script to print the table for a sequence length (default 512):
 from __future__ import annotations
 
 import math
+import os
 import sys
 import time
 
 import numpy as np
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))   # run as a script too
 
 from oracle import gpt_stage_oracle as orc
 from paper_2507_19845_amd import synth
@@ -186,5 +189,4 @@ def main():
 
 
 if __name__ == "__main__":
-    sys.path.insert(0, __import__("os").path.dirname(__import__("os").path.dirname(__import__("os").path.abspath(__file__))))
     main()
