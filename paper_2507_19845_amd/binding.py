@@ -103,6 +103,14 @@ def lib() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise FileNotFoundError(
             f"{LIB_PATH} not found: build it with `python -m paper_2507_19845_amd.build`")
+    # a library built from other sources than the ones beside it would make every parity
+    # statement meaningless: refuse it (the stamp is written by paper_2507_19845_amd.build)
+    stamp = LIB_PATH + ".srchash"
+    if os.path.exists(stamp) and os.path.isdir(os.path.join(_HERE, "csrc")):
+        from . import build as _build
+        if open(stamp).read().strip() != _build.source_hash():
+            raise RuntimeError(f"{LIB_PATH} is older than its sources: rebuild with "
+                               "`python -m paper_2507_19845_amd.build`")
     L = C.CDLL(LIB_PATH)
     vp, i32, sz, f32 = C.c_void_p, C.c_int, C.c_size_t, C.c_float
     cfgp, parp = C.POINTER(gpt_stage_cfg), C.POINTER(gpt_stage_params)

@@ -7,6 +7,7 @@ paper_2507_19845_amd/libgptstage.so.  No GPU is needed to build.
 """
 from __future__ import annotations
 
+import hashlib
 import os
 import re
 import subprocess
@@ -17,6 +18,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgptstage.so")
+STAMP = LIB + ".srchash"
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instructions are switched off on purpose for every device pass
@@ -74,14 +76,30 @@ def sources():
     return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
+def source_hash() -> str:
+    """Hash of everything the library is built from (kernel sources, their headers, the C header)."""
+    h = hashlib.sha256()
+    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".hpp")))
+    files.append(os.path.join(os.path.dirname(HERE), "include", "gpt_stage.h"))
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
 def build_library(jobs: int = 8) -> str:
     os.makedirs(OBJ, exist_ok=True)
+    stamp = source_hash()
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(_compile, sources()))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
+    # what the library was built from: the binding refuses a library older than its sources
+    with open(STAMP, "w") as f:
+        f.write(stamp + "\n")
     return LIB
 
 
