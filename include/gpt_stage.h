@@ -453,6 +453,41 @@ int gpt_fbd_coord_simulate(void* coord, const int32_t* prog_start, const int32_t
                            int32_t* log, int log_capacity, int32_t* n_executed,
                            int32_t* deadlocked);
 
+/* ---- run-time scheduling of the task matrix: the ready set ----------------------------------
+ * Section 5.2: with asynchronous transfers "a compute thread can always pick the highest-priority
+ * ready input for execution", and the scheduler is to be "resource-aware".  A task is READY when
+ * the tasks it depends on have been issued and its external input has arrived: x of micro-batch i
+ * for F(i,0), dy of micro-batch i for B(i,C-1).  Its priority is its position in the static plan
+ * of the policy (gpt_dpp_plan), so with every input present from the start the order IS that
+ * plan.  Two rules keep results and memory those of the plan: backward tasks of one chunk go in
+ * ascending micro-batch order (the order the chunk's gradients accumulate in, hence every result
+ * bit), and a micro-batch is only started while the free stash slots, after setting aside what
+ * the micro-batches in flight still need, cover all its chunks -- twice that when it would start
+ * ahead of a lower-numbered one, which must still be able to pass through (a started
+ * micro-batch can always finish; the width follows the memory at hand).
+ *
+ * gpt_dpp_simulate_ready (host only, discrete time, one task per step): x_at[i] / dy_at[i] = the
+ * step from which the input / output gradient of micro-batch i is present (NULL: all from step 0).
+ * dynamic = 0: the static plan, idling whenever its next task's input is missing; dynamic = 1:
+ * the first ready task of the plan.  order receives the tasks in order of issue; *n_steps the
+ * steps used, *idle_steps those without a task (either may be NULL).  Returns the number of
+ * tasks or a negative gpts_status.
+ *
+ * gpt_dpp_run_ready: the same scheduler driving the GPU.  x_ready[i] / dy_ready[i] are hipEvent_t
+ * (NULL array or NULL entry: present from the start) that whoever delivers the data records on
+ * its own stream; they are polled with hipEventQuery.  Tasks are issued on `stream` as in
+ * gpt_dpp_run.  Unlike every other call this one BLOCKS the calling host thread until all tasks
+ * have been issued, waiting (yielding) while nothing is ready, and gives up with GPTS_EHIP after
+ * timeout_seconds without progress -- tasks issued until then have been enqueued.  The stash
+ * pool needs at least one slot per chunk, the boundary pool min(micro-batches, stash slots) + 1
+ * buffers.  order_out (may be NULL) receives the order of issue. */
+int gpt_dpp_simulate_ready(int policy, int n_chunks, int n_microbatches, int max_live_stash,
+                           const int32_t* x_at, const int32_t* dy_at, int dynamic,
+                           gpt_dpp_task* order, int capacity, int32_t* n_steps, int32_t* idle_steps);
+int gpt_dpp_run_ready(const gpt_dpp_job* job, const void* const* x_ready, const void* const* dy_ready,
+                      double timeout_seconds, void* stream, gpt_dpp_task* order_out, int capacity,
+                      gpt_dpp_report* report);
+
 #ifdef __cplusplus
 }
 #endif

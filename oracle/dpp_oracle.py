@@ -115,3 +115,74 @@ def gradient_ready_position(order, n_chunks: int):
         if phase == "B":
             last[j] = pos
     return last
+
+
+# ---- run-time scheduling: the ready set -----------------------------------------------------
+def ready_set_schedule(policy: str, n_chunks: int, n_microbatches: int, max_live_stash: int = 0,
+                       x_at=None, dy_at=None, dynamic: bool = True):
+    """Section 5.2, lightweight communication library: "a compute thread can always pick the
+    highest-priority ready input for execution".  Discrete time, one task per step.
+
+    External inputs: x of micro-batch i is present from step x_at[i] (needed by F(i,0)), dy of
+    micro-batch i from step dy_at[i] (needed by B(i,C-1)); None = present from step 0.
+    A task may run at a step if
+      * the tasks it needs (see dependencies_hold) have run and its external input is present;
+      * backward tasks of one chunk run in ascending micro-batch order (gradient accumulation
+        order is that of the static plan);
+      * memory: a forward task needs a free stash slot; F(i,0) additionally needs that the free
+        slots, minus what the micro-batches in flight still need to reach the last chunk, cover
+        all n_chunks of the new micro-batch -- and n_chunks more when a lower-numbered micro-batch
+        has not started yet (its backward tasks go first, so it must be able to pass through).
+        The number of slots is the peak of the static plan.
+    Priority = position in the static plan of `policy`.  dynamic=False: only the plan's next
+    task is considered (a static schedule waiting for its input).
+    Returns (order, n_steps, idle_steps)."""
+    C, M = n_chunks, n_microbatches
+    plan = traversal(policy, C, M, max_live_stash)
+    slots = peak_live_stash(plan)
+    x_at = [0] * M if x_at is None else list(x_at)
+    dy_at = [0] * M if dy_at is None else list(dy_at)
+    done, order = set(), []
+    step = idle = 0
+
+    def free_slots():
+        return slots - sum(1 for (ph, i, j) in done if ph == "F") + sum(1 for (ph, i, j) in done if ph == "B")
+
+    def still_needed():
+        need = 0
+        for i in range(M):
+            fwd = sum(1 for j in range(C) if ("F", i, j) in done)
+            if 0 < fwd < C:
+                need += C - fwd
+        return need
+
+    def can_run(t):
+        ph, i, j = t
+        if ph == "F":
+            if j == 0:
+                if x_at[i] > step:
+                    return False
+                lower_started = all(("F", k, 0) in done for k in range(i))
+                return free_slots() - still_needed() >= (C if lower_started else 2 * C)
+            return ("F", i, j - 1) in done and free_slots() > 0
+        if ("F", i, j) not in done:
+            return False
+        if any(("B", k, j) not in done for k in range(i)):
+            return False
+        if j == C - 1:
+            return dy_at[i] <= step
+        return ("B", i, j + 1) in done
+
+    guard = max(x_at + dy_at) + 4 * len(plan) + 8
+    while len(done) < len(plan):
+        assert step <= guard, "no progress"
+        pending = [t for t in plan if t not in done]
+        candidates = pending if dynamic else pending[:1]
+        pick = next((t for t in candidates if can_run(t)), None)
+        if pick is None:
+            idle += 1
+        else:
+            done.add(pick)
+            order.append(pick)
+        step += 1
+    return order, step, idle

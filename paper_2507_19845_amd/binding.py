@@ -38,7 +38,7 @@ EXPORTS = (
     "gpt_stage_trace_create", "gpt_stage_trace_destroy", "gpt_stage_trace_reset",
     "gpt_stage_trace_collect", "gpt_stage_trace_op_name",
     "gpt_dpp_plan", "gpt_dpp_stash_slot_bytes", "gpt_dpp_act_slot_bytes", "gpt_dpp_run",
-    "gpt_dpp_allowance_from_free_memory",
+    "gpt_dpp_allowance_from_free_memory", "gpt_dpp_simulate_ready", "gpt_dpp_run_ready",
     "gpt_fbd_coord_create", "gpt_fbd_coord_destroy", "gpt_fbd_coord_expected", "gpt_fbd_coord_register",
     "gpt_fbd_coord_align", "gpt_fbd_coord_ready", "gpt_fbd_coord_execute", "gpt_fbd_coord_simulate",
 )
@@ -156,6 +156,9 @@ def lib() -> C.CDLL:
         "gpt_dpp_act_slot_bytes": (sz, [cfgp]),
         "gpt_dpp_run": (i32, [C.POINTER(gpt_dpp_job), vp, C.POINTER(gpt_dpp_report)]),
         "gpt_dpp_allowance_from_free_memory": (i32, [parp, i32, i32, sz, C.POINTER(sz), C.POINTER(sz)]),
+        "gpt_dpp_simulate_ready": (i32, [i32, i32, i32, i32, i32p, i32p, i32, C.POINTER(gpt_dpp_task), i32, i32p, i32p]),
+        "gpt_dpp_run_ready": (i32, [C.POINTER(gpt_dpp_job), C.POINTER(vp), C.POINTER(vp), C.c_double, vp,
+                                    C.POINTER(gpt_dpp_task), i32, C.POINTER(gpt_dpp_report)]),
         "gpt_fbd_coord_create": (i32, [i32, i32, i32p, i32p, i32, i32p, C.POINTER(vp)]),
         "gpt_fbd_coord_destroy": (i32, [vp]),
         "gpt_fbd_coord_expected": (i32, [vp, i32, C.c_char_p]),
@@ -424,6 +427,64 @@ def gpt_dpp_allowance_from_free_memory(chunks, n_microbatches: int, reserve_byte
     if n < 0:
         _check(n)
     return n, sp.value, ap.value
+
+
+def gpt_dpp_simulate_ready(policy: int, n_chunks: int, n_microbatches: int, max_live_stash: int = 0,
+                           x_at=None, dy_at=None, dynamic: bool = True):
+    """-> ([(phase, microbatch, chunk), ...] in order of issue, n_steps, idle_steps)"""
+    cap = 2 * max(n_chunks, 0) * max(n_microbatches, 0)
+    arr = (gpt_dpp_task * max(cap, 1))()
+    steps, idle = C.c_int32(0), C.c_int32(0)
+    xa = _i32(list(x_at)) if x_at is not None else None
+    da = _i32(list(dy_at)) if dy_at is not None else None
+    n = lib().gpt_dpp_simulate_ready(policy, n_chunks, n_microbatches, max_live_stash, xa, da,
+                                     1 if dynamic else 0, arr, cap, C.byref(steps), C.byref(idle))
+    if n < 0:
+        _check(n)
+    return [(arr[k].phase, arr[k].microbatch, arr[k].chunk) for k in range(n)], steps.value, idle.value
+
+
+def _dpp_job(policy, chunks, xs, dys, ys, dxs, dparams, stash_pool, act_pool, max_live_stash, grad_ready):
+    def ptrs(ts):
+        a = (C.c_void_p * len(ts))()
+        for k, t in enumerate(ts):
+            a[k] = _ptr(t)
+        return a
+    keep = [_params_array(chunks), ptrs(xs), ptrs(dys), ptrs(ys), ptrs(dxs), ptrs(dparams)]
+    ev = None
+    if grad_ready is not None:
+        ev = (C.c_void_p * len(grad_ready))()
+        for k, e in enumerate(grad_ready):
+            ev[k] = _event(e)
+    job = gpt_dpp_job(n_chunks=len(chunks), n_microbatches=len(xs), policy=policy,
+                      max_live_stash=max_live_stash, chunks=keep[0], x=keep[1], dy=keep[2],
+                      y=keep[3], dx=keep[4], dparams=keep[5],
+                      stash_pool=_ptr(stash_pool), stash_pool_bytes=stash_pool.numel() if stash_pool is not None else 0,
+                      act_pool=_ptr(act_pool), act_pool_bytes=act_pool.numel() if act_pool is not None else 0,
+                      grad_ready=ev)
+    return job, keep + [ev]
+
+
+def gpt_dpp_run_ready(policy: int, chunks, xs, dys, ys, dxs, dparams, stash_pool, act_pool,
+                      x_ready=None, dy_ready=None, max_live_stash: int = 0, timeout_seconds: float = 30.0,
+                      grad_ready=None, stream=None):
+    """x_ready / dy_ready: None or one torch.cuda.Event (or None) per micro-batch.
+    -> (gpt_dpp_report, [(phase, microbatch, chunk), ...] in order of issue)"""
+    job, keep = _dpp_job(policy, chunks, xs, dys, ys, dxs, dparams, stash_pool, act_pool, max_live_stash, grad_ready)
+
+    def events(evs):
+        if evs is None:
+            return None
+        a = (C.c_void_p * len(evs))()
+        for k, e in enumerate(evs):
+            a[k] = _event(e) if e is not None else None
+        return a
+    xe, de = events(x_ready), events(dy_ready)
+    cap = 2 * len(chunks) * len(xs)
+    order = (gpt_dpp_task * cap)()
+    rep = gpt_dpp_report()
+    _check(lib().gpt_dpp_run_ready(C.byref(job), xe, de, timeout_seconds, _stream(stream), order, cap, C.byref(rep)))
+    return rep, [(order[k].phase, order[k].microbatch, order[k].chunk) for k in range(rep.n_tasks)]
 
 
 def gpt_dpp_run(policy: int, chunks, xs, dys, ys, dxs, dparams, stash_pool, act_pool,

@@ -281,3 +281,130 @@ def test_dpp_full_size_four_chunks_against_the_stage_run():
     err = max_norm_err(bfc[0][0], y_ref)
     print(f"[parity] dpp 4 chunks, y of micro-batch 0 vs oracle: {err:.3e}", flush=True)
     assert err <= TOL["bf16"]
+
+
+# ---- run-time scheduling: the ready set (host) ------------------------------------------------
+def _lib_ready(policy, C, M, cap, x_at, dy_at, dynamic):
+    order, steps, idle = B.gpt_dpp_simulate_ready(POLICY[policy], C, M, cap, x_at, dy_at, dynamic)
+    return [("F" if p == B.GPT_DPP_FWD else "B", i, j) for p, i, j in order], steps, idle
+
+
+@pytest.mark.parametrize("policy,cap", [("dfc", 0), ("bfc", 0), ("bfc_best_effort", 6)])
+def test_ready_set_with_everything_present_is_the_static_plan(policy, cap):
+    C, M = 3, 4
+    want = dpo.traversal(policy, C, M, cap)
+    for dynamic in (False, True):
+        got, steps, idle = _lib_ready(policy, C, M, cap, None, None, dynamic)
+        assert got == want and steps == len(want) and idle == 0
+        assert dpo.ready_set_schedule(policy, C, M, cap, dynamic=dynamic) == (want, len(want), 0)
+
+
+def test_ready_set_works_around_a_late_input_where_the_static_plan_idles():
+    """Micro-batch 0's input is late.  The static breadth-first plan starts with F(0,0) and idles
+    until it arrives; the ready-set scheduler runs the other micro-batches meanwhile."""
+    C, M = 2, 4
+    x_at = [6, 0, 0, 0]
+    static = _lib_ready("bfc", C, M, 0, x_at, None, False)
+    dynamic = _lib_ready("bfc", C, M, 0, x_at, None, True)
+    assert static[2] == 6 and static[1] == 2 * C * M + 6          # six idle steps up front
+    assert dynamic[2] == 0 and dynamic[1] == 2 * C * M            # none: six other tasks were ready
+    assert dynamic[0][:6] == [("F", 1, 0), ("F", 2, 0), ("F", 3, 0), ("F", 1, 1), ("F", 2, 1), ("F", 3, 1)]
+    assert dpo.dependencies_hold(dynamic[0], C, M)
+    # backward on each chunk still in ascending micro-batch order
+    for j in range(C):
+        assert [i for ph, i, jj in dynamic[0] if ph == "B" and jj == j] == list(range(M))
+    assert static == dpo.ready_set_schedule("bfc", C, M, 0, x_at, None, False)
+    assert dynamic == dpo.ready_set_schedule("bfc", C, M, 0, x_at, None, True)
+
+
+def test_ready_set_matches_the_oracle_on_random_arrivals_and_respects_memory():
+    rng = np.random.default_rng(7)
+    for trial in range(60):
+        C, M = int(rng.integers(1, 5)), int(rng.integers(1, 7))
+        policy = ("dfc", "bfc", "bfc_best_effort")[trial % 3]
+        cap = int(rng.integers(0, C * M + 1)) if policy == "bfc_best_effort" else 0
+        x_at = [int(v) for v in rng.integers(0, 3 * C * M, M)]
+        dy_at = [int(v) for v in rng.integers(0, 5 * C * M, M)]
+        for dynamic in (False, True):
+            got = _lib_ready(policy, C, M, cap, x_at, dy_at, dynamic)
+            want = dpo.ready_set_schedule(policy, C, M, cap, x_at, dy_at, dynamic)
+            assert got == want, (policy, C, M, cap, x_at, dy_at, dynamic)
+            order = got[0]
+            assert dpo.dependencies_hold(order, C, M)
+            assert dpo.peak_live_stash(order) <= dpo.peak_live_stash(dpo.traversal(policy, C, M, cap))
+            assert len(order) == 2 * C * M
+        # the ready set never needs more steps than the static plan
+        assert _lib_ready(policy, C, M, cap, x_at, dy_at, True)[1] <= _lib_ready(policy, C, M, cap, x_at, dy_at, False)[1]
+
+
+def test_ready_set_bad_arguments():
+    with pytest.raises(B.GptStageError):
+        B.gpt_dpp_simulate_ready(9, 2, 2)
+    with pytest.raises(B.GptStageError):
+        B.gpt_dpp_simulate_ready(B.GPT_DPP_BFC, 2, 2, x_at=[-1, 0])
+    arr = (B.gpt_dpp_task * 2)()
+    assert B.lib().gpt_dpp_simulate_ready(B.GPT_DPP_BFC, 2, 2, 0, None, None, 1, arr, 2, None, None) == B.GPTS_ENOMEM
+
+
+@pytest.mark.gpu
+def test_ready_set_driver_on_the_gpu_inputs_arriving_out_of_order():
+    """gpt_dpp_run_ready with the inputs' arrival signalled by events: micro-batch 0's x is held
+    back behind a spin kernel on a side stream, so the driver starts with the others; every
+    result bit equals the static run, and an event that is never recorded ends in a time-out
+    error, not a hang."""
+    import torch
+    C, M = 2, 3
+    shape = synth.StageShape(name="dpp_ready", n_layers=2, hidden=128, n_heads=2, head_dim=64, ffn=256, seq=128,
+                             batch=1, dtype="bf16", n_microbatches=M, bias_std=0.02)
+    params_np = [{k: synth.to_storage(v, "bf16") for k, v in synth.make_layer_params(shape, l, 0).items()}
+                 for l in range(shape.n_layers)]
+    ref = _run_dpp(shape, C, M, B.GPT_DPP_BFC, 0, params_np)
+    cfg = ref[3]
+    nparam = B.gpt_stage_param_count(cfg)
+    ws = torch.empty(max(B.gpt_stage_workspace_bytes(cfg, 1), 256), dtype=torch.uint8, device="cuda")
+    chunks, weights, dps = [], [], []
+    for j in range(C):
+        w = torch.empty(nparam, dtype=torch.bfloat16, device="cuda")
+        for tid, name in enumerate(synth.TENSOR_NAMES):
+            off, n = B.gpt_stage_param_offset(cfg, 0, tid)
+            w[off:off + n].copy_(B.to_device(params_np[j][name].reshape(-1), "bf16"))
+        weights.append(w)
+        dps.append(torch.zeros(nparam, dtype=torch.float32, device="cuda"))
+        chunks.append(B.gpt_stage_params(cfg=cfg, weights=w.data_ptr(), workspace=ws.data_ptr(), prepared=None, trace=None))
+    xs = [B.to_device(synth.make_x(shape, 0, m), "bf16") for m in range(M)]
+    dys = [B.to_device(synth.make_dy(shape, 0, m), "bf16") for m in range(M)]
+    ys, dxs = [torch.empty_like(x) for x in xs], [torch.empty_like(x) for x in xs]
+    stash = torch.empty(B.gpt_dpp_stash_slot_bytes(chunks) * C * M, dtype=torch.uint8, device="cuda")
+    act = torch.empty(B.gpt_dpp_act_slot_bytes(cfg) * (M + 1), dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    x_ready = [torch.cuda.Event() for _ in range(M)]
+    torch.cuda.synchronize()
+    x_ready[1].record()
+    x_ready[2].record()                       # present at once
+    with torch.cuda.stream(side):
+        torch.cuda._sleep(200_000_000)        # ~0.1 s before micro-batch 0's input "arrives"
+        x_ready[0].record(side)
+    rep, order = B.gpt_dpp_run_ready(B.GPT_DPP_BFC, chunks, xs, dys, ys, dxs, dps, stash, act, x_ready=x_ready)
+    torch.cuda.synchronize()
+    assert rep.n_tasks == 2 * C * M
+    assert order[0] == (B.GPT_DPP_FWD, 1, 0)                      # did not wait for micro-batch 0
+    named = [("F" if p == B.GPT_DPP_FWD else "B", i, j) for p, i, j in order]
+    assert dpo.dependencies_hold(named, C, M)
+    got = ([B.to_host(t) for t in ys], [B.to_host(t) for t in dxs], [t.cpu().numpy() for t in dps])
+    for a, b in zip(ref[:3], got):
+        for ta, tb in zip(a, b):
+            assert np.array_equal(ta, tb)
+    # an input that never arrives: the call gives up instead of waiting for ever
+    never = torch.cuda.Event()
+    never.record(side)                        # creates the event handle ...
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        torch.cuda._sleep(2_000_000_000)      # ... and this re-record completes only after ~1 s
+        never.record(side)
+    for d in dps:
+        d.zero_()
+    with pytest.raises(B.GptStageError) as e:
+        B.gpt_dpp_run_ready(B.GPT_DPP_BFC, chunks, xs, dys, ys, dxs, dps, stash, act,
+                            dy_ready=[never, None, None], timeout_seconds=0.2)
+    assert e.value.code == B.GPTS_EHIP and "did not arrive" in str(e.value)
+    torch.cuda.synchronize()
