@@ -109,6 +109,32 @@ def test_split_backward_data_phase_then_one_weight_phase(mode):
     _report(shape.name, compare(shape, split, oracle_run(shape, params, xs, dys)))
 
 
+def test_split_backward_other_paths():
+    """The weight phase where one launch per linear is not possible: tokens per micro-batch not a
+    multiple of 128 (one accumulating product per micro-batch, bit-identical to the unsplit
+    run), and a single micro-batch (one product, nothing to concatenate)."""
+    shape = W[1].with_(name="bf16_split_192", n_layers=2, hidden=2048, n_heads=16, head_dim=128, ffn=4096,
+                       seq=192, batch=1, bias_std=0.02, ln_jitter=0.1)
+    print(f"[case] split backward, fallback paths {shape}", flush=True)
+    params, xs, dys = _inputs(shape, n_mb=2)
+    whole = gpu_run(shape, params, xs, dys, decoupled=True)
+    split = gpu_run(shape, params, xs, dys, decoupled=True, split_wgrad=True)
+    for a, b in zip(whole[0] + whole[1], split[0] + split[1]):
+        assert np.array_equal(a, b)
+    for ga, gb in zip(whole[2], split[2]):
+        for k in ga:
+            assert np.array_equal(ga[k], gb[k]), k
+    one = shape.with_(name="bf16_split_one", seq=256)
+    params, xs, dys = _inputs(one, n_mb=1)
+    whole = gpu_run(one, params, xs, dys, decoupled=True)
+    split = gpu_run(one, params, xs, dys, decoupled=True, split_wgrad=True)
+    assert np.array_equal(whole[0][0], split[0][0]) and np.array_equal(whole[1][0], split[1][0])
+    for ga, gb in zip(whole[2], split[2]):
+        for k in ga:
+            assert np.array_equal(ga[k], gb[k]), k     # one segment: the same product, the same bits
+    _report(one.name, compare(one, split, oracle_run(one, params, xs, dys)))
+
+
 def test_backward_stream_waits_for_the_forward_event():
     """The forward stream is held back by a long spin kernel; the backward stream
     must still see a complete stash because bwd_only waits on the event that the
