@@ -115,11 +115,11 @@ typedef struct {
                             contents undefined between calls; two calls that
                             may overlap in time must not share it            */
   const void* prepared;  /* NULL, or device buffer filled by gpt_stage_prepare() for the
-                            CURRENT contents of `weights` (bf16 stages): the weight
-                            matrices re-laid-out as tiled images the matrix-product
-                            kernels copy with fully contiguous transfers.  Same
-                            results bit for bit, faster forward and dgrad products.
-                            Must be rebuilt whenever the weights change.           */
+                            CURRENT contents of `weights` and THIS cfg (bf16 stages): the weight
+                            matrices re-laid-out as tiled images the forward matrix products
+                            copy with fully contiguous transfers (fp16 images with
+                            cfg.fwd_fp16).  Same results bit for bit, faster forward
+                            products.  Must be rebuilt whenever the weights change.        */
   void*       trace;     /* NULL, or a tracer from gpt_stage_trace_create(): every
                             operator of the call is then bracketed by a pair of
                             hipEvents on the stream (see "operator tracer")    */
@@ -156,11 +156,13 @@ double gpt_stage_model_flops(const gpt_stage_cfg* cfg, int causal_aware);
  * the thread's next failing call. */
 const char* gpt_stage_strerror(int code);
 
-/* Prepared weights (optional, bf16 stages).  gpt_stage_prepare() enqueues kernels that
- * read p->weights and write `prepared` (device, gpt_stage_prepared_bytes(): about twice
- * the weight bytes -- one image for the forward products, one for the data gradients).
- * Call it once per weight update (e.g. once per optimizer step, shared by all
- * micro-batches), then pass the buffer as p->prepared.  p->prepared is ignored here. */
+/* Prepared weights (optional, bf16 stages; required with cfg.fwd_fp16).  gpt_stage_prepare()
+ * enqueues kernels that read p->weights and write `prepared` (device,
+ * gpt_stage_prepared_bytes(): about the weight bytes -- one image per weight matrix, for the
+ * forward products; the data gradients read the raw weights at the same speed).  Rebuilding
+ * costs a read and a write of the weights, and pays once a few micro-batches share the images:
+ * call it once per weight update (e.g. once per optimizer step), then pass the buffer as
+ * p->prepared.  p->prepared is ignored here. */
 size_t gpt_stage_prepared_bytes(const gpt_stage_cfg* cfg);   /* 0 for fp32 stages */
 int gpt_stage_prepare(const gpt_stage_params* p, void* prepared, void* stream);
 

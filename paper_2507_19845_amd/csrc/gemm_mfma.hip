@@ -700,9 +700,13 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const MfmaArgs a) {
 // is two transposing reads: lane group lane>>4 is the k-octet, lane&15 the column.
 // F16: both operands hold fp16 values (A an activation stored in fp16, B the fp16 image of a
 // weight); the f16 form of the matrix instruction is used and the 16-bit outputs are fp16.
-template <int EPI, bool B_IMG, bool KM = false, bool F16 = false>
+// BKM: only B is K-major (data gradient on the raw weight: A = dOut [M, K] K-contiguous, B = W
+// [K, N]); A fragments are plain 16-byte reads, B fragments transposing reads -- both hand a
+// lane the same eight k values, so the two kinds mix freely.
+template <int EPI, bool B_IMG, bool KM = false, bool F16 = false, bool BKM = false>
 __global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
-  static_assert(!(KM && B_IMG), "images are K-contiguous");
+  static_assert(!(KM && B_IMG) && !(BKM && (KM || B_IMG)), "images are K-contiguous; BKM is the mixed form");
+  constexpr bool B_KM = KM || BKM;
   static_assert(!F16 || B_IMG, "fp16 products read the weight through its fp16 image");
   constexpr int BM = 256, BN = 256, BK = 32, NS = 4, NW = 4, WGN = 2;
   constexpr int WM = BM / 2, WN = BN / WGN, NB = WM / 16;   // 8 x 8 blocks of 16 x 16 per wave
@@ -726,9 +730,9 @@ __global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
   const int sps = a.K / BK;                     // slices per K segment: a multiple of 4 (checked by the dispatcher)
   const int nk = sps * a.k_segments;
 
-  const size_t lda = KM ? (size_t)a.M : (size_t)a.K, ldb = KM ? (size_t)a.N : (size_t)a.K;
+  const size_t lda = KM ? (size_t)a.M : (size_t)a.K, ldb = B_KM ? (size_t)a.N : (size_t)a.K;
   Operand<BM, WM, BK, KM, true, false, NW> opA;
-  Operand<BN, WN, BK, KM, true, B_IMG, NW> opB;
+  Operand<BN, WN, BK, B_KM, true, B_IMG, NW> opB;
   opA.init(m0, a.M, lda, wave, lane, wm * WM);
   opB.init(n0, a.N, ldb, wave, lane, wn * WN);
   constexpr int NIA = BM * BK * 2 / 1024 / NW, NIB = BN * BK * 2 / 1024 / NW, N_DMA = NIA + NIB;
@@ -738,18 +742,18 @@ __global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
   // swizzle has period 16 rows)
   const int frag_off = (lane & 15) * RB + (((lane >> 4) ^ swz_kc<BK / 8>(lane & 15)) << 4);
   const char* fragA = lds + (KM ? 0 : wm * WM * RB + frag_off);
-  const char* fragB = lds + A_BYTES + (KM ? 0 : wn * WN * RB + frag_off);
+  const char* fragB = lds + A_BYTES + (B_KM ? 0 : wn * WN * RB + frag_off);
   // K-major: transposing read t (0, 1) of block rb fetches k-rows 8*(lane>>4) + 4t + 0..3 of the
   // block's 16 columns; the lane supplies the address of k-row +(lane&15)>>2, 8-byte piece lane&3
-  int rdA[KM ? 2 : 1][KM ? NB : 1], rdB[KM ? 2 : 1][KM ? NB : 1];
-  if constexpr (KM) {
+  int rdA[KM ? 2 : 1][KM ? NB : 1], rdB[B_KM ? 2 : 1][B_KM ? NB : 1];
+  if constexpr (B_KM) {
     constexpr int ROWB = BM * 2;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int k = 8 * (lane >> 4) + 4 * t + ((lane & 15) >> 2), sw = swz_km<true>(k);
 #pragma unroll
       for (int rb = 0; rb < NB; ++rb) {
-        rdA[t][rb] = k * ROWB + (((((wm * WM) >> 4) + rb) ^ sw) << 5) + (lane & 3) * 8;
+        if constexpr (KM) rdA[t][rb] = k * ROWB + (((((wm * WM) >> 4) + rb) ^ sw) << 5) + (lane & 3) * 8;
         rdB[t][rb] = k * ROWB + (((((wn * WN) >> 4) + rb) ^ sw) << 5) + (lane & 3) * 8;
       }
     }
@@ -759,7 +763,7 @@ __global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
     else return tr_pair(fragA + stage * STAGE + rdA[0][rb], fragA + stage * STAGE + rdA[1][rb]);
   };
   auto frag_b = [&](int stage, int rb) -> bf16x8 {
-    if constexpr (!KM) return *reinterpret_cast<const bf16x8*>(fragB + stage * STAGE + rb * 16 * RB);
+    if constexpr (!B_KM) return *reinterpret_cast<const bf16x8*>(fragB + stage * STAGE + rb * 16 * RB);
     else return tr_pair(fragB + stage * STAGE + rdB[0][rb], fragB + stage * STAGE + rdB[1][rb]);
   };
   bf16x8 fa[2][NB], fb[2][NB];
@@ -859,10 +863,10 @@ __global__ __launch_bounds__(256) void gemm_mi16_kernel(const MfmaArgs a) {
   gemm_epilogue<BM, BN, EPI, NW, NS * STAGE, F16>(write_pass, a, lds, m0, n0, wm, wn, wave, lane);
 }
 
-template <int EPI, bool B_IMG, bool KM = false, bool F16 = false>
+template <int EPI, bool B_IMG, bool KM = false, bool F16 = false, bool BKM = false>
 hipError_t launch_mi16(const MfmaArgs& a, hipStream_t st) {
   const int tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
-  hipLaunchKernelGGL((gemm_mi16_kernel<EPI, B_IMG, KM, F16>), dim3(tiles), dim3(256), 0, st, a);
+  hipLaunchKernelGGL((gemm_mi16_kernel<EPI, B_IMG, KM, F16, BKM>), dim3(tiles), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
@@ -891,7 +895,11 @@ template <bool AK, bool BKM, int EPI> hipError_t pick_tile(const MfmaArgs& a, hi
     if constexpr (AK == BKM) {
       if (a.K % 128 == 0) return launch_mi16<EPI, false, AK>(a, st);
     }
-    // otherwise a K-contiguous A operand (dgrad) takes the five-stage ring with paired fetches
+    // data gradient on the raw weight (A K-contiguous, B K-major): the mixed form of the same kernel
+    if constexpr (!AK && BKM) {
+      if (a.K % 128 == 0) return launch_mi16<EPI, false, false, false, true>(a, st);
+    }
+    // otherwise the 32x32x16 kernel (a K-contiguous A takes its five-stage ring with paired fetches)
     return launch<256, 256, 32, AK ? 4 : GPTS_KC_STAGES, AK, BKM, EPI, false, GPTS_BIG_WAVES>(a, st);
   }
   return launch<128, 128, 64, 2, AK, BKM, EPI>(a, st);

@@ -185,8 +185,9 @@ GradStashLayer grad_stash_layer(const gpt_stage_cfg& c) {
   return s;
 }
 
-// ---- prepared weights: per layer and linear (qkv, out-proj, fc1, fc2) the forward
-// image ([out rows, in]) followed by the dgrad image ([in rows, out]) ---------------------
+// ---- prepared weights: per layer and linear (qkv, out-proj, fc1, fc2) the forward image of
+// the weight ([out rows, in]).  The data gradients read the raw weight: its K-major form goes
+// through the same 16x16x32 kernel at the speed an image gave, so none is built for them.
 struct LinDims { int out, in, wid; };
 inline void linears(const Dims& D, LinDims (&L)[4]) {
   L[0] = {3 * D.P, D.H, GPTS_W_QKV};
@@ -194,16 +195,15 @@ inline void linears(const Dims& D, LinDims (&L)[4]) {
   L[2] = {D.F, D.H, GPTS_W_FC1};
   L[3] = {D.H, D.F, GPTS_W_FC2};
 }
-// element offset of image (layer, linear, which: 0 forward / 1 dgrad); total when layer == L
-size_t prepared_off(const Dims& D, int layer, int lin, int which) {
+// element offset of the image of (layer, linear); total when layer == L
+size_t prepared_off(const Dims& D, int layer, int lin) {
   LinDims L[4];
   linears(D, L);
   size_t per_layer = 0, off = 0;
   for (int i = 0; i < 4; ++i) {
-    const size_t f = gemm_image_elems(L[i].out, L[i].in), b = gemm_image_elems(L[i].in, L[i].out);
-    if (i < lin) off += f + b;
-    if (i == lin && which == 1) off += f;
-    per_layer += f + b;
+    const size_t f = gemm_image_elems(L[i].out, L[i].in);
+    if (i < lin) off += f;
+    per_layer += f;
   }
   return (size_t)layer * per_layer + (layer == D.L ? 0 : off);
 }
@@ -335,8 +335,8 @@ int fwd_layer(const gpt_stage_params* p, int l, const void* X, char* blk, void* 
   const double TH = (double)D.T * D.H, attn_fl = 4.0 * D.B * D.a * D.d * ((double)D.S * (D.S + 1) / 2.0);
   const bool bf = dt == GPTS_BF16;
   const bf16* prep = bf ? static_cast<const bf16*>(p->prepared) : nullptr;
-  auto img = [&](int l_, int lin, int which) -> const void* {
-    return prep ? (const void*)(prep + prepared_off(D, l_, lin, which)) : nullptr;
+  auto img = [&](int l_, int lin) -> const void* {
+    return prep ? (const void*)(prep + prepared_off(D, l_, lin)) : nullptr;
   };
   const int top = phase == 0 ? GPTS_TR_LN_FWD : GPTS_TR_RECOMPUTE;   // a re-run counts as recomputation
   const int top_gemm = phase == 0 ? GPTS_TR_GEMM_FWD : GPTS_TR_RECOMPUTE;
@@ -359,7 +359,7 @@ int fwd_layer(const gpt_stage_params* p, int l, const void* X, char* blk, void* 
                   stat1 + D.T, st, h16), "ln1 fwd");
   GemmEpilogue ep;
   ep.bias = w(l, GPTS_B_QKV);
-  ep.b_image = img(l, 0, 0);
+  ep.b_image = img(l, 0);
   GPTS_OP(top_gemm, 0, phase, gf(D.T, 3 * D.P, D.H), gb(D.T, 3 * D.P, D.H, e), fwd_gemm(3 * D.P, D.H, A, GPTS_W_QKV, s + sl.QKV, ep), "qkv gemm");
   GPTS_OP(top_attn, 0, phase, attn_fl, (double)D.T * 4 * D.P * e, attention_fwd(dt, D.B, D.S, D.a, D.d, s + sl.QKV, s + sl.C,
                                 reinterpret_cast<float*>(s + sl.LSE), fwk + fw.attn, st, h16), "attention fwd");
@@ -367,7 +367,7 @@ int fwd_layer(const gpt_stage_params* p, int l, const void* X, char* blk, void* 
   ep.bias = w(l, GPTS_B_O);
   ep.residual = X;
   ep.residual_f32 = ep.out_f32 = bf;
-  ep.b_image = img(l, 1, 0);
+  ep.b_image = img(l, 1);
   GPTS_OP(top_gemm, 1, phase, gf(D.T, D.H, D.P), gb(D.T, D.H, D.P, 2 * kResBytes), fwd_gemm(D.H, D.P, s + sl.C, GPTS_W_O, s + sl.X1, ep), "out-proj gemm");
   GPTS_OP(top, 1, phase, 0.0, TH * (kResBytes + e), ln_fwd(dt, bf, D.T, D.H, c.ln_eps, s + sl.X1, w(l, GPTS_LN2_G), w(l, GPTS_LN2_B), A2,
                   stat2, stat2 + D.T, st, h16), "ln2 fwd");
@@ -375,7 +375,7 @@ int fwd_layer(const gpt_stage_params* p, int l, const void* X, char* blk, void* 
   ep.bias = w(l, GPTS_B_FC1);
   ep.gelu_out = G;
   ep.gelu_kind = c.gelu;
-  ep.b_image = img(l, 2, 0);
+  ep.b_image = img(l, 2);
   GPTS_OP(top_gemm, 2, phase, gf(D.T, D.F, D.H), gb(D.T, D.F, D.H, 2 * e), fwd_gemm(D.F, D.H, A2, GPTS_W_FC1, s + sl.U, ep), "fc1 gemm");
   if (!Yout) return GPTS_OK;
   ep = GemmEpilogue();
@@ -383,7 +383,7 @@ int fwd_layer(const gpt_stage_params* p, int l, const void* X, char* blk, void* 
   ep.residual = s + sl.X1;
   ep.residual_f32 = bf;
   ep.out_f32 = bf && y_f32;   // the stage output y is bf16, the stream between layers fp32
-  ep.b_image = img(l, 3, 0);
+  ep.b_image = img(l, 3);
   GPTS_OP(top_gemm, 3, phase, gf(D.T, D.H, D.F), gb(D.T, D.H, D.F, 2 * kResBytes), fwd_gemm(D.H, D.F, G, GPTS_W_FC2, Yout, ep), "fc2 gemm");
   return GPTS_OK;
 }
@@ -467,10 +467,6 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
   auto gf = [](double M, double N, double K) { return 2.0 * M * N * K; };
   auto gb = [&](double M, double N, double K, double out_bytes) { return (M * K + N * K) * e + M * N * out_bytes; };
   const double TH = (double)D.T * D.H, attn_fl = 4.0 * D.B * D.a * D.d * ((double)D.S * (D.S + 1) / 2.0);
-  const bf16* prep = dt == GPTS_BF16 ? static_cast<const bf16*>(p->prepared) : nullptr;
-  auto img = [&](int l, int lin) -> const void* {
-    return prep ? (const void*)(prep + prepared_off(D, l, lin, 1)) : nullptr;
-  };
   const void* dY = dy;
   if (data_only) {
     // the top layer's output gradient is the caller's buffer: keep a copy for the weight phase
@@ -501,10 +497,7 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
       if (l > 0) dXout = gs + (size_t)(l - 1) * gl.end + gl.dY;   // the layer below reads it as its dY
     }
     GemmEpilogue none;
-    GemmEpilogue d_fc1, d_o, d_qkv;   // plain dgrads, each with the image of its weight
-    d_fc1.b_image = img(l, 2);
-    d_o.b_image = img(l, 1);
-    d_qkv.b_image = img(l, 0);
+    GemmEpilogue d_fc1, d_o, d_qkv;   // plain dgrads (on the raw weights)
     // y = x1 + g W2^T + b2 ;  g = gelu(u)
     const bool h16 = c.fwd_fp16 != 0;            // QKV, C, U of the stash hold fp16 values
     const bool rebuild = c.recompute == 1 || h16;     // A, A2, G are rebuilt here (as bf16)
@@ -519,7 +512,6 @@ int run_bwd(const gpt_stage_params* p, const void* act_stash, const void* dy, vo
     GemmEpilogue ep;
     ep.dgelu_u = U;
     ep.gelu_kind = c.gelu;
-    ep.b_image = img(l, 3);
     // the matrix-core product also leaves the column sums of dU (the fc1 bias gradient) as
     // per-tile-row partials, when it runs and they fit the column-sum scratch
     const int cs_rows = (dt == GPTS_BF16 && gemm_mfma_supported(1, D.T, D.F, D.H)) ? gemm_mfma_colsum_rows(D.T, D.F) : 0;
@@ -775,7 +767,7 @@ const char* gpt_stage_strerror(int code) {
 size_t gpt_stage_prepared_bytes(const gpt_stage_cfg* c) {
   if (gpt_stage_validate(c) != GPTS_OK || c->dtype != GPTS_BF16) return 0;
   Dims D(*c);
-  return prepared_off(D, D.L, 0, 0) * 2;
+  return prepared_off(D, D.L, 0) * 2;
 }
 int gpt_stage_prepare(const gpt_stage_params* p, void* prepared, void* stream) {
   int rc = check_call(p);
@@ -791,8 +783,7 @@ int gpt_stage_prepare(const gpt_stage_params* p, void* prepared, void* stream) {
   for (int l = 0; l < D.L; ++l)
     for (int i = 0; i < 4; ++i) {
       const bf16* w = W + tensor_off(D, l, L[i].wid);
-      GPTS_TRY(gemm_prepare_image(w, out + prepared_off(D, l, i, 0), L[i].out, L[i].in, false, st, p->cfg.fwd_fp16 != 0), "prepare fwd image");
-      GPTS_TRY(gemm_prepare_image(w, out + prepared_off(D, l, i, 1), L[i].in, L[i].out, true, st), "prepare dgrad image");
+      GPTS_TRY(gemm_prepare_image(w, out + prepared_off(D, l, i), L[i].out, L[i].in, false, st, p->cfg.fwd_fp16 != 0), "prepare fwd image");
     }
   return GPTS_OK;
 }

@@ -168,20 +168,20 @@ def test_backward_stream_waits_for_the_forward_event():
 
 @pytest.mark.parametrize("ffn", [16384 - 64, 8192], ids=["ffn_ragged", "ffn_mult_128"])
 def test_prepared_weights_give_identical_results(ffn):
-    """With the weight images of gpt_stage_prepare() the forward and dgrad products read
-    the same numbers through a different layout: every output must be bit-identical to
-    the run on the raw weights.  One layer of the decoupled workload's shape (large
+    """With the weight images of gpt_stage_prepare() the forward products read the same
+    numbers through a different layout: every output must be bit-identical to the run on the
+    raw weights.  One layer of the decoupled workload's shape (large
     enough for the 256x256 tiles the images are made for).  ffn 16320: ragged N, and a
-    contraction length that is not a multiple of 128 (the fc2 forward and fc1 dgrad images
-    then feed the 32x32x16 kernel); ffn 8192: every image-fed product takes the 16x16x32
-    kernel, as in the benchmark."""
+    contraction length that is not a multiple of 128 (the fc2 forward image then feeds the
+    32x32x16 kernel); ffn 8192: every image-fed product takes the 16x16x32 kernel, as in the
+    benchmark."""
     shape = W[3].with_(name="bf16_prepared", n_layers=1, ffn=ffn, n_microbatches=1, bias_std=0.02)
     print(f"[case] prepared weights {shape}", flush=True)
     params, xs, dys = _inputs(shape)
     bufs = B.StageBuffers(shape)
     bufs.load_params(params)
     raw = gpu_run(shape, params, xs, dys, bufs=bufs)
-    assert B.gpt_stage_prepared_bytes(bufs.cfg) > 2 * B.gpt_stage_param_bytes(bufs.cfg) * 0.99
+    assert B.gpt_stage_prepared_bytes(bufs.cfg) > B.gpt_stage_param_bytes(bufs.cfg) * 0.99
     bufs.prepare()
     try:
         prep = gpu_run(shape, params, xs, dys, bufs=bufs)
