@@ -119,6 +119,25 @@ def test_recompute_levels_validate_and_shrink_the_stash():
     assert w0[1] - w0[0] >= sizes[0] // s.n_layers - s.tokens * s.hidden * 4 - 4096
 
 
+def test_split_backward_is_refused_where_it_cannot_work():
+    """Keep-only-x recomputation leaves no activations for a later weight phase: both halves of
+    the split backward return GPTS_EINVAL before anything is launched (fake, aligned pointers)."""
+    cfg = B.make_cfg(synth.WORKLOADS[1].with_(recompute=2))
+    p = B.gpt_stage_params(cfg=cfg, weights=0x10000, workspace=0x20000)
+    L = B.lib()
+    assert L.gpt_stage_bwd_data_only(ctypes.byref(p), 0x30000, 0x40000, 0x50000, 0x60000, 0x70000, None, None) == B.GPTS_EINVAL
+    assert "recompute" in B.gpt_stage_strerror(B.GPTS_EINVAL)
+    arr = (ctypes.c_void_p * 1)(0x30000)
+    assert L.gpt_stage_wgrad_flush(ctypes.byref(p), 1, arr, arr, 0x60000, None) == B.GPTS_EINVAL
+    assert B.gpt_stage_grad_stash_bytes(cfg) > 0
+    ok = B.make_cfg(synth.WORKLOADS[3])
+    T, H, P, F, Ln = 4096, 4096, 4096, 16384, 4
+    assert B.gpt_stage_grad_stash_bytes(ok) == Ln * (2 * T * H + T * F + T * 3 * P) * 2
+    q = B.gpt_stage_params(cfg=ok, weights=0x10000, workspace=0x20000)
+    assert L.gpt_stage_wgrad_flush(ctypes.byref(q), 0, arr, arr, 0x60000, None) == B.GPTS_EINVAL
+    assert L.gpt_stage_bwd_data_only(ctypes.byref(q), 0x30000, 0x40000, 0x50000, 0x60000, None, None, None) == B.GPTS_EINVAL
+
+
 def test_bf16_needs_tile_multiples():
     s = synth.WORKLOADS[1].with_(seq=1000, batch=1)
     assert B.gpt_stage_validate(B.make_cfg(s)) == B.GPTS_ESHAPE
