@@ -209,8 +209,13 @@ def dpp_bench(args, shape):
     act = torch.empty(B.gpt_dpp_act_slot_bytes(cfg) * (M + 2), dtype=torch.uint8, device="cuda")
     flops = B.gpt_stage_model_flops(cfg, True) * C * M
     rows = {}
-    for name, pol, cap in (("dfc", B.GPT_DPP_DFC, 0), ("bfc", B.GPT_DPP_BFC, 0),
-                           ("bfc_best_effort_cap_half", B.GPT_DPP_BFC_BEST_EFFORT, C * M // 2)):
+    gslot = B.gpt_dpp_grad_slot_bytes(chunks)
+    gpool = torch.empty(gslot * M, dtype=torch.uint8, device="cuda") if gslot else None
+    # "+wp": backward tasks run the data phase, one weight phase per chunk and window
+    for name, pol, cap, wp in (("dfc", B.GPT_DPP_DFC, 0, False), ("bfc", B.GPT_DPP_BFC, 0, False),
+                               ("bfc_best_effort_cap_half", B.GPT_DPP_BFC_BEST_EFFORT, C * M // 2, False),
+                               ("dfc+wp", B.GPT_DPP_DFC, 0, True), ("bfc+wp", B.GPT_DPP_BFC, 0, True),
+                               ("bfc_best_effort_cap_half+wp", B.GPT_DPP_BFC_BEST_EFFORT, C * M // 2, True)):
         ev0 = torch.cuda.Event(enable_timing=True)
         ready = [torch.cuda.Event(enable_timing=True) for _ in range(C)]
         for e in [ev0] + ready:
@@ -221,7 +226,7 @@ def dpp_bench(args, shape):
                 if prepared[j] is not None:
                     B.gpt_stage_prepare(chunks[j], prepared[j])
             return B.gpt_dpp_run(pol, chunks, xs, dys, ys, dxs, dps, stash, act, max_live_stash=cap,
-                                 grad_ready=ready if timed_events else None)
+                                 grad_ready=ready if timed_events else None, grad_pool=gpool if wp else None)
         for _ in range(args.warmup):
             step(False)
         torch.cuda.synchronize()

@@ -386,7 +386,22 @@ typedef struct {
                                      slots of gpt_dpp_act_slot_bytes() each                 */
   size_t act_pool_bytes;
   void* const* grad_ready;        /* NULL, or [n_chunks] hipEvent_t: event j is recorded when
-                                     the last backward task of chunk j has been enqueued   */
+                                     the last backward task of chunk j (and, with grad_pool,
+                                     its last weight phase) has been enqueued              */
+  void* grad_pool;                /* NULL: every backward task is a whole gpt_stage_bwd_only.
+                                     Otherwise (gpt_dpp_run only) device memory for W slots of
+                                     gpt_dpp_grad_slot_bytes(), W the window of the policy:
+                                     backward tasks run the data phase only and, as soon as a
+                                     chunk has seen the backward tasks of all micro-batches of
+                                     a window, ONE weight phase (gpt_stage_wgrad_flush) adds
+                                     the chunk's weight gradients over those micro-batches --
+                                     what breadth first buys on top of the early gradient
+                                     exchange: the wider the window, the fewer passes over the
+                                     fp32 gradient matrices.  The stash pool must then hold
+                                     n_chunks * W slots (handed out in a fixed, equally spaced
+                                     pattern, which the one-launch weight phase needs); a
+                                     stash is released after its chunk's weight phase.      */
+  size_t grad_pool_bytes;
 } gpt_dpp_job;
 
 typedef struct {
@@ -398,6 +413,7 @@ typedef struct {
 } gpt_dpp_report;
 
 size_t gpt_dpp_stash_slot_bytes(const gpt_stage_params* chunks, int n_chunks); /* 0 on bad input */
+size_t gpt_dpp_grad_slot_bytes(const gpt_stage_params* chunks, int n_chunks);  /* 0 on bad input */
 size_t gpt_dpp_act_slot_bytes(const gpt_stage_cfg* cfg);                        /* 0 on bad input */
 
 /* The best-effort allowance from the memory that is free right now on the current device

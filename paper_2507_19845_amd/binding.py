@@ -37,7 +37,7 @@ EXPORTS = (
     "gpt_stage_op_attention_bwd",
     "gpt_stage_trace_create", "gpt_stage_trace_destroy", "gpt_stage_trace_reset",
     "gpt_stage_trace_collect", "gpt_stage_trace_op_name",
-    "gpt_dpp_plan", "gpt_dpp_stash_slot_bytes", "gpt_dpp_act_slot_bytes", "gpt_dpp_run",
+    "gpt_dpp_plan", "gpt_dpp_stash_slot_bytes", "gpt_dpp_grad_slot_bytes", "gpt_dpp_act_slot_bytes", "gpt_dpp_run",
     "gpt_dpp_allowance_from_free_memory", "gpt_dpp_simulate_ready", "gpt_dpp_run_ready",
     "gpt_fbd_coord_create", "gpt_fbd_coord_destroy", "gpt_fbd_coord_expected", "gpt_fbd_coord_register",
     "gpt_fbd_coord_align", "gpt_fbd_coord_ready", "gpt_fbd_coord_execute", "gpt_fbd_coord_simulate",
@@ -73,7 +73,8 @@ class gpt_dpp_job(C.Structure):
                 ("y", C.POINTER(C.c_void_p)), ("dx", C.POINTER(C.c_void_p)),
                 ("dparams", C.POINTER(C.c_void_p)), ("stash_pool", C.c_void_p),
                 ("stash_pool_bytes", C.c_size_t), ("act_pool", C.c_void_p),
-                ("act_pool_bytes", C.c_size_t), ("grad_ready", C.POINTER(C.c_void_p))]
+                ("act_pool_bytes", C.c_size_t), ("grad_ready", C.POINTER(C.c_void_p)),
+                ("grad_pool", C.c_void_p), ("grad_pool_bytes", C.c_size_t)]
 
 
 class gpt_dpp_report(C.Structure):
@@ -153,6 +154,7 @@ def lib() -> C.CDLL:
         "gpt_stage_trace_op_name": (C.c_char_p, [i32]),
         "gpt_dpp_plan": (i32, [i32, i32, i32, i32, C.POINTER(gpt_dpp_task), i32, C.POINTER(i32)]),
         "gpt_dpp_stash_slot_bytes": (sz, [parp, i32]),
+        "gpt_dpp_grad_slot_bytes": (sz, [parp, i32]),
         "gpt_dpp_act_slot_bytes": (sz, [cfgp]),
         "gpt_dpp_run": (i32, [C.POINTER(gpt_dpp_job), vp, C.POINTER(gpt_dpp_report)]),
         "gpt_dpp_allowance_from_free_memory": (i32, [parp, i32, i32, sz, C.POINTER(sz), C.POINTER(sz)]),
@@ -415,6 +417,10 @@ def gpt_dpp_stash_slot_bytes(chunks) -> int:
     return lib().gpt_dpp_stash_slot_bytes(_params_array(chunks), len(chunks))
 
 
+def gpt_dpp_grad_slot_bytes(chunks) -> int:
+    return lib().gpt_dpp_grad_slot_bytes(_params_array(chunks), len(chunks))
+
+
 def gpt_dpp_act_slot_bytes(cfg) -> int:
     return lib().gpt_dpp_act_slot_bytes(C.byref(cfg))
 
@@ -444,7 +450,8 @@ def gpt_dpp_simulate_ready(policy: int, n_chunks: int, n_microbatches: int, max_
     return [(arr[k].phase, arr[k].microbatch, arr[k].chunk) for k in range(n)], steps.value, idle.value
 
 
-def _dpp_job(policy, chunks, xs, dys, ys, dxs, dparams, stash_pool, act_pool, max_live_stash, grad_ready):
+def _dpp_job(policy, chunks, xs, dys, ys, dxs, dparams, stash_pool, act_pool, max_live_stash, grad_ready,
+             grad_pool=None):
     def ptrs(ts):
         a = (C.c_void_p * len(ts))()
         for k, t in enumerate(ts):
@@ -461,7 +468,8 @@ def _dpp_job(policy, chunks, xs, dys, ys, dxs, dparams, stash_pool, act_pool, ma
                       y=keep[3], dx=keep[4], dparams=keep[5],
                       stash_pool=_ptr(stash_pool), stash_pool_bytes=stash_pool.numel() if stash_pool is not None else 0,
                       act_pool=_ptr(act_pool), act_pool_bytes=act_pool.numel() if act_pool is not None else 0,
-                      grad_ready=ev)
+                      grad_ready=ev, grad_pool=_ptr(grad_pool),
+                      grad_pool_bytes=grad_pool.numel() if grad_pool is not None else 0)
     return job, keep + [ev]
 
 
@@ -488,27 +496,13 @@ def gpt_dpp_run_ready(policy: int, chunks, xs, dys, ys, dxs, dparams, stash_pool
 
 
 def gpt_dpp_run(policy: int, chunks, xs, dys, ys, dxs, dparams, stash_pool, act_pool,
-                max_live_stash: int = 0, grad_ready=None, stream=None) -> gpt_dpp_report:
+                max_live_stash: int = 0, grad_ready=None, stream=None, grad_pool=None) -> gpt_dpp_report:
     """chunks: list of gpt_stage_params; xs, dys, ys, dxs: one tensor per micro-batch;
     dparams: one fp32 tensor per chunk; stash_pool / act_pool: uint8 tensors (act_pool may be
-    None for a single chunk); grad_ready: None or one torch.cuda.Event per chunk."""
-    def ptrs(ts):
-        a = (C.c_void_p * len(ts))()
-        for k, t in enumerate(ts):
-            a[k] = _ptr(t)
-        return a
-    keep = [_params_array(chunks), ptrs(xs), ptrs(dys), ptrs(ys), ptrs(dxs), ptrs(dparams)]
-    ev = None
-    if grad_ready is not None:
-        ev = (C.c_void_p * len(grad_ready))()
-        for k, e in enumerate(grad_ready):
-            ev[k] = _event(e)
-    job = gpt_dpp_job(n_chunks=len(chunks), n_microbatches=len(xs), policy=policy,
-                      max_live_stash=max_live_stash, chunks=keep[0], x=keep[1], dy=keep[2],
-                      y=keep[3], dx=keep[4], dparams=keep[5],
-                      stash_pool=_ptr(stash_pool), stash_pool_bytes=stash_pool.numel() if stash_pool is not None else 0,
-                      act_pool=_ptr(act_pool), act_pool_bytes=act_pool.numel() if act_pool is not None else 0,
-                      grad_ready=ev)
+    None for a single chunk); grad_ready: None or one torch.cuda.Event per chunk; grad_pool:
+    None, or a uint8 tensor of gradient-stash slots (one weight phase per chunk and window)."""
+    job, keep = _dpp_job(policy, chunks, xs, dys, ys, dxs, dparams, stash_pool, act_pool, max_live_stash,
+                         grad_ready, grad_pool)
     rep = gpt_dpp_report()
     _check(lib().gpt_dpp_run(C.byref(job), _stream(stream), C.byref(rep)))
     return rep

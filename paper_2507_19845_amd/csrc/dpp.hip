@@ -129,11 +129,18 @@ struct TaskIssuer {
   void* stream;
   Pool stash, act;
   std::vector<int> slot_of, fwd_buf, bwd_buf, left;
+  // weight phase per chunk and window (job->grad_pool): W micro-batches per window, stash slot of
+  // task (i, j) fixed at j*W + i%W so that a chunk's stashes of one window are equally spaced
+  int W = 0;
+  size_t stash_slot_bytes, grad_slot_bytes = 0;
+  int live_fixed = 0, peak_fixed = 0;
   TaskIssuer(const gpt_dpp_job* j, void* st, size_t stash_slot, size_t act_slot)
       : job(j), stream(st), stash(j->stash_pool, stash_slot, j->stash_pool ? j->stash_pool_bytes : 0),
         act(j->act_pool, act_slot, j->act_pool ? j->act_pool_bytes : 0),
         slot_of((size_t)j->n_chunks * j->n_microbatches, -1), fwd_buf(j->n_microbatches, -1),
-        bwd_buf(j->n_microbatches, -1), left(j->n_chunks, j->n_microbatches) {}
+        bwd_buf(j->n_microbatches, -1), left(j->n_chunks, j->n_microbatches), stash_slot_bytes(stash_slot) {}
+  void* stash_at(int i, int j) { return static_cast<char*>(job->stash_pool) + (size_t)(j * W + i % W) * stash_slot_bytes; }
+  void* grad_at(int i) { return static_cast<char*>(job->grad_pool) + (size_t)(i % W) * grad_slot_bytes; }
   int issue(const gpt_dpp_task& k) {
     const int C = job->n_chunks, i = k.microbatch, j = k.chunk;
     if (k.phase == GPT_DPP_FWD) {
@@ -145,10 +152,17 @@ struct TaskIssuer {
         out_id = act.take();
         out = act.at(out_id);
       }
-      if (stash.free_ids.empty()) return set_error(GPTS_ENOMEM, "dpp: stash pool exhausted");
-      const int s = stash.take();
-      slot_of[(size_t)i * C + j] = s;
-      const int rc = gpt_stage_fwd_only(&job->chunks[j], in, stash.at(s), out, stream, nullptr);
+      void* slot;
+      if (W > 0) {
+        slot = stash_at(i, j);
+        if (++live_fixed > peak_fixed) peak_fixed = live_fixed;
+      } else {
+        if (stash.free_ids.empty()) return set_error(GPTS_ENOMEM, "dpp: stash pool exhausted");
+        const int s = stash.take();
+        slot_of[(size_t)i * C + j] = s;
+        slot = stash.at(s);
+      }
+      const int rc = gpt_stage_fwd_only(&job->chunks[j], in, slot, out, stream, nullptr);
       if (rc != GPTS_OK) return rc;
       if (j != 0) act.give(fwd_buf[i]);
       fwd_buf[i] = out_id;
@@ -161,10 +175,28 @@ struct TaskIssuer {
         out_id = act.take();
         dout = act.at(out_id);
       }
-      const int s = slot_of[(size_t)i * C + j];
-      const int rc = gpt_stage_bwd_only(&job->chunks[j], stash.at(s), din, dout, job->dparams[j], stream, nullptr);
-      if (rc != GPTS_OK) return rc;
-      stash.give(s);
+      if (W > 0) {
+        int rc = gpt_stage_bwd_data_only(&job->chunks[j], stash_at(i, j), din, dout, job->dparams[j], grad_at(i), stream, nullptr);
+        if (rc != GPTS_OK) return rc;
+        const int M = job->n_microbatches;
+        if (i % W == W - 1 || i == M - 1) {
+          // the chunk has seen every micro-batch of the window: one weight phase over them
+          const int w0 = i / W * W, n = i - w0 + 1;
+          std::vector<const void*> as(n), gs(n);
+          for (int m = 0; m < n; ++m) {
+            as[m] = stash_at(w0 + m, j);
+            gs[m] = grad_at(w0 + m);
+          }
+          rc = gpt_stage_wgrad_flush(&job->chunks[j], n, as.data(), gs.data(), job->dparams[j], stream);
+          if (rc != GPTS_OK) return rc;
+          live_fixed -= n;
+        }
+      } else {
+        const int s = slot_of[(size_t)i * C + j];
+        const int rc = gpt_stage_bwd_only(&job->chunks[j], stash.at(s), din, dout, job->dparams[j], stream, nullptr);
+        if (rc != GPTS_OK) return rc;
+        stash.give(s);
+      }
       if (j != C - 1) act.give(bwd_buf[i]);
       bwd_buf[i] = out_id;
       if (--left[j] == 0 && job->grad_ready && job->grad_ready[j]) {
@@ -290,6 +322,17 @@ size_t gpt_dpp_stash_slot_bytes(const gpt_stage_params* chunks, int n_chunks) {
   return align256(m);
 }
 
+size_t gpt_dpp_grad_slot_bytes(const gpt_stage_params* chunks, int n_chunks) {
+  if (!chunks || n_chunks < 1) return 0;
+  size_t m = 0;
+  for (int j = 0; j < n_chunks; ++j) {
+    const size_t b = gpt_stage_grad_stash_bytes(&chunks[j].cfg);
+    if (b == 0) return 0;
+    if (b > m) m = b;
+  }
+  return align256(m);
+}
+
 size_t gpt_dpp_act_slot_bytes(const gpt_stage_cfg* cfg) {
   if (gpt_stage_validate(cfg) != GPTS_OK) return 0;
   return align256((size_t)cfg->batch * cfg->seq * cfg->hidden * (cfg->dtype == GPTS_BF16 ? 2 : 4));
@@ -336,6 +379,17 @@ int gpt_dpp_run(const gpt_dpp_job* job, void* stream, gpt_dpp_report* report) {
   const int n = gpt_dpp_plan(job->policy, C, M, allowance, plan.data(), (int)plan.size(), &peak_stash);
   if (n < 0) return n;
   TaskIssuer issuer(job, stream, stash_slot, act_slot);
+  if (job->grad_pool) {
+    const int W = window(job->policy, C, M, allowance);
+    const size_t gslot = gpt_dpp_grad_slot_bytes(job->chunks, C);
+    if (!gslot) return set_error(GPTS_ESHAPE, "dpp_run: a chunk's cfg is not valid");
+    if (job->grad_pool_bytes < (size_t)W * gslot)
+      return set_error(GPTS_ENOMEM, "dpp_run: grad_pool too small (one gradient-stash slot per micro-batch of a window)");
+    if (!job->stash_pool || job->stash_pool_bytes < (size_t)C * W * stash_slot)
+      return set_error(GPTS_ENOMEM, "dpp_run: with grad_pool the stash pool must hold n_chunks * window slots");
+    issuer.W = W;
+    issuer.grad_slot_bytes = gslot;
+  }
 
   // dry run of the pool usage, so that nothing is enqueued when a pool is too small
   {
@@ -347,7 +401,7 @@ int gpt_dpp_run(const gpt_dpp_job* job, void* stream, gpt_dpp_report* report) {
       if (!edge && ++live_act > peak_act) peak_act = live_act;
       if (!first) --live_act;
     }
-    if ((size_t)peak_stash > issuer.stash.free_ids.size()) return set_error(GPTS_ENOMEM, "dpp_run: stash pool too small for this policy");
+    if (!issuer.W && (size_t)peak_stash > issuer.stash.free_ids.size()) return set_error(GPTS_ENOMEM, "dpp_run: stash pool too small for this policy");
     if ((size_t)peak_act > issuer.act.free_ids.size()) return set_error(GPTS_ENOMEM, "dpp_run: boundary-activation pool too small for this policy");
   }
   for (int t = 0; t < n; ++t) {
@@ -356,7 +410,7 @@ int gpt_dpp_run(const gpt_dpp_job* job, void* stream, gpt_dpp_report* report) {
   }
   if (report) {
     report->n_tasks = n;
-    report->peak_live_stash = issuer.stash.peak;
+    report->peak_live_stash = issuer.W ? issuer.peak_fixed : issuer.stash.peak;
     report->peak_live_act = issuer.act.peak;
     report->stash_slot_bytes = stash_slot;
     report->act_slot_bytes = act_slot;
@@ -371,6 +425,7 @@ int gpt_dpp_run_ready(const gpt_dpp_job* job, const void* const* x_ready, const 
   if (rc != GPTS_OK) return rc;
   rc = check_counts(job->policy, job->n_chunks, job->n_microbatches, "dpp_run_ready: unknown policy");
   if (rc != GPTS_OK) return rc;
+  if (job->grad_pool) return set_error(GPTS_EINVAL, "dpp_run_ready: the per-chunk weight phase (grad_pool) is for gpt_dpp_run");
   const int C = job->n_chunks, M = job->n_microbatches, total = 2 * C * M;
   if (order_out && capacity < total) return set_error(GPTS_ENOMEM, "dpp_run_ready: order_out holds fewer than 2*chunks*microbatches entries");
   if (!(timeout_seconds > 0)) return set_error(GPTS_EINVAL, "dpp_run_ready: timeout_seconds must be > 0");

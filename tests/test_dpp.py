@@ -106,7 +106,7 @@ def test_library_plan_rejects_bad_arguments():
 
 
 # ---- GPU: the driver ---------------------------------------------------------------------
-def _run_dpp(shape, C, M, policy, cap, params_np, pool_slots=None, expect_peak=None):
+def _run_dpp(shape, C, M, policy, cap, params_np, pool_slots=None, expect_peak=None, weight_phase=False):
     import torch
     chunk_shape = shape.with_(n_layers=shape.n_layers // C)
     Lc = chunk_shape.n_layers
@@ -132,7 +132,10 @@ def _run_dpp(shape, C, M, policy, cap, params_np, pool_slots=None, expect_peak=N
         peak = expect_peak
     stash = torch.empty(B.gpt_dpp_stash_slot_bytes(chunks) * (pool_slots or peak), dtype=torch.uint8, device="cuda")
     act = torch.empty(B.gpt_dpp_act_slot_bytes(cfg) * (2 * M + 2), dtype=torch.uint8, device="cuda")
-    rep = B.gpt_dpp_run(policy, chunks, xs, dys, ys, dxs, dps, stash, act, max_live_stash=cap)
+    grad_pool = None
+    if weight_phase:     # one gradient-stash slot per micro-batch of a window (peak = n_chunks * window)
+        grad_pool = torch.empty(B.gpt_dpp_grad_slot_bytes(chunks) * (peak // C), dtype=torch.uint8, device="cuda")
+    rep = B.gpt_dpp_run(policy, chunks, xs, dys, ys, dxs, dps, stash, act, max_live_stash=cap, grad_pool=grad_pool)
     torch.cuda.synchronize()
     assert rep.n_tasks == 2 * C * M and rep.peak_live_stash == peak
     return ([B.to_host(t) for t in ys], [B.to_host(t) for t in dxs], [t.cpu().numpy() for t in dps], cfg, rep)
@@ -408,3 +411,49 @@ def test_ready_set_driver_on_the_gpu_inputs_arriving_out_of_order():
                             dy_ready=[never, None, None], timeout_seconds=0.2)
     assert e.value.code == B.GPTS_EHIP and "did not arrive" in str(e.value)
     torch.cuda.synchronize()
+
+
+@pytest.mark.gpu
+def test_dpp_weight_phase_per_chunk_and_window():
+    """With a gradient-stash pool the driver runs data-phase backward tasks and one weight phase
+    per chunk and window.  Same y, dx, bias and LayerNorm gradients bit for bit; weight gradients
+    bit-identical where the weight phase takes one product per micro-batch (depth first: windows
+    of one) and equal up to the fp32 summation order where it contracts over a window in one
+    launch (breadth first, >= 100 tiles of 256x256)."""
+    from parity_util import max_norm_err
+    C, M = 2, 3
+    shape = synth.StageShape(name="dpp_wp", n_layers=2, hidden=2048, n_heads=16, head_dim=128, ffn=4096, seq=256,
+                             batch=1, dtype="bf16", n_microbatches=M, bias_std=0.02, ln_jitter=0.1)
+    params_np = [{k: synth.to_storage(v, "bf16") for k, v in synth.make_layer_params(shape, l, 0).items()}
+                 for l in range(shape.n_layers)]
+    ref = _run_dpp(shape, C, M, B.GPT_DPP_BFC, 0, params_np)
+    cfg = ref[3]
+    weights = {}
+    for tid, name in enumerate(synth.TENSOR_NAMES):
+        weights[name] = B.gpt_stage_param_offset(cfg, 0, tid)
+    for policy, cap, one_launch in ((B.GPT_DPP_DFC, 0, False), (B.GPT_DPP_BFC, 0, True),
+                                    (B.GPT_DPP_BFC_BEST_EFFORT, 2 * C, True)):
+        got = _run_dpp(shape, C, M, policy, cap, params_np, weight_phase=True)
+        for a, b in zip(ref[0] + ref[1], got[0] + got[1]):
+            assert np.array_equal(a, b)
+        changed = 0
+        for j in range(C):
+            for name, (off, n) in weights.items():
+                a, b = ref[2][j][off:off + n], got[2][j][off:off + n]
+                if name in ("w_qkv", "w_fc1", "w_fc2") and one_launch:
+                    assert max_norm_err(b, a) < 2e-6, (policy, j, name)
+                    changed += int(not np.array_equal(a, b))
+                else:
+                    assert np.array_equal(a, b), (policy, j, name)
+        assert (changed > 0) == one_launch
+    # pools too small for the fixed slot pattern are refused before anything runs
+    import torch
+    chunks = [B.gpt_stage_params(cfg=cfg, weights=0x10000, workspace=0x20000, prepared=None, trace=None)] * C
+    t = [torch.zeros(1, 256, 2048, dtype=torch.bfloat16, device="cuda") for _ in range(M)]
+    dps = [torch.zeros(8, device="cuda") for _ in range(C)]
+    stash = torch.empty(B.gpt_dpp_stash_slot_bytes(chunks) * (C * M - 1), dtype=torch.uint8, device="cuda")
+    act = torch.empty(B.gpt_dpp_act_slot_bytes(cfg) * 8, dtype=torch.uint8, device="cuda")
+    gp = torch.empty(B.gpt_dpp_grad_slot_bytes(chunks) * M, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.GptStageError) as e:
+        B.gpt_dpp_run(B.GPT_DPP_BFC, chunks, t, t, t, t, dps, stash, act, grad_pool=gp)
+    assert e.value.code == B.GPTS_ENOMEM
