@@ -60,6 +60,9 @@ def parse():
     ap.add_argument("--recompute", type=int, nargs="?", const=1, default=0, choices=[0, 1, 2],
                     help="activation recomputation: 1 = LayerNorm/GeLU outputs rebuilt in backward, "
                          "2 = only each layer's input is stashed and backward re-runs the layer's forward")
+    ap.add_argument("--graph", action="store_true",
+                    help="coupled schedule only: capture one step in a HIP graph and time its replays "
+                         "(the stage calls only enqueue kernels; pays on launch-bound small stages)")
     ap.add_argument("--op", choices=["attention", "layernorm", "gemm"], default=None,
                     help="time one operator alone (gpt_stage_op_* entry points) at the workload's shapes")
     ap.add_argument("--pmc-summary", default=None, metavar="DIR",
@@ -291,11 +294,19 @@ def run_workload(args, shape):
         bufs.dparams.zero_()
         step()
     torch.cuda.synchronize()
+    run_step = step
+    use_graph = args.graph and not decoupled
+    if use_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run_step = graph.replay
+        run_step()
     bufs.dparams.zero_()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run_step()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms = wall * 1e3 / args.steps
@@ -327,6 +338,7 @@ def run_workload(args, shape):
                                        else "inside every micro-batch's backward call",
                    "grad_stash_GiB_per_microbatch": B.gpt_stage_grad_stash_bytes(bufs.cfg) / 2**30 if split else 0.0,
                    "prepared_weights": "rebuilt every step (timed)" if prepare else "off (raw weights)",
+                   "launch": "one HIP graph replay per step" if use_graph else "eager",
                    "forward_activations": "fp16" if shape.fwd_fp16 else shape.dtype,
                    "stash": stash,
                    "stash_GiB_per_microbatch": B.gpt_stage_stash_bytes(bufs.cfg) / 2**30,

@@ -618,3 +618,42 @@ def test_recompute_variant_identical_results_smaller_stash(dtype):
         for ga, gb_ in zip(f16[2], f16_ref[2]):
             for k in ga:
                 assert np.array_equal(ga[k], gb_[k]), k
+
+
+def test_stage_calls_can_be_captured_in_a_hip_graph():
+    """The stage calls only enqueue kernels (and device-to-device copies) on the given stream and
+    allocate nothing, so a forward + backward can be captured once and replayed.  Every replay --
+    with the program's own eager work and synchronisations in between, and new inputs copied into
+    the captured buffers -- must give the bits of the eager call.  The gradient buffer is cleared
+    inside the graph by a fill kernel (not a memset node)."""
+    shape = W[1].with_(name="bf16_graph", n_layers=2, hidden=256, n_heads=4, head_dim=64, ffn=512,
+                       seq=128, batch=2, bias_std=0.02, ln_jitter=0.1)
+    print(f"[case] hip graph {shape}", flush=True)
+    params, xs, dys = _inputs(shape, n_mb=3)
+    bufs = B.StageBuffers(shape)
+    bufs.load_params(params)
+    p = bufs.params()
+    x_s, dy_s, y_s, dx_s = (bufs.act() for _ in range(4))       # the captured call's buffers
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                              # warm-up outside capture
+        B.gpt_stage_fwd_bwd(p, x_s, dy_s, bufs.stash[0], y_s, dx_s, bufs.dparams)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        bufs.dparams.zero_()
+        B.gpt_stage_fwd_bwd(p, x_s, dy_s, bufs.stash[0], y_s, dx_s, bufs.dparams)
+    for m in range(3):
+        x_d, dy_d = B.to_device(xs[m], shape.dtype), B.to_device(dys[m], shape.dtype)
+        # eager reference on separate buffers (also the "program's own work" between replays)
+        ref = gpu_run(shape, params, [xs[m]], [dys[m]])
+        torch.cuda.synchronize()
+        x_s.copy_(x_d)
+        dy_s.copy_(dy_d)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(B.to_host(y_s), ref[0][0]) and np.array_equal(B.to_host(dx_s), ref[1][0]), m
+        for ga, gb in zip(bufs.read_grads(), ref[2]):
+            for k in ga:
+                assert np.array_equal(ga[k], gb[k]), (m, k)
