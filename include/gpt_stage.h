@@ -103,7 +103,7 @@ typedef struct {
                         activations, amplified by the softmax, shows in the gradients.
                         Needs p->prepared (built by gpt_stage_prepare() with the SAME cfg: the
                         forward images then hold fp16) and hidden, attention width and ffn
-                        multiples of 128, head_dim 64 or 128.  Forward activations are bounded
+                        multiples of 128.  Forward activations are bounded
                         by LayerNorm and the softmax; values beyond fp16's range saturate. */
 } gpt_stage_cfg;
 

@@ -96,22 +96,26 @@ __device__ __forceinline__ void dma_floats(const float* __restrict__ src, int id
 }
 
 // A [64][D] bf16 tile in LDS: row r, 16-byte chunk c stored at
-// r*(2D) + ((c ^ swz16(r)) << 4) (the XOR only touches the low 3 bits of c).
+// r*(2D) + ((c ^ swz(r)) << 4), swz(r) = swz16(r) cut to the chunks a row has (the XOR only
+// touches the low 3 bits of c; a row of head dimension 32 has 4 chunks, so 2 bits there).
 // 64 rows starting at global row `row0` (clamped to < S) are copied by the NW waves
-// of the workgroup; each DMA instruction moves 1 KiB.
+// of the workgroup; each DMA instruction moves 1 KiB (a tile of fewer instructions than waves
+// is copied by the first waves only).
 template <int D, int NW>
 __device__ __forceinline__ void dma_tile(const bf16* __restrict__ src, size_t ld, int row0, int S,
                                          char* tile, int wave, int lane) {
   constexpr int ROWB = D * 2;              // bytes per row
   constexpr int CPR = ROWB / 16;           // chunks per row
-  constexpr int NI = BKV * ROWB / 1024 / NW;  // instructions per wave
-  static_assert(NI >= 1, "tile smaller than one DMA instruction per wave");
+  constexpr int NT = BKV * ROWB / 1024;        // instructions per tile
+  constexpr int NI = NT >= NW ? NT / NW : 1;   // instructions per (issuing) wave
+  static_assert(NT >= 1 && (NT >= NW ? NT % NW == 0 : true), "tile / wave count mismatch");
+  if (NT < NW && wave >= NT) return;
   const uint32_t lds_tile = lds_addr(tile);
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
     const int slot = (wave * NI + i) * 64 + lane;
     const int r = slot / CPR, pc = slot % CPR;
-    const int c = pc ^ swz16(r);
+    const int c = pc ^ (swz16(r) & (CPR - 1));
     int gr = row0 + r;
     gr = gr < S ? gr : S - 1;
     dma16(src, (uint32_t)(((size_t)gr * ld + c * 8) * 2), lds_tile + (wave * NI + i) * 1024);
@@ -120,8 +124,10 @@ __device__ __forceinline__ void dma_tile(const bf16* __restrict__ src, size_t ld
 // A transposed-image tile (D*128 contiguous bytes) global -> LDS, flat.
 template <int D, int NW>
 __device__ __forceinline__ void dma_image(const bf16* __restrict__ tile_src, char* tile, int wave, int lane) {
-  constexpr int NI = D * 128 / 1024 / NW;
-  static_assert(NI >= 1, "tile smaller than one DMA instruction per wave");
+  constexpr int NT = D * 128 / 1024;
+  constexpr int NI = NT >= NW ? NT / NW : 1;
+  static_assert(NT >= 1 && (NT >= NW ? NT % NW == 0 : true), "tile / wave count mismatch");
+  if (NT < NW && wave >= NT) return;
   const uint32_t lds_tile = lds_addr(tile);
 #pragma unroll
   for (int i = 0; i < NI; ++i)
@@ -188,7 +194,7 @@ __device__ __forceinline__ int image_frag_off(int ql, int h) { return ql * 128 +
 // Natural-tile fragment (A operand, 32 rows x 16 d): byte offset for row block 0 and
 // k-step 0; row block rb adds rb*32*ROWB, k-step kk XORs kk<<5.
 template <int D> __device__ __forceinline__ int natural_frag_off(int ql, int h) {
-  return ql * (D * 2) + ((h ^ swz16(ql)) << 4);
+  return ql * (D * 2) + ((h ^ (swz16(ql) & (D / 8 - 1))) << 4);
 }
 __device__ __forceinline__ bf16x8 lds_frag(const char* p) { return *reinterpret_cast<const bf16x8*>(p); }
 
@@ -367,13 +373,23 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16* __restrict_
     const int n = gid % a;
     const size_t row = gid / a;  // b*S + i
     const size_t off = row * (size_t)a * D + (size_t)n * D + sub * PER;
+    if constexpr (PER >= 4) {
 #pragma unroll
-    for (int e = 0; e < PER; e += 4) {
-      const bf16x4 o = *reinterpret_cast<const bf16x4*>(out + off + e);
-      const bf16x4 g = *reinterpret_cast<const bf16x4*>(dout + off + e);
+      for (int e = 0; e < PER; e += 4) {
+        const bf16x4 o = *reinterpret_cast<const bf16x4*>(out + off + e);
+        const bf16x4 g = *reinterpret_cast<const bf16x4*>(dout + off + e);
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
-        acc = fmaf(O16 ? (float)__builtin_bit_cast(f16x4, o)[k] : (float)o[k], (float)g[k], acc);
+        for (int k = 0; k < 4; ++k)
+          acc = fmaf(O16 ? (float)__builtin_bit_cast(f16x4, o)[k] : (float)o[k], (float)g[k], acc);
+      }
+    } else {   // head dimension 32: two elements per lane
+      typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+      typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+      const bf16x2 o = *reinterpret_cast<const bf16x2*>(out + off);
+      const bf16x2 g = *reinterpret_cast<const bf16x2*>(dout + off);
+#pragma unroll
+      for (int k = 0; k < 2; ++k)
+        acc = fmaf(O16 ? (float)__builtin_bit_cast(f16x2, o)[k] : (float)o[k], (float)g[k], acc);
     }
   }
 #pragma unroll
@@ -724,7 +740,7 @@ void launch_timage(const TImageArgs& t, int B, int S, int a, hipStream_t st) {
 // The kernels address a tile row with a 32-bit byte offset from the (batch, head) base and
 // count (batch, row, head) triples in an int.
 bool attention_mfma_supported(int B, int S, int a, int d) {
-  return (d == 64 || d == 128) && B >= 1 && S >= 1 && a >= 1 && (size_t)S * 3 * a * d < (1ull << 31) &&
+  return (d == 32 || d == 64 || d == 128) && B >= 1 && S >= 1 && a >= 1 && (size_t)S * 3 * a * d < (1ull << 31) &&
          (size_t)B * S * a < (1ull << 27);
 }
 
@@ -751,10 +767,14 @@ hipError_t attention_fwd_mfma(int B, int S, int a, int d, const void* qkv, void*
     launch_timage<128>(t, B, S, a, st);
     if (f16) hipLaunchKernelGGL((attn_fwd_mfma_kernel<128, true>), g, blk, 0, st, q, vimg, (bf16*)out, lse, S, a);
     else hipLaunchKernelGGL((attn_fwd_mfma_kernel<128, false>), g, blk, 0, st, q, vimg, (bf16*)out, lse, S, a);
-  } else {
+  } else if (d == 64) {
     launch_timage<64>(t, B, S, a, st);
     if (f16) hipLaunchKernelGGL((attn_fwd_mfma_kernel<64, true>), g, blk, 0, st, q, vimg, (bf16*)out, lse, S, a);
     else hipLaunchKernelGGL((attn_fwd_mfma_kernel<64, false>), g, blk, 0, st, q, vimg, (bf16*)out, lse, S, a);
+  } else {
+    launch_timage<32>(t, B, S, a, st);
+    if (f16) hipLaunchKernelGGL((attn_fwd_mfma_kernel<32, true>), g, blk, 0, st, q, vimg, (bf16*)out, lse, S, a);
+    else hipLaunchKernelGGL((attn_fwd_mfma_kernel<32, false>), g, blk, 0, st, q, vimg, (bf16*)out, lse, S, a);
   }
   return hipGetLastError();
 }
@@ -794,9 +814,12 @@ hipError_t attention_bwd_mfma(int B, int S, int a, int d, const void* qkv, const
   if (d == 128) {
     if (q16) launch_bwd<128, true>(gd, gw, t, B, S, a, total, q, q16, o, g, qimg, kimg, doimg, lse, delta, dq, st);
     else launch_bwd<128, false>(gd, gw, t, B, S, a, total, q, q, o, g, qimg, kimg, doimg, lse, delta, dq, st);
-  } else {
+  } else if (d == 64) {
     if (q16) launch_bwd<64, true>(gd, gw, t, B, S, a, total, q, q16, o, g, qimg, kimg, doimg, lse, delta, dq, st);
     else launch_bwd<64, false>(gd, gw, t, B, S, a, total, q, q, o, g, qimg, kimg, doimg, lse, delta, dq, st);
+  } else {
+    if (q16) launch_bwd<32, true>(gd, gw, t, B, S, a, total, q, q16, o, g, qimg, kimg, doimg, lse, delta, dq, st);
+    else launch_bwd<32, false>(gd, gw, t, B, S, a, total, q, q, o, g, qimg, kimg, doimg, lse, delta, dq, st);
   }
   return hipGetLastError();
 }

@@ -84,10 +84,10 @@ hipError_t attention_bwd_simple(int dtype, int B, int S, int a, int d, const voi
                                 const void* out, const float* lse, const void* dout, void* dqkv,
                                 float* delta, hipStream_t st);
 
-// bf16 MFMA attention (head_dim 64 or 128).  scratch: device memory of
+// bf16 MFMA attention (head_dim 32, 64 or 128).  scratch: device memory of
 // attention_mfma_scratch_bytes(B, S, a, d, phase) bytes (phase 0 forward: the transposed
 // image of V; phase 1 backward: delta and the transposed images of Q, K and dO).
-bool attention_mfma_supported(int B, int S, int a, int d);   // head_dim 64/128 and index ranges
+bool attention_mfma_supported(int B, int S, int a, int d);   // head_dim 32/64/128 and index ranges
 size_t attention_mfma_scratch_bytes(int B, int S, int a, int d, int phase);
 // f16: qkv and out are fp16 (forward activations kept in fp16); lse is fp32 either way.
 hipError_t attention_fwd_mfma(int B, int S, int a, int d, const void* qkv, void* out, float* lse,

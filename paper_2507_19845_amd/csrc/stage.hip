@@ -272,7 +272,7 @@ hipError_t gemm(int dtype, int form, int M, int N, int K, const void* A, const v
   return gemm_simple(dtype, form, M, N, K, A, B, C, ep, st);
 }
 
-// Attention: MFMA kernels for bf16 with head_dim 64/128, the plain FMA kernels otherwise.
+// Attention: MFMA kernels for bf16 (head_dim 32, 64, 128), the plain FMA kernels for fp32.
 // scratch: attention_scratch_bytes(.., phase) bytes of device memory.
 bool attention_uses_mfma(int dtype, int B, int S, int a, int d) {
   return dtype == GPTS_BF16 && attention_mfma_supported(B, S, a, d);
@@ -709,7 +709,7 @@ int gpt_stage_validate(const gpt_stage_cfg* c) {
     if (c->hidden % 128 || P % 128 || c->ffn % 128)
       return fail(GPTS_ESHAPE, "fwd_fp16 needs hidden, attention width and ffn to be multiples of 128");
     if (!attention_mfma_supported(c->batch, c->seq, c->n_heads, c->head_dim))
-      return fail(GPTS_ESHAPE, "fwd_fp16 needs head_dim 64 or 128 and seq*3*width < 2^31");
+      return fail(GPTS_ESHAPE, "fwd_fp16 needs seq*3*width < 2^31 (32-bit offsets of the attention kernels)");
     if (!gemm_fwd_f16_supported(Ti, 3 * Pi, c->hidden) || !gemm_fwd_f16_supported(Ti, c->hidden, Pi) ||
         !gemm_fwd_f16_supported(Ti, c->ffn, c->hidden) || !gemm_fwd_f16_supported(Ti, c->hidden, c->ffn))
       return fail(GPTS_ESHAPE, "fwd_fp16: a forward product exceeds the 32-bit operand offsets of the kernels");

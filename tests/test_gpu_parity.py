@@ -44,10 +44,15 @@ SMALL = [
                seq=320, batch=1, bias_std=0.02, ln_jitter=0.1),
     W[1].with_(name="bf16_erf", n_layers=1, hidden=256, n_heads=4, head_dim=64, ffn=512, seq=64,
                batch=1, gelu="erf", bias_std=0.02),
+    # bf16 heads of dimension 32 (matrix-core attention with 4-chunk tile rows)
+    W[1].with_(name="bf16_d32", n_layers=2, hidden=256, n_heads=6, head_dim=32, ffn=512, seq=320,
+               batch=1, bias_std=0.02, ln_jitter=0.1),
     # fp16 forward activations (cfg.fwd_fp16): ragged token count against the 256-row tiles,
     # attention width != hidden, both head dimensions, both GeLU forms
     W[1].with_(name="bf16_fwd16_d128", n_layers=2, hidden=512, n_heads=3, head_dim=128, ffn=640,
                seq=320, batch=1, bias_std=0.02, ln_jitter=0.1, fwd_fp16=True),
+    W[1].with_(name="bf16_fwd16_d32", n_layers=1, hidden=256, n_heads=4, head_dim=32, ffn=512,
+               seq=200 + 56, batch=1, bias_std=0.02, ln_jitter=0.1, fwd_fp16=True),
     W[1].with_(name="bf16_fwd16_d64_erf", n_layers=2, hidden=384, n_heads=4, head_dim=64, ffn=896,
                seq=192, batch=2, gelu="erf", bias_std=0.02, ln_jitter=0.1, fwd_fp16=True),
 ]
@@ -538,7 +543,7 @@ def test_op_colsum(dtype, M, N):
 @pytest.mark.parametrize("dtype,Bn,S,a,d", [("fp32", 2, 64, 4, 32), ("fp32", 1, 97, 2, 64), ("bf16", 2, 256, 3, 64),
                                             ("bf16", 1, 384, 2, 128), ("bf16", 1, 1, 2, 64), ("fp32", 1, 130, 1, 128),
                                             ("bf16", 2, 1000, 2, 128), ("bf16", 1, 777, 3, 64), ("bf16", 1, 2048, 1, 128),
-                                            ("bf16", 3, 50, 2, 32)])
+                                            ("bf16", 3, 50, 2, 32), ("bf16", 2, 700, 3, 32)])
 def test_op_attention(dtype, Bn, S, a, d):
     print(f"[case] attention {dtype} B={Bn} S={S} a={a} d={d}", flush=True)
     dt = B.GPTS_BF16 if dtype == "bf16" else B.GPTS_FP32
