@@ -21,9 +21,13 @@
  *
  * General rules (all entry points)
  *  - Every pointer named "device" is GPU memory owned by the caller; the library
- *    allocates no device memory, keeps no mutable global state and frees nothing.
+ *    allocates no device memory and frees nothing.  Its only state is the calling
+ *    thread's last error text, the host objects the caller creates (tracers,
+ *    coordinators) and the fixed scratch array of gpt_stage_op_colsum_noalloc.
  *  - Every call only enqueues kernels on `stream` (a hipStream_t passed as
- *    void*; NULL = the default stream) and returns; it never synchronises.
+ *    void*; NULL = the default stream) and returns; it never synchronises
+ *    (exceptions, documented where they are declared: gpt_stage_trace_collect and
+ *    gpt_dpp_run_ready block the calling host thread).
  *  - Device pointers must be 16-byte aligned.
  *  - Return value: GPTS_OK (0) or a negative gpts_status; nothing is launched
  *    when validation fails.  No exceptions cross this boundary.
